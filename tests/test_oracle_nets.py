@@ -1,0 +1,74 @@
+"""Pins for the oracle's layer-chained forwards (CPU only): the MLP against numpy integer
+matmuls, the ResNet-shaped network against torch.nn.functional.conv2d in float64."""
+import numpy as np
+import torch
+
+import workloads as wl
+from oracle import nets
+from test_oracle_bmm import np_unpack_pm1
+from test_oracle_bconv import unpack4
+
+
+def test_mlp_vs_numpy(orc):
+    params = wl.mlp_params()
+    imgs = wl.mlp_images(8)
+    scores, hidden = nets.mlp_forward(imgs, params, keep=True)
+    assert scores.shape == (8, 10) and scores.dtype == np.int32
+    x = np.where(imgs.astype(np.int64) >= 127, 1, -1)
+    for l in range(3):
+        v = x @ np_unpack_pm1(params["W"][l], params["K"][l]).T
+        x = np.where(v >= params["thr"][l][None, :], 1, -1)
+        assert (np_unpack_pm1(hidden[l], x.shape[1]) == x).all()
+        assert (hidden[l][:, wl.nwords(x.shape[1]):] == 0).all()
+    ref = x @ np_unpack_pm1(params["W"][3], params["K"][3]).T
+    assert (scores == ref).all()
+    assert (np.abs(scores) <= 1024).all() and (scores % 2 == 0).all()
+
+
+def _torch_bconv(x_pm1, f_words, C, stride, pad):
+    xt = torch.from_numpy(x_pm1.astype(np.float64)).permute(0, 3, 1, 2)
+    ft = torch.from_numpy(unpack4(f_words, C).astype(np.float64)).permute(0, 3, 1, 2)
+    xt = torch.nn.functional.pad(xt, (pad, pad, pad, pad), value=-1.0)
+    return torch.nn.functional.conv2d(xt, ft, stride=stride).permute(0, 2, 3, 1).numpy().astype(np.int64)
+
+
+def test_resnet_small_vs_torch(orc):
+    # same block structure as the benchmark network, small channel counts and a 32x32 input
+    blocks = ((64, 64, 1), (64, 96, 2), (96, 96, 1), (96, 128, 2))
+    p = wl.resnet18_params(blocks=blocks, classes=13, config=95)
+    x = wl.resnet18_input(2, hw=32, config=95)
+    tr = nets.resnet18_forward(x, p, keep=True)
+    # independent chain
+    stem = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2),
+                                      torch.from_numpy(p["stem_w"]).double().permute(0, 3, 1, 2),
+                                      stride=4, padding=3).permute(0, 2, 3, 1).numpy()
+    np.testing.assert_allclose(tr["stem_f32"], stem, rtol=1e-6, atol=1e-7)
+    assert np.abs(stem).min() > 1e-6          # no stem value sits on the threshold in this case
+    a = np.where(stem >= 0, 1, -1).astype(np.int64)
+    assert (unpack4(tr["x0"], 64) == a).all()
+    R = a.copy()
+    for b, (cin, cout, st) in enumerate(blocks):
+        blk = p["blocks"][b]
+        v1 = _torch_bconv(a, blk["W1"], cin, st, 1)
+        h = np.where(v1 >= blk["thr1"], 1, -1)
+        v2 = _torch_bconv(h, blk["W2"], cout, 1, 1)
+        sc = _torch_bconv(a, blk["Wd"], cin, st, 0) if "Wd" in blk else R
+        S = v2 + sc
+        assert (tr["S%d" % b] == S).all()
+        a = np.where(S >= blk["thr2"], 1, -1)
+        assert (unpack4(tr["y%d" % b], cout) == a).all()
+        R = S
+    pooled = a.sum(axis=(1, 2))
+    assert (tr["pooled"] == pooled).all()
+    hw = a.shape[1] * a.shape[2]
+    logits = (pooled.astype(np.float64) / hw) @ p["fc_w"].astype(np.float64).T
+    np.testing.assert_allclose(tr["logits"], logits, rtol=1e-5, atol=1e-6)
+    # tier 1 gives the same bits and sums
+    tr1 = nets.resnet18_forward(x, p, keep=True, tier=1)
+    for key in tr:
+        assert np.array_equal(tr[key], tr1[key]), key
+    # injected stem bits are honoured
+    x0 = tr["x0"].copy()
+    x0[0, 0, 0, 0] ^= np.uint32(1)
+    tr2 = nets.resnet18_forward(x, p, stem_bits=x0, keep=True)
+    assert not np.array_equal(tr2["S0"], tr["S0"])

@@ -1,0 +1,156 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module only draws random numbers and lays them out; it contains none of the method's
+arithmetic (no dot products, no thresholds applied, no convolution).  It is the one module the
+GPU tests, ``bench.py`` and the CPU oracle's tests all share.
+
+Recipe: ``numpy.random.Generator(PCG64(seed))`` with ``seed = 20061657 + 1000 * config + index``
+(index numbers the tensors of a configuration in order of use).  A packed +1/-1 operand is drawn
+directly as uniform 32-bit words, which makes every bit an independent fair coin (p = 0.5); the
+bits beyond the logical width are cleared, because the packed layout requires pad bits to be 0.
+Thresholds are ``integers(lo, hi + 1)`` as int32.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SEED_BASE = 20061657
+
+
+def seed_for(config: int, index: int) -> int:
+    return SEED_BASE + 1000 * config + index
+
+
+def _rng(config: int, index: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed_for(config, index)))
+
+
+def nwords(nbits: int) -> int:
+    return (int(nbits) + 31) // 32
+
+
+def round_up(v: int, m: int) -> int:
+    return (int(v) + m - 1) // m * m
+
+
+def random_bits(rng: np.random.Generator, shape_rows, nbits: int, ldw: int | None = None) -> np.ndarray:
+    """Uniform random packed bits: array of shape (*shape_rows, ldw) uint32, pad bits zero."""
+    if isinstance(shape_rows, int):
+        shape_rows = (shape_rows,)
+    kw = nwords(nbits)
+    ldw = kw if ldw is None else ldw
+    assert ldw >= kw
+    w = rng.integers(0, 1 << 32, size=tuple(shape_rows) + (ldw,), dtype=np.uint64).astype(np.uint32)
+    if nbits % 32:
+        w[..., kw - 1] &= np.uint32((1 << (nbits % 32)) - 1)
+    w[..., kw:] = 0
+    return w
+
+
+def random_thresholds(rng: np.random.Generator, n: int, lo: int, hi: int) -> np.ndarray:
+    return rng.integers(lo, hi + 1, size=n, dtype=np.int64).astype(np.int32)
+
+
+# ------------------------------------------------------------------------------------ config 1, 2
+def bmm_case(config: int, M: int, N: int, K: int, thr_div: int = 8, index0: int = 0) -> dict:
+    """A [M][ldw], B [N][ldw] random bits; tau [N] uniform integers in [-K/thr_div, K/thr_div]."""
+    ldw = round_up(nwords(K), 4)
+    A = random_bits(_rng(config, index0 + 0), M, K, ldw)
+    B = random_bits(_rng(config, index0 + 1), N, K, ldw)
+    t = K // thr_div
+    tau = random_thresholds(_rng(config, index0 + 2), N, -t, t)
+    return {"A": A, "B": B, "tau": tau, "M": M, "N": N, "K": K, "ldw": ldw}
+
+
+CFG2_SQUARES = (2048, 4096, 8192, 16384)
+CFG2_FC = ((8, 4096, 4096), (128, 4096, 4096), (1024, 4096, 4096))   # (M, N, K)
+
+
+def cfg1() -> dict:
+    return bmm_case(1, 1024, 1024, 1024)
+
+
+def cfg2_shapes():
+    """(name, M, N, K, index0) for every shape of the BMM sweep."""
+    out = []
+    for i, n in enumerate(CFG2_SQUARES):
+        out.append(("sq%d" % n, n, n, n, 10 * i))
+    for i, (m, n, k) in enumerate(CFG2_FC):
+        out.append(("fc%d" % m, m, n, k, 100 + 10 * i))
+    return out
+
+
+def cfg2_case(name: str) -> dict:
+    for nm, M, N, K, idx in cfg2_shapes():
+        if nm == name:
+            return bmm_case(2, M, N, K, index0=idx)
+    raise KeyError(name)
+
+
+# ------------------------------------------------------------------------------------ config 3
+MLP_DIMS = (784, 1024, 1024, 1024, 10)
+
+
+def mlp_params(dims=MLP_DIMS, config: int = 3) -> dict:
+    """Random +1/-1 weights W_l [N_l][ldw_l] and per-neuron thresholds uniform in [-32, 32]."""
+    W, K, thr = [], [], []
+    for l in range(len(dims) - 1):
+        k, n = dims[l], dims[l + 1]
+        W.append(random_bits(_rng(config, 10 + l), n, k, round_up(nwords(k), 4)))
+        K.append(k)
+        if l < len(dims) - 2:
+            thr.append(random_thresholds(_rng(config, 20 + l), n, -32, 32))
+    return {"W": W, "K": K, "thr": thr, "in_thr": 127, "dims": tuple(dims)}
+
+
+def mlp_images(batch: int, pixels: int = 784, config: int = 3) -> np.ndarray:
+    """Synthetic 8-bit images, every pixel uniform in [0, 255]; stands in for MNIST digits."""
+    return _rng(config, 0).integers(0, 256, size=(batch, pixels), dtype=np.int64).astype(np.uint8)
+
+
+# ------------------------------------------------------------------------------------ config 4
+def bconv_case(config: int, N: int, H: int, W: int, C: int, O: int, k: int, stride: int, pad: int,
+               thr_range: int = 64, index0: int = 0) -> dict:
+    x = random_bits(_rng(config, index0 + 0), (N, H, W), C)
+    f = random_bits(_rng(config, index0 + 1), (O, k, k), C)
+    tau = random_thresholds(_rng(config, index0 + 2), O, -thr_range, thr_range)
+    return {"x": x, "filt": f, "tau": tau, "N": N, "H": H, "W": W, "C": C, "O": O, "k": k,
+            "stride": stride, "pad": pad}
+
+
+def cfg4a(N: int = 128) -> dict:
+    return bconv_case(4, N, 56, 56, 128, 128, 3, 1, 1, index0=0)
+
+
+def cfg4b(N: int = 128) -> dict:
+    return bconv_case(4, N, 56, 56, 64, 128, 3, 2, 1, index0=10)
+
+
+# ------------------------------------------------------------------------------------ config 5
+RESNET18_BLOCKS = ((64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1),
+                   (128, 256, 2), (256, 256, 1), (256, 512, 2), (512, 512, 1))
+
+
+def resnet18_params(blocks=RESNET18_BLOCKS, classes: int = 1000, config: int = 5) -> dict:
+    """fp32 stem [64][7][7][3] and FC [classes][512] ~ N(0, 0.02); binarized 3x3 / 1x1 weights
+    random bits; thresholds uniform integers in [-64, 64]; stem threshold 0."""
+    c0 = blocks[0][0]
+    p = {"stem_w": _rng(config, 1).normal(0.0, 0.02, size=(c0, 7, 7, 3)).astype(np.float32),
+         "stem_thr": np.zeros(c0, dtype=np.float32),
+         "blocks": []}
+    for b, (cin, cout, stride) in enumerate(blocks):
+        blk = {"cin": cin, "cout": cout, "stride": stride,
+               "W1": random_bits(_rng(config, 100 + 10 * b + 0), (cout, 3, 3), cin),
+               "thr1": random_thresholds(_rng(config, 100 + 10 * b + 1), cout, -64, 64),
+               "W2": random_bits(_rng(config, 100 + 10 * b + 2), (cout, 3, 3), cout),
+               "thr2": random_thresholds(_rng(config, 100 + 10 * b + 3), cout, -64, 64)}
+        if stride != 1 or cin != cout:
+            blk["Wd"] = random_bits(_rng(config, 100 + 10 * b + 4), (cout, 1, 1), cin)
+        p["blocks"].append(blk)
+    p["fc_w"] = _rng(config, 2).normal(0.0, 0.02, size=(classes, blocks[-1][1])).astype(np.float32)
+    return p
+
+
+def resnet18_input(batch: int, hw: int = 224, config: int = 5) -> np.ndarray:
+    """Synthetic images [batch][hw][hw][3] fp32 uniform in [-1, 1]; stands in for ImageNet crops."""
+    return _rng(config, 0).uniform(-1.0, 1.0, size=(batch, hw, hw, 3)).astype(np.float32)
