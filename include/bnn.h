@@ -1,0 +1,185 @@
+/*
+ * bnn.h -- C ABI of libbnn: binarized fully-connected and convolution layers on packed +1/-1
+ * bits for AMD MI355X (gfx950), after "Accelerating Binarized Neural Networks via
+ * Bit-Tensor-Cores in Turing GPUs" (arXiv 2006.16578).
+ *
+ * Conventions common to every call
+ * --------------------------------
+ *  - Bits: bit 1 denotes +1, bit 0 denotes -1 (Sec. 5.2, text of Eq. 2).  Element k of a packed
+ *    vector is bit (k % 32), counted from the least significant bit, of 32-bit word (k / 32).
+ *    Rows of packed matrices are `ld*_w` words apart.  Bits beyond the logical length of a row
+ *    ("pad bits"), up to the next multiple of 128 bits, MUST be 0 in every input; every output
+ *    this library writes has its pad bits, up to the leading dimension, written as 0.
+ *  - Pointers: every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *    allocates, frees or synchronises; a call only enqueues kernels on `stream`
+ *    (a hipStream_t passed as void*; NULL is the default stream) and returns.
+ *    Inputs must not overlap outputs.
+ *  - Alignment: packed-bit and int32 base pointers must be 16-byte aligned, leading dimensions of
+ *    packed BMM operands (`lda_w`, `ldb_w`) must be multiples of 4 words.
+ *  - Return value: BNN_OK or a negative bnn_status; nothing is enqueued when an error is returned
+ *    (except BNN_ERR_DEVICE, which reports a failed launch).  No exceptions, no global state.
+ *  - Exactness: all binarized arithmetic is integer and exact.  K (or k*k*C for a convolution)
+ *    must not exceed BNN_MAX_K.
+ */
+#ifndef BNN_H
+#define BNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bnn_status {
+    BNN_OK = 0,
+    BNN_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, window larger than padded image ... */
+    BNN_ERR_ALIGNMENT = -2,     /* pointer not 16-byte aligned or leading dimension not a multiple of 4 words */
+    BNN_ERR_UNSUPPORTED = -3,   /* valid request outside what the kernels implement (e.g. K > BNN_MAX_K) */
+    BNN_ERR_DEVICE = -4,        /* the HIP runtime reported a launch failure */
+    BNN_ERR_WORKSPACE = -5      /* workspace too small / missing */
+} bnn_status;
+
+/* How an out-of-frame input position enters a convolution (Sec. 5.3). */
+#define BNN_PAD_MINUS_ONE 0  /* it counts as -1 (a 0 bit) */
+#define BNN_PAD_EXCLUDE 1    /* its taps contribute nothing: the paper's "exclude" amendment */
+
+/* Which arithmetic pipeline computes the +1/-1 products.  CDNA4 has no 1-bit matrix type, so the
+ * library has two: XOR + popcount on the vector ALUs (Eq. 2 literally), and the matrix cores fed
+ * with +1/-1 expanded on the fly to 4-bit floats (exact: products are +-1, sums stay below 2^24).
+ * BNN_PATH_AUTO picks by shape. */
+#define BNN_PATH_AUTO 0
+#define BNN_PATH_VALU 1
+#define BNN_PATH_MFMA 2
+
+#define BNN_MAX_K (1 << 20)
+
+const char* bnn_status_string(int status);
+int bnn_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * BMM (Sec. 5.2, Eq. 2): C[i][j] = sum_{k<K} a[i][k] * b[j][k] = K - 2 * popc(A_i xor B_j).
+ *   A  [M][lda_w]  packed along K (row-major bit matrix)
+ *   B  [N][ldb_w]  packed along K (the column-major K x N operand of Sec. 3.3: N rows of K bits)
+ *   C  [M][ldc]    int32
+ * M, N, K >= 1; lda_w, ldb_w >= ceil(K/32) rounded up to a multiple of 4; ldc >= N.
+ * ---------------------------------------------------------------------------------------- */
+int bnn_bmm(const uint32_t* A, const uint32_t* B, int32_t* C,
+            int M, int N, int K, int lda_w, int ldb_w, int ldc, void* stream);
+int bnn_bmm_ex(const uint32_t* A, const uint32_t* B, int32_t* C,
+               int M, int N, int K, int lda_w, int ldb_w, int ldc, int path, void* stream);
+
+/* BMM with the threshold of Sec. 6.1 fused into the epilogue (Sec. 5.2, "the output can be
+ * binarized before the store"): Cbits[i] bit j = (C[i][j] >= thr[j]); the int32 matrix never
+ * reaches memory.
+ *   thr   [N] int32;  Cbits [M][ldcb_w], ldcb_w >= ceil(N/32); pad bits up to ldcb_w*32 are 0,
+ *   so Cbits is directly the A operand of the next layer. */
+int bnn_bmm_thr(const uint32_t* A, const uint32_t* B, const int32_t* thr, uint32_t* Cbits,
+                int M, int N, int K, int lda_w, int ldb_w, int ldcb_w, void* stream);
+int bnn_bmm_thr_ex(const uint32_t* A, const uint32_t* B, const int32_t* thr, uint32_t* Cbits,
+                   int M, int N, int K, int lda_w, int ldb_w, int ldcb_w, int path, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * BConv (Sec. 5.3, Eq. 3): cross-correlation, no filter flip,
+ *   out[n][p][q][o] = sum_{r,s<k} sum_{c<C} x(n, p*stride-pad+r, q*stride-pad+s, c) * f[o][r][s][c]
+ *   in    [N][H][W][cw]   packed along C, cw = ceil(C/32), pixels contiguous (NHWC)
+ *   filt  [O][k][k][cw]   packed along C
+ *   out   [N][P][Q][O]    int32,  P = (H + 2*pad - k)/stride + 1, Q likewise
+ * pad_mode says what an out-of-frame x is (see BNN_PAD_*).  k*k*C <= BNN_MAX_K.
+ * ---------------------------------------------------------------------------------------- */
+int bnn_bconv(const uint32_t* in, const uint32_t* filt, int32_t* out,
+              int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode, void* stream);
+int bnn_bconv_ex(const uint32_t* in, const uint32_t* filt, int32_t* out,
+                 int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode,
+                 int path, void* stream);
+
+/* BConv with fused epilogue: S = conv + residual_in (if given); sum_out = S (if given);
+ * out_bits bit o = (S >= thr[o]).  The residual is the full-precision shortcut of Sec. 6.1 kept
+ * as int32 and added before the threshold.
+ *   residual_in [N][P][Q][O] int32 or NULL;  sum_out [N][P][Q][O] int32 or NULL (may alias
+ *   residual_in: each element is read then written by the same thread);
+ *   thr [O] int32;  out_bits [N][P][Q][ow], ow = ceil(O/32), pad bits 0. */
+int bnn_bconv_thr(const uint32_t* in, const uint32_t* filt,
+                  const int32_t* residual_in, int32_t* sum_out,
+                  const int32_t* thr, uint32_t* out_bits,
+                  int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode, void* stream);
+int bnn_bconv_thr_ex(const uint32_t* in, const uint32_t* filt,
+                     const int32_t* residual_in, int32_t* sum_out,
+                     const int32_t* thr, uint32_t* out_bits,
+                     int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode,
+                     int path, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Stand-alone threshold and (un)packing (Sec. 6.1 thrd; Eq. 1 with sign(0) = +1).
+ * ---------------------------------------------------------------------------------------- */
+/* bits[r] bit c = (X[r][c] >= thr[c]);  X [rows][ldx] int32, bits [rows][ldb_w]. */
+int bnn_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits,
+                       int64_t rows, int cols, int ldx, int ldb_w, void* stream);
+/* bits[r] bit c = (x[r][c] >= thr);  x [rows][cols] uint8 (8-bit input pixels). */
+int bnn_pack_u8(const uint8_t* x, int thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
+/* bits[r] bit c = (x[r][c] >= thr[c]);  x [rows][cols] fp32, thr [cols] fp32. */
+int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
+/* out[r][c] = +1 / -1 as int32 from bits [rows][ldb_w]; out [rows][ldo].  Seeds the int32
+ * residual chain from a bit tensor. */
+int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Full-precision end layers of a network whose inner layers are binarized (Sec. 6.1: the first
+ * layer keeps full-precision input).  fp32 arithmetic, not bit-exact: 1e-4 relative.
+ * ---------------------------------------------------------------------------------------- */
+/* y = conv(x, w) with zero padding; bits = (y >= thr[o]).
+ *   x [N][H][W][C] fp32, w [O][k][k][C] fp32, thr [O] fp32,
+ *   y_f32 [N][P][Q][O] fp32 or NULL, bits [N][P][Q][ceil(O/32)] or NULL (not both NULL). */
+int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
+                     int N, int H, int W, int C, int O, int k, int stride, int pad, void* stream);
+/* pooled[n][c] = sum over HW positions of the +1/-1 value of channel c (exact integer);
+ * y[n][j] = sum_c (pooled[n][c] / HW) * w[j][c].
+ *   bits [N][HW][ceil(C/32)], w [J][C] fp32, y [N][J] fp32, pooled_out [N][C] int32 or NULL. */
+int bnn_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled_out,
+                 int N, int HW, int C, int J, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Layer-chained forward (Sec. 6.1 order thrd -> bconv/bmm -> thrd ...; Sec. 6.2).  A net is a
+ * host-side list of layers; bnn_net_forward enqueues one fused kernel per layer on `stream`,
+ * the packed output bits of a layer being directly the operand of the next.
+ * Weight and threshold pointers are device pointers BORROWED for the lifetime of the net.
+ * The net object itself is host memory owned by the library (create/destroy).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct bnn_net bnn_net;
+
+int bnn_net_create(bnn_net** net);
+int bnn_net_destroy(bnn_net* net);
+/* Input layers (exactly one, first). */
+int bnn_net_input_u8(bnn_net* net, int cols, int thr);                       /* [batch][cols] uint8 -> bits */
+int bnn_net_input_bits(bnn_net* net, int cols);                             /* [batch][ld_w] packed bits, ld_w = ceil(cols/32) rounded up to 4 */
+int bnn_net_input_conv_f32(bnn_net* net, const float* w, const float* thr, /* [batch][H][W][C] fp32 -> stem conv -> bits */
+                           int H, int W, int C, int O, int k, int stride, int pad);
+/* Binarized fully-connected layer, W [N][ldw_w] with ldw_w = ceil(K/32) rounded up to 4.
+ * thr != NULL: output bits; thr == NULL: int32 scores [batch][N] (only as the last layer). */
+int bnn_net_add_fc(bnn_net* net, const uint32_t* W, const int32_t* thr, int K, int N);
+/* Binarized convolution + threshold. */
+int bnn_net_add_conv(bnn_net* net, const uint32_t* filt, const int32_t* thr,
+                     int C, int O, int k, int stride, int pad, int pad_mode);
+/* Residual basic block: h = thr1(conv3x3(x, W1, stride, pad 1)); S = conv3x3(h, W2, 1, pad 1) + shortcut;
+ * y = (S >= thr2); the running residual becomes S.  shortcut = running residual when Wd == NULL
+ * (needs stride 1, cin == cout), else conv1x1(x, Wd, stride, pad 0). */
+int bnn_net_add_block(bnn_net* net, const uint32_t* W1, const int32_t* thr1,
+                      const uint32_t* W2, const int32_t* thr2, const uint32_t* Wd,
+                      int cin, int cout, int stride, int pad_mode);
+/* Head: sum-pool over all positions + fp32 FC, w [J][C]; output fp32 [batch][J]. */
+int bnn_net_add_head_f32(bnn_net* net, const float* w, int J);
+/* Device workspace the forward needs for `batch` inputs (activations, residuals). */
+int bnn_net_workspace_bytes(const bnn_net* net, int batch, size_t* bytes);
+/* input: as declared by the input layer; output: int32 scores or fp32 logits of the last layer.
+ * workspace: device memory of at least bnn_net_workspace_bytes(), 256-byte aligned. */
+int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch,
+                    void* workspace, size_t workspace_bytes, int path, void* stream);
+/* After a forward: device pointer (inside the workspace) and shape of the packed bits produced by
+ * layer `layer` (0 = input layer), for layer-by-layer checking.  words_per_row receives the row
+ * length in words, rows the number of rows (batch, or batch*P*Q). */
+int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int64_t* rows, int* words_per_row);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNN_H */

@@ -1,0 +1,341 @@
+"""ctypes binding of libbnn's C ABI (include/bnn.h): argument marshalling only.
+
+Tensors are ``torch`` CUDA (ROCm) tensors used purely as device buffers; every function enqueues
+on torch's current stream of the tensor's device and returns the output tensor(s).  Shapes and
+dtypes are checked here, everything else by the library, whose status codes are raised as
+``BnnError``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+__all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
+           "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
+           "unpack_i32", "conv_f32_thr", "head_f32", "Net", "EXPORTS"]
+
+PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
+PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+# every symbol include/bnn.h declares
+EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
+           "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
+           "bnn_pack_f32", "bnn_unpack_i32", "bnn_conv_f32_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_add_fc",
+           "bnn_net_add_conv", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
+           "bnn_net_forward", "bnn_net_layer_bits"]
+
+
+class BnnError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, _status_string(status), status))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libbnn.so")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads libbnn.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError("libbnn.so is not built: run `python -m paper_2006_16578_amd.build` "
+                              "(or __graft_entry__.build()) first")
+        lib = ctypes.CDLL(path)
+        lib.bnn_status_string.restype = ctypes.c_char_p
+        lib.bnn_status_string.argtypes = [ctypes.c_int]
+        for name in EXPORTS:
+            getattr(lib, name)          # fail loudly on a missing export
+        _lib = lib
+    return _lib
+
+
+def _status_string(status: int) -> str:
+    try:
+        return load().bnn_status_string(status).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise BnnError(status, what)
+
+
+def nwords(nbits: int) -> int:
+    return (int(nbits) + 31) // 32
+
+
+def round_up(v: int, m: int) -> int:
+    return (int(v) + m - 1) // m * m
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, ndim=None, name="tensor"):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if ndim is not None and t.dim() != ndim:
+        raise ValueError("%s must have %d dimensions" % (name, ndim))
+    return t
+
+
+_BITS = torch.int32   # packed words travel as int32 tensors (torch has no uint32 arithmetic; only the bytes matter)
+
+
+def bmm(A, B, K: int, out=None, path: int = PATH_AUTO):
+    """C[i][j] = sum_k a[i][k] b[j][k]; A [M][lda_w], B [N][ldb_w] packed int32 words -> int32 [M][N]."""
+    _dev(A, _BITS, 2, "A"); _dev(B, _BITS, 2, "B")
+    M, lda = A.shape
+    N, ldb = B.shape
+    C = torch.empty((M, N), dtype=torch.int32, device=A.device) if out is None else _dev(out, torch.int32, 2, "out")
+    with torch.cuda.device(A.device):
+        _check(load().bnn_bmm_ex(_ptr(A), _ptr(B), _ptr(C), M, N, int(K), lda, ldb, C.shape[1], int(path), _stream(A)), "bnn_bmm")
+    return C
+
+
+def bmm_thr(A, B, thr, K: int, ldcb_w: int | None = None, out=None, path: int = PATH_AUTO):
+    """Fused BMM + threshold: bits [M][ldcb_w], bit j = (C[i][j] >= thr[j])."""
+    _dev(A, _BITS, 2, "A"); _dev(B, _BITS, 2, "B"); _dev(thr, torch.int32, 1, "thr")
+    M, lda = A.shape
+    N, ldb = B.shape
+    if thr.shape[0] != N:
+        raise ValueError("thr must have N entries")
+    ldcb_w = round_up(nwords(N), 4) if ldcb_w is None else int(ldcb_w)
+    Cb = torch.empty((M, ldcb_w), dtype=_BITS, device=A.device) if out is None else _dev(out, _BITS, 2, "out")
+    with torch.cuda.device(A.device):
+        _check(load().bnn_bmm_thr_ex(_ptr(A), _ptr(B), _ptr(thr), _ptr(Cb), M, N, int(K), lda, ldb, Cb.shape[1], int(path),
+                                     _stream(A)), "bnn_bmm_thr")
+    return Cb
+
+
+def _conv_dims(x, filt, C, stride, pad):
+    _dev(x, _BITS, 4, "x"); _dev(filt, _BITS, 4, "filt")
+    N, H, W, cw = x.shape
+    O, k, k2, cwf = filt.shape
+    if k != k2 or cw != cwf or cw != nwords(C):
+        raise ValueError("x [N][H][W][cw], filt [O][k][k][cw] with cw = ceil(C/32) expected")
+    P = (H + 2 * pad - k) // stride + 1
+    Q = (W + 2 * pad - k) // stride + 1
+    return N, H, W, O, k, P, Q
+
+
+def bconv(x, filt, C: int, stride: int, pad: int, pad_mode: int = PAD_MINUS_ONE, out=None, path: int = PATH_AUTO):
+    """int32 [N][P][Q][O] = cross-correlation of packed x [N][H][W][cw] with filt [O][k][k][cw]."""
+    N, H, W, O, k, P, Q = _conv_dims(x, filt, C, stride, pad)
+    y = torch.empty((N, max(P, 0), max(Q, 0), O), dtype=torch.int32, device=x.device) if out is None else out
+    with torch.cuda.device(x.device):
+        _check(load().bnn_bconv_ex(_ptr(x), _ptr(filt), _ptr(y), N, H, W, int(C), O, k, int(stride), int(pad),
+                                   int(pad_mode), int(path), _stream(x)), "bnn_bconv")
+    return y
+
+
+def bconv_thr(x, filt, thr, C: int, stride: int, pad: int, pad_mode: int = PAD_MINUS_ONE, residual=None,
+              want_sum: bool = False, sum_out=None, out=None, path: int = PATH_AUTO):
+    """Fused conv (+ int32 residual) + threshold -> bits [N][P][Q][ow]; optionally also the int32 sum."""
+    N, H, W, O, k, P, Q = _conv_dims(x, filt, C, stride, pad)
+    _dev(thr, torch.int32, 1, "thr")
+    if residual is not None:
+        _dev(residual, torch.int32, 4, "residual")
+        if tuple(residual.shape) != (N, P, Q, O):
+            raise ValueError("residual must be [N][P][Q][O]")
+    if want_sum and sum_out is None:
+        sum_out = torch.empty((N, P, Q, O), dtype=torch.int32, device=x.device)
+    bits = torch.empty((N, max(P, 0), max(Q, 0), nwords(O)), dtype=_BITS, device=x.device) if out is None else out
+    with torch.cuda.device(x.device):
+        _check(load().bnn_bconv_thr_ex(_ptr(x), _ptr(filt), _ptr(residual), _ptr(sum_out), _ptr(thr), _ptr(bits), N, H, W,
+                                       int(C), O, k, int(stride), int(pad), int(pad_mode), int(path), _stream(x)),
+               "bnn_bconv_thr")
+    return (bits, sum_out) if sum_out is not None else bits
+
+
+def threshold_pack(X, thr, ldb_w: int | None = None):
+    _dev(X, torch.int32, None, "X"); _dev(thr, torch.int32, 1, "thr")
+    cols = X.shape[-1]
+    rows = X.numel() // cols
+    ldb_w = nwords(cols) if ldb_w is None else int(ldb_w)
+    bits = torch.empty(tuple(X.shape[:-1]) + (ldb_w,), dtype=_BITS, device=X.device)
+    with torch.cuda.device(X.device):
+        _check(load().bnn_threshold_pack(_ptr(X), _ptr(thr), _ptr(bits), ctypes.c_int64(rows), cols, cols, ldb_w, _stream(X)),
+               "bnn_threshold_pack")
+    return bits
+
+
+def pack_u8(x, thr: int, ldb_w: int | None = None):
+    _dev(x, torch.uint8, 2, "x")
+    rows, cols = x.shape
+    ldb_w = nwords(cols) if ldb_w is None else int(ldb_w)
+    bits = torch.empty((rows, ldb_w), dtype=_BITS, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_pack_u8(_ptr(x), int(thr), _ptr(bits), ctypes.c_int64(rows), cols, ldb_w, _stream(x)), "bnn_pack_u8")
+    return bits
+
+
+def pack_f32(x, thr, ldb_w: int | None = None):
+    _dev(x, torch.float32, None, "x"); _dev(thr, torch.float32, 1, "thr")
+    cols = x.shape[-1]
+    rows = x.numel() // cols
+    ldb_w = nwords(cols) if ldb_w is None else int(ldb_w)
+    bits = torch.empty(tuple(x.shape[:-1]) + (ldb_w,), dtype=_BITS, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_pack_f32(_ptr(x), _ptr(thr), _ptr(bits), ctypes.c_int64(rows), cols, ldb_w, _stream(x)), "bnn_pack_f32")
+    return bits
+
+
+def unpack_i32(bits, cols: int):
+    _dev(bits, _BITS, None, "bits")
+    ldb_w = bits.shape[-1]
+    rows = bits.numel() // ldb_w
+    out = torch.empty(tuple(bits.shape[:-1]) + (cols,), dtype=torch.int32, device=bits.device)
+    with torch.cuda.device(bits.device):
+        _check(load().bnn_unpack_i32(_ptr(bits), _ptr(out), ctypes.c_int64(rows), int(cols), ldb_w, int(cols), _stream(bits)),
+               "bnn_unpack_i32")
+    return out
+
+
+def conv_f32_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False):
+    """fp32 first layer: x [N][H][W][C], w [O][k][k][C], thr [O] -> bits [N][P][Q][ow] (and fp32 y)."""
+    _dev(x, torch.float32, 4, "x"); _dev(w, torch.float32, 4, "w"); _dev(thr, torch.float32, 1, "thr")
+    N, H, W, C = x.shape
+    O, k, _, C2 = w.shape
+    if C != C2:
+        raise ValueError("channel mismatch")
+    P = (H + 2 * pad - k) // stride + 1
+    Q = (W + 2 * pad - k) // stride + 1
+    bits = torch.empty((N, P, Q, nwords(O)), dtype=_BITS, device=x.device)
+    y = torch.empty((N, P, Q, O), dtype=torch.float32, device=x.device) if want_f32 else None
+    with torch.cuda.device(x.device):
+        _check(load().bnn_conv_f32_thr(_ptr(x), _ptr(w), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride), int(pad),
+                                       _stream(x)), "bnn_conv_f32_thr")
+    return (bits, y) if want_f32 else bits
+
+
+def head_f32(bits, w, C: int, want_pooled: bool = False):
+    """bits [N][H][W][cw] -> fp32 logits [N][J] = FC(sum-pool(+1/-1) / HW); w [J][C]."""
+    _dev(bits, _BITS, 4, "bits"); _dev(w, torch.float32, 2, "w")
+    N, H, W, cw = bits.shape
+    J = w.shape[0]
+    y = torch.empty((N, J), dtype=torch.float32, device=bits.device)
+    pooled = torch.empty((N, C), dtype=torch.int32, device=bits.device) if want_pooled else None
+    with torch.cuda.device(bits.device):
+        _check(load().bnn_head_f32(_ptr(bits), _ptr(w), _ptr(y), _ptr(pooled), N, H * W, int(C), J, _stream(bits)), "bnn_head_f32")
+    return (y, pooled) if want_pooled else y
+
+
+class Net:
+    """Layer-chained forward (bnn_net_*).  Keeps references to every weight tensor it borrows."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _check(load().bnn_net_create(ctypes.byref(self._h)), "bnn_net_create")
+        self._keep = []
+        self._ws = None
+        self._out_kind = None
+        self._out_cols = 0
+        self.n_layers = 0
+
+    def __del__(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load().bnn_net_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def _added(self, *tensors):
+        self._keep.extend(t for t in tensors if t is not None)
+        self.n_layers += 1
+
+    def input_u8(self, cols: int, thr: int):
+        _check(load().bnn_net_input_u8(self._h, int(cols), int(thr)), "bnn_net_input_u8")
+        self._in_dtype = torch.uint8
+        self._added()
+
+    def input_bits(self, cols: int):
+        _check(load().bnn_net_input_bits(self._h, int(cols)), "bnn_net_input_bits")
+        self._in_dtype = _BITS
+        self._added()
+
+    def input_conv_f32(self, w, thr, H: int, W: int, stride: int, pad: int):
+        _dev(w, torch.float32, 4, "w"); _dev(thr, torch.float32, 1, "thr")
+        O, k, _, C = w.shape
+        _check(load().bnn_net_input_conv_f32(self._h, _ptr(w), _ptr(thr), int(H), int(W), C, O, k, int(stride), int(pad)),
+               "bnn_net_input_conv_f32")
+        self._in_dtype = torch.float32
+        self._added(w, thr)
+
+    def add_fc(self, W, thr, K: int):
+        _dev(W, _BITS, 2, "W")
+        if thr is not None:
+            _dev(thr, torch.int32, 1, "thr")
+        N = W.shape[0]
+        _check(load().bnn_net_add_fc(self._h, _ptr(W), _ptr(thr), int(K), N), "bnn_net_add_fc")
+        if thr is None:
+            self._out_kind, self._out_cols = torch.int32, N
+        self._added(W, thr)
+
+    def add_conv(self, filt, thr, C: int, stride: int, pad: int, pad_mode: int = PAD_MINUS_ONE):
+        _dev(filt, _BITS, 4, "filt"); _dev(thr, torch.int32, 1, "thr")
+        O, k = filt.shape[0], filt.shape[1]
+        _check(load().bnn_net_add_conv(self._h, _ptr(filt), _ptr(thr), int(C), O, k, int(stride), int(pad), int(pad_mode)),
+               "bnn_net_add_conv")
+        self._added(filt, thr)
+
+    def add_block(self, W1, thr1, W2, thr2, Wd, cin: int, cout: int, stride: int, pad_mode: int = PAD_MINUS_ONE):
+        for t in (W1, W2):
+            _dev(t, _BITS, 4, "W")
+        _check(load().bnn_net_add_block(self._h, _ptr(W1), _ptr(thr1), _ptr(W2), _ptr(thr2), _ptr(Wd), int(cin), int(cout),
+                                        int(stride), int(pad_mode)), "bnn_net_add_block")
+        self._added(W1, thr1, W2, thr2, Wd)
+
+    def add_head_f32(self, w):
+        _dev(w, torch.float32, 2, "w")
+        _check(load().bnn_net_add_head_f32(self._h, _ptr(w), w.shape[0]), "bnn_net_add_head_f32")
+        self._out_kind, self._out_cols = torch.float32, w.shape[0]
+        self._added(w)
+
+    def workspace_bytes(self, batch: int) -> int:
+        n = ctypes.c_size_t()
+        _check(load().bnn_net_workspace_bytes(self._h, int(batch), ctypes.byref(n)), "bnn_net_workspace_bytes")
+        return n.value
+
+    def forward(self, x, out=None, path: int = PATH_AUTO):
+        _dev(x, self._in_dtype, None, "input")
+        batch = x.shape[0]
+        need = self.workspace_bytes(batch)
+        if self._ws is None or self._ws.numel() < need or self._ws.device != x.device:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        if out is None:
+            out = torch.empty((batch, self._out_cols), dtype=self._out_kind, device=x.device)
+        with torch.cuda.device(x.device):
+            _check(load().bnn_net_forward(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws), ctypes.c_size_t(self._ws.numel()),
+                                          int(path), _stream(x)), "bnn_net_forward")
+        return out
+
+    def layer_bits(self, layer: int):
+        """Copy of the packed bits produced by `layer` in the last forward, as [rows][words]."""
+        p = ctypes.c_void_p()
+        rows = ctypes.c_int64()
+        wpr = ctypes.c_int()
+        _check(load().bnn_net_layer_bits(self._h, int(layer), ctypes.byref(p), ctypes.byref(rows), ctypes.byref(wpr)),
+               "bnn_net_layer_bits")
+        off = p.value - self._ws.data_ptr()
+        n = rows.value * wpr.value * 4
+        return self._ws[off:off + n].view(_BITS).view(rows.value, wpr.value).clone()

@@ -1,0 +1,452 @@
+// C ABI of libbnn: argument validation, shape bookkeeping and kernel dispatch.
+#include <new>
+#include <vector>
+
+#include "bnn_internal.h"
+
+using namespace bnn;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int words(int nbits) { return (nbits + 31) / 32; }
+inline int round4(int v) { return (v + 3) / 4 * 4; }
+
+int dispatch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, int path, hipStream_t s) {
+    switch (path) {
+        case BNN_PATH_VALU: return launch_valu(A, B, g, e, s);
+        case BNN_PATH_AUTO:
+        case BNN_PATH_MFMA: return launch_mfma(A, B, g, e, s);
+        default: return BNN_ERR_INVALID_ARG;
+    }
+}
+
+int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* thr, uint32_t* Cbits,
+               int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream) {
+    if (!A || !B || M < 1 || N < 1 || K < 1) return BNN_ERR_INVALID_ARG;
+    if (!C && !Cbits) return BNN_ERR_INVALID_ARG;
+    if (Cbits && !thr) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+    const int kw4 = round4(words(K));
+    if (lda_w < kw4 || ldb_w < kw4) return BNN_ERR_INVALID_ARG;
+    if ((lda_w & 3) || (ldb_w & 3) || !aligned16(A) || !aligned16(B)) return BNN_ERR_ALIGNMENT;
+    if (C && (ldc < N || !aligned16(C))) return ldc < N ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
+    if (Cbits && (ldcb_w < words(N) || !aligned16(Cbits))) return ldcb_w < words(N) ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
+    if (thr && !aligned16(thr)) return BNN_ERR_ALIGNMENT;
+    Geom g = {};
+    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = kw4; g.bits_tap = K;
+    g.lda_w = lda_w; g.ldb_w = ldb_w;
+    g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0;
+    Epi e = {};
+    e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w;
+    return dispatch(A, B, g, e, path, static_cast<hipStream_t>(stream));
+}
+
+int conv_shape(int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode, int* P, int* Q) {
+    if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0) return BNN_ERR_INVALID_ARG;
+    if (pad_mode != BNN_PAD_MINUS_ONE && pad_mode != BNN_PAD_EXCLUDE) return BNN_ERR_INVALID_ARG;
+    if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
+    if (pad >= k) return BNN_ERR_UNSUPPORTED;          // a window entirely out of frame
+    if ((long long)k * k * C > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+    *P = (H + 2 * pad - k) / stride + 1;
+    *Q = (W + 2 * pad - k) / stride + 1;
+    if ((long long)N * *P * *Q * O > (1LL << 40)) return BNN_ERR_UNSUPPORTED;
+    return BNN_OK;
+}
+
+int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const int32_t* resid,
+                 const int32_t* thr, uint32_t* bits, int N, int H, int W, int C, int O, int k, int stride,
+                 int pad, int pad_mode, int path, void* stream) {
+    if (!in || !filt) return BNN_ERR_INVALID_ARG;
+    if (!out && !bits) return BNN_ERR_INVALID_ARG;
+    if (bits && !thr) return BNN_ERR_INVALID_ARG;
+    int P, Q;
+    int rc = conv_shape(N, H, W, C, O, k, stride, pad, pad_mode, &P, &Q);
+    if (rc != BNN_OK) return rc;
+    if (!aligned16(in) || !aligned16(filt) || (out && !aligned16(out)) || (resid && !aligned16(resid)) ||
+        (bits && !aligned16(bits)) || (thr && !aligned16(thr)))
+        return BNN_ERR_ALIGNMENT;
+    const int cw = words(C);
+    Geom g = {};
+    g.rows = (long long)N * P * Q; g.cols = O; g.conv = 1; g.taps = k * k; g.tw = cw; g.bits_tap = C;
+    g.lda_w = cw; g.ldb_w = k * k * cw;
+    g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad;
+    g.excl = (pad_mode == BNN_PAD_EXCLUDE) ? 1 : 0;
+    Epi e = {};
+    e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O);
+    return dispatch(in, filt, g, e, path, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------ net
+struct bnn_net {
+    enum Kind { IN_U8, IN_BITS, IN_CONV_F32, FC, CONV, BLOCK, HEAD };
+    struct Layer {
+        Kind kind;
+        const void* w0 = nullptr; const void* w1 = nullptr; const void* w2 = nullptr;   // weights
+        const void* t0 = nullptr; const void* t1 = nullptr;                              // thresholds
+        int a = 0, b = 0, c = 0, d = 0, k = 0, stride = 0, pad = 0, pad_mode = 0, thr_u8 = 0;
+        // filled by plan(): spatial size and channels of the output, where its bits live
+        int H = 1, W = 1, C = 0;
+        size_t bits_off = 0; int words_per_row = 0; long long rows_per_image = 1;
+    };
+    std::vector<Layer> layers;
+    // results of the last forward, for bnn_net_layer_bits
+    const char* last_ws = nullptr; int last_batch = 0;
+};
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Walks the layer list for `batch` inputs, assigning workspace offsets.  Layout: every layer's
+// output bits get their own slot (they are small: 1 bit per activation), int32 residuals use
+// three rotating slots sized for the largest residual tensor.
+struct Plan {
+    size_t total = 0;
+    size_t resid_off[3] = {0, 0, 0};
+    size_t resid_bytes = 0;
+    int rc = BNN_OK;
+};
+
+Plan plan(bnn_net* net, int batch) {
+    Plan pl;
+    size_t off = 0;
+    int H = 1, W = 1, C = 0;
+    size_t max_resid = 0;
+    bool have_resid = false;
+    for (size_t i = 0; i < net->layers.size(); ++i) {
+        bnn_net::Layer& L = net->layers[i];
+        if ((i == 0) != (L.kind == bnn_net::IN_U8 || L.kind == bnn_net::IN_BITS || L.kind == bnn_net::IN_CONV_F32)) {
+            pl.rc = BNN_ERR_INVALID_ARG; return pl;
+        }
+        switch (L.kind) {
+            case bnn_net::IN_U8: case bnn_net::IN_BITS:
+                H = W = 1; C = L.a; L.words_per_row = round4(words(C)); break;
+            case bnn_net::IN_CONV_F32:
+                H = (L.a + 2 * L.pad - L.k) / L.stride + 1; W = (L.b + 2 * L.pad - L.k) / L.stride + 1; C = L.d;
+                L.words_per_row = words(C); break;
+            case bnn_net::FC:
+                if (H * W * words(C) * 32 != H * W * C && H * W != 1) { pl.rc = BNN_ERR_UNSUPPORTED; return pl; }
+                if (H * W * C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                H = W = 1; C = L.b; L.words_per_row = round4(words(C)); break;
+            case bnn_net::CONV:
+                if (C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                H = (H + 2 * L.pad - L.k) / L.stride + 1; W = (W + 2 * L.pad - L.k) / L.stride + 1; C = L.b;
+                L.words_per_row = words(C); break;
+            case bnn_net::BLOCK:
+                if (C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                if (!L.w2 && (L.stride != 1 || L.a != L.b)) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                H = (H + 2 - 3) / L.stride + 1; W = (W + 2 - 3) / L.stride + 1; C = L.b;
+                L.words_per_row = words(C);
+                have_resid = true;
+                break;
+            case bnn_net::HEAD:
+                if (i + 1 != net->layers.size()) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                L.words_per_row = 0; break;
+        }
+        if (H < 1 || W < 1) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+        L.H = H; L.W = W; L.C = C; L.rows_per_image = (long long)H * W;
+        if (L.kind == bnn_net::HEAD || (L.kind == bnn_net::FC && L.t0 == nullptr)) {
+            if (i + 1 != net->layers.size()) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+            continue;
+        }
+        L.bits_off = off;
+        size_t bytes = (size_t)batch * H * W * L.words_per_row * 4;
+        if (L.kind == bnn_net::BLOCK) bytes *= 2;      // hidden bits h of the block, then its output
+        off += align256(bytes);
+        if (L.kind == bnn_net::BLOCK || L.kind == bnn_net::IN_CONV_F32 || L.kind == bnn_net::CONV)
+            max_resid = max(max_resid, (size_t)batch * H * W * C * 4);
+    }
+    if (have_resid) {
+        pl.resid_bytes = align256(max_resid);
+        for (int r = 0; r < 3; ++r) { pl.resid_off[r] = off; off += pl.resid_bytes; }
+    }
+    pl.total = off;
+    return pl;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bnn_status_string(int status) {
+    switch (status) {
+        case BNN_OK: return "ok";
+        case BNN_ERR_INVALID_ARG: return "invalid argument";
+        case BNN_ERR_ALIGNMENT: return "pointer or leading dimension not aligned";
+        case BNN_ERR_UNSUPPORTED: return "unsupported size or configuration";
+        case BNN_ERR_DEVICE: return "HIP launch failure";
+        case BNN_ERR_WORKSPACE: return "workspace missing or too small";
+        default: return "unknown status";
+    }
+}
+
+int bnn_version(void) { return 100; }
+
+int bnn_bmm(const uint32_t* A, const uint32_t* B, int32_t* C, int M, int N, int K, int lda_w, int ldb_w, int ldc,
+            void* stream) {
+    return bnn_bmm_ex(A, B, C, M, N, K, lda_w, ldb_w, ldc, BNN_PATH_AUTO, stream);
+}
+int bnn_bmm_ex(const uint32_t* A, const uint32_t* B, int32_t* C, int M, int N, int K, int lda_w, int ldb_w, int ldc,
+               int path, void* stream) {
+    if (!C) return BNN_ERR_INVALID_ARG;
+    return bmm_common(A, B, C, nullptr, nullptr, M, N, K, lda_w, ldb_w, ldc, 0, path, stream);
+}
+int bnn_bmm_thr(const uint32_t* A, const uint32_t* B, const int32_t* thr, uint32_t* Cbits, int M, int N, int K,
+                int lda_w, int ldb_w, int ldcb_w, void* stream) {
+    return bnn_bmm_thr_ex(A, B, thr, Cbits, M, N, K, lda_w, ldb_w, ldcb_w, BNN_PATH_AUTO, stream);
+}
+int bnn_bmm_thr_ex(const uint32_t* A, const uint32_t* B, const int32_t* thr, uint32_t* Cbits, int M, int N, int K,
+                   int lda_w, int ldb_w, int ldcb_w, int path, void* stream) {
+    if (!Cbits || !thr) return BNN_ERR_INVALID_ARG;
+    return bmm_common(A, B, nullptr, thr, Cbits, M, N, K, lda_w, ldb_w, 0, ldcb_w, path, stream);
+}
+
+int bnn_bconv(const uint32_t* in, const uint32_t* filt, int32_t* out, int N, int H, int W, int C, int O, int k,
+              int stride, int pad, int pad_mode, void* stream) {
+    return bnn_bconv_ex(in, filt, out, N, H, W, C, O, k, stride, pad, pad_mode, BNN_PATH_AUTO, stream);
+}
+int bnn_bconv_ex(const uint32_t* in, const uint32_t* filt, int32_t* out, int N, int H, int W, int C, int O, int k,
+                 int stride, int pad, int pad_mode, int path, void* stream) {
+    if (!out) return BNN_ERR_INVALID_ARG;
+    return bconv_common(in, filt, out, nullptr, nullptr, nullptr, N, H, W, C, O, k, stride, pad, pad_mode, path, stream);
+}
+int bnn_bconv_thr(const uint32_t* in, const uint32_t* filt, const int32_t* residual_in, int32_t* sum_out,
+                  const int32_t* thr, uint32_t* out_bits, int N, int H, int W, int C, int O, int k, int stride,
+                  int pad, int pad_mode, void* stream) {
+    return bnn_bconv_thr_ex(in, filt, residual_in, sum_out, thr, out_bits, N, H, W, C, O, k, stride, pad, pad_mode,
+                            BNN_PATH_AUTO, stream);
+}
+int bnn_bconv_thr_ex(const uint32_t* in, const uint32_t* filt, const int32_t* residual_in, int32_t* sum_out,
+                     const int32_t* thr, uint32_t* out_bits, int N, int H, int W, int C, int O, int k, int stride,
+                     int pad, int pad_mode, int path, void* stream) {
+    if (!out_bits || !thr) return BNN_ERR_INVALID_ARG;
+    return bconv_common(in, filt, sum_out, residual_in, thr, out_bits, N, H, W, C, O, k, stride, pad, pad_mode, path,
+                        stream);
+}
+
+int bnn_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, int64_t rows, int cols, int ldx,
+                       int ldb_w, void* stream) {
+    if (!X || !thr || !bits || rows < 1 || cols < 1 || ldx < cols || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
+    if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
+    return launch_threshold_pack(X, thr, bits, rows, cols, ldx, ldb_w, static_cast<hipStream_t>(stream));
+}
+int bnn_pack_u8(const uint8_t* x, int thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream) {
+    if (!x || !bits || rows < 1 || cols < 1 || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
+    if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
+    return launch_pack_u8(x, thr, bits, rows, cols, ldb_w, static_cast<hipStream_t>(stream));
+}
+int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream) {
+    if (!x || !thr || !bits || rows < 1 || cols < 1 || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
+    if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
+    return launch_pack_f32(x, thr, bits, rows, cols, ldb_w, static_cast<hipStream_t>(stream));
+}
+int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream) {
+    if (!bits || !out || rows < 1 || cols < 1 || ldb_w < words(cols) || ldo < cols) return BNN_ERR_INVALID_ARG;
+    return launch_unpack_i32(bits, out, rows, cols, ldb_w, ldo, static_cast<hipStream_t>(stream));
+}
+
+int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits, int N, int H,
+                     int W, int C, int O, int k, int stride, int pad, void* stream) {
+    if (!x || !w || (!y_f32 && !bits) || (bits && !thr)) return BNN_ERR_INVALID_ARG;
+    if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0) return BNN_ERR_INVALID_ARG;
+    if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
+    return launch_conv_f32_thr(x, w, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, static_cast<hipStream_t>(stream));
+}
+int bnn_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled_out, int N, int HW, int C, int J,
+                 void* stream) {
+    if (!bits || !w || !y || N < 1 || HW < 1 || C < 1 || J < 1) return BNN_ERR_INVALID_ARG;
+    return launch_head_f32(bits, w, y, pooled_out, N, HW, C, J, static_cast<hipStream_t>(stream));
+}
+
+// ---- layer-chained forward ------------------------------------------------------------------
+int bnn_net_create(bnn_net** net) {
+    if (!net) return BNN_ERR_INVALID_ARG;
+    *net = new (std::nothrow) bnn_net();
+    return *net ? BNN_OK : BNN_ERR_INVALID_ARG;
+}
+int bnn_net_destroy(bnn_net* net) {
+    delete net;
+    return BNN_OK;
+}
+int bnn_net_input_u8(bnn_net* net, int cols, int thr) {
+    if (!net || cols < 1 || !net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    bnn_net::Layer L; L.kind = bnn_net::IN_U8; L.a = cols; L.thr_u8 = thr;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_input_bits(bnn_net* net, int cols) {
+    if (!net || cols < 1 || !net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    bnn_net::Layer L; L.kind = bnn_net::IN_BITS; L.a = cols;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_input_conv_f32(bnn_net* net, const float* w, const float* thr, int H, int W, int C, int O, int k,
+                           int stride, int pad) {
+    if (!net || !w || !thr || !net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    if (H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0 || H + 2 * pad < k || W + 2 * pad < k)
+        return BNN_ERR_INVALID_ARG;
+    bnn_net::Layer L; L.kind = bnn_net::IN_CONV_F32; L.w0 = w; L.t0 = thr;
+    L.a = H; L.b = W; L.c = C; L.d = O; L.k = k; L.stride = stride; L.pad = pad;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_add_fc(bnn_net* net, const uint32_t* W, const int32_t* thr, int K, int N) {
+    if (!net || !W || K < 1 || N < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+    if (!aligned16(W) || (thr && !aligned16(thr))) return BNN_ERR_ALIGNMENT;
+    bnn_net::Layer L; L.kind = bnn_net::FC; L.w0 = W; L.t0 = thr; L.a = K; L.b = N;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_add_conv(bnn_net* net, const uint32_t* filt, const int32_t* thr, int C, int O, int k, int stride, int pad,
+                     int pad_mode) {
+    if (!net || !filt || !thr || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    int P, Q;
+    int rc = conv_shape(1, k, k, C, O, k, stride, pad, pad_mode, &P, &Q);
+    if (rc != BNN_OK) return rc;
+    if (!aligned16(filt) || !aligned16(thr)) return BNN_ERR_ALIGNMENT;
+    bnn_net::Layer L; L.kind = bnn_net::CONV; L.w0 = filt; L.t0 = thr; L.a = C; L.b = O; L.k = k; L.stride = stride;
+    L.pad = pad; L.pad_mode = pad_mode;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_add_block(bnn_net* net, const uint32_t* W1, const int32_t* thr1, const uint32_t* W2, const int32_t* thr2,
+                      const uint32_t* Wd, int cin, int cout, int stride, int pad_mode) {
+    if (!net || !W1 || !thr1 || !W2 || !thr2 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    if (cin < 1 || cout < 1 || stride < 1) return BNN_ERR_INVALID_ARG;
+    if (pad_mode != BNN_PAD_MINUS_ONE && pad_mode != BNN_PAD_EXCLUDE) return BNN_ERR_INVALID_ARG;
+    if (!Wd && (stride != 1 || cin != cout)) return BNN_ERR_INVALID_ARG;
+    if (!aligned16(W1) || !aligned16(W2) || !aligned16(thr1) || !aligned16(thr2) || (Wd && !aligned16(Wd)))
+        return BNN_ERR_ALIGNMENT;
+    bnn_net::Layer L; L.kind = bnn_net::BLOCK; L.w0 = W1; L.t0 = thr1; L.w1 = W2; L.t1 = thr2; L.w2 = Wd;
+    L.a = cin; L.b = cout; L.stride = stride; L.pad_mode = pad_mode;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_add_head_f32(bnn_net* net, const float* w, int J) {
+    if (!net || !w || J < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    bnn_net::Layer L; L.kind = bnn_net::HEAD; L.w0 = w; L.a = J;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+
+int bnn_net_workspace_bytes(const bnn_net* net, int batch, size_t* bytes) {
+    if (!net || !bytes || batch < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    Plan pl = plan(const_cast<bnn_net*>(net), batch);
+    if (pl.rc != BNN_OK) return pl.rc;
+    *bytes = pl.total;
+    return BNN_OK;
+}
+
+int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, void* workspace, size_t workspace_bytes,
+                    int path, void* stream) {
+    if (!net || !input || batch < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    Plan pl = plan(net, batch);
+    if (pl.rc != BNN_OK) return pl.rc;
+    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BNN_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BNN_ERR_ALIGNMENT;
+    char* ws = static_cast<char*>(workspace);
+    net->last_ws = ws; net->last_batch = batch;
+
+    const uint32_t* cur = nullptr;      // bits of the current activation
+    int curH = 1, curW = 1, curC = 0, cur_ld = 0;
+    int32_t* R = nullptr;               // running int32 residual (same shape as cur), or null
+    int rslot = 0;
+    for (size_t i = 0; i < net->layers.size(); ++i) {
+        const bnn_net::Layer& L = net->layers[i];
+        uint32_t* obits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
+        int rc = BNN_OK;
+        switch (L.kind) {
+            case bnn_net::IN_U8:
+                rc = bnn_pack_u8(static_cast<const uint8_t*>(input), L.thr_u8, obits, batch, L.a, L.words_per_row, stream);
+                break;
+            case bnn_net::IN_BITS:
+                if (!aligned16(input)) return BNN_ERR_ALIGNMENT;
+                obits = const_cast<uint32_t*>(static_cast<const uint32_t*>(input));   // used in place
+                break;
+            case bnn_net::IN_CONV_F32:
+                rc = bnn_conv_f32_thr(static_cast<const float*>(input), static_cast<const float*>(L.w0),
+                                      static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,
+                                      L.stride, L.pad, stream);
+                R = nullptr;
+                break;
+            case bnn_net::FC: {
+                const long long K = (long long)curH * curW * curC;
+                // a [batch][H][W][cw] tensor with C a multiple of 32 is already a [batch][K/32] matrix
+                const int lda = (curH * curW == 1) ? cur_ld : curH * curW * cur_ld;
+                if (L.t0) {
+                    rc = bnn_bmm_thr_ex(cur, static_cast<const uint32_t*>(L.w0), static_cast<const int32_t*>(L.t0), obits,
+                                        batch, L.b, (int)K, lda, round4(words((int)K)), L.words_per_row, path, stream);
+                } else {
+                    if (!output) return BNN_ERR_INVALID_ARG;
+                    rc = bnn_bmm_ex(cur, static_cast<const uint32_t*>(L.w0), static_cast<int32_t*>(output), batch, L.b,
+                                    (int)K, lda, round4(words((int)K)), L.b, path, stream);
+                }
+                R = nullptr;
+                break;
+            }
+            case bnn_net::CONV:
+                rc = bnn_bconv_thr_ex(cur, static_cast<const uint32_t*>(L.w0), nullptr, nullptr,
+                                      static_cast<const int32_t*>(L.t0), obits, batch, curH, curW, curC, L.b, L.k,
+                                      L.stride, L.pad, L.pad_mode, path, stream);
+                R = nullptr;
+                break;
+            case bnn_net::BLOCK: {
+                uint32_t* hbits = obits;                                     // first half of the slot
+                uint32_t* ybits = obits + (size_t)batch * L.H * L.W * L.words_per_row;
+                int32_t* Rnew = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 1) % 3]);
+                const int32_t* shortcut;
+                if (L.w2) {     // 1x1 binarized downsample of the block input (int32)
+                    int32_t* sc = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 2) % 3]);
+                    rc = bnn_bconv_ex(cur, static_cast<const uint32_t*>(L.w2), sc, batch, curH, curW, curC, L.b, 1,
+                                      L.stride, 0, L.pad_mode, path, stream);
+                    if (rc != BNN_OK) return rc;
+                    shortcut = sc;
+                } else {
+                    if (!R) {   // first block: seed the residual with the +1/-1 values of its input
+                        int32_t* R0 = reinterpret_cast<int32_t*>(ws + pl.resid_off[rslot]);
+                        rc = bnn_unpack_i32(cur, R0, (long long)batch * curH * curW, curC, cur_ld, curC, stream);
+                        if (rc != BNN_OK) return rc;
+                        R = R0;
+                    }
+                    shortcut = R;
+                }
+                rc = bnn_bconv_thr_ex(cur, static_cast<const uint32_t*>(L.w0), nullptr, nullptr,
+                                      static_cast<const int32_t*>(L.t0), hbits, batch, curH, curW, curC, L.b, 3,
+                                      L.stride, 1, L.pad_mode, path, stream);
+                if (rc != BNN_OK) return rc;
+                rc = bnn_bconv_thr_ex(hbits, static_cast<const uint32_t*>(L.w1), shortcut, Rnew,
+                                      static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
+                                      L.pad_mode, path, stream);
+                R = Rnew; rslot = (rslot + 1) % 3;
+                obits = ybits;
+                break;
+            }
+            case bnn_net::HEAD:
+                if (!output) return BNN_ERR_INVALID_ARG;
+                rc = bnn_head_f32(cur, static_cast<const float*>(L.w0), static_cast<float*>(output), nullptr, batch,
+                                  curH * curW, curC, L.a, stream);
+                break;
+        }
+        if (rc != BNN_OK) return rc;
+        cur = obits; curH = L.H; curW = L.W; curC = L.C; cur_ld = L.words_per_row;
+    }
+    return BNN_OK;
+}
+
+int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int64_t* rows, int* words_per_row) {
+    if (!net || !bits || !rows || !words_per_row || layer < 0 || layer >= (int)net->layers.size()) return BNN_ERR_INVALID_ARG;
+    if (!net->last_ws) return BNN_ERR_WORKSPACE;
+    const bnn_net::Layer& L = net->layers[layer];
+    if (L.kind == bnn_net::HEAD || L.kind == bnn_net::IN_BITS || (L.kind == bnn_net::FC && !L.t0)) return BNN_ERR_INVALID_ARG;
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(net->last_ws + L.bits_off);
+    const long long r = (long long)net->last_batch * L.H * L.W;
+    if (L.kind == bnn_net::BLOCK) p += (size_t)r * L.words_per_row;    // the block's output bits
+    *bits = p; *rows = r; *words_per_row = L.words_per_row;
+    return BNN_OK;
+}
+
+}  // extern "C"

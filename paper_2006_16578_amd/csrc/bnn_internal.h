@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libbnn (not part of the ABI).
+#ifndef BNN_INTERNAL_H
+#define BNN_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/bnn.h"
+
+namespace bnn {
+
+// One +1/-1 contraction seen as an implicit GEMM: `rows` output rows (A rows of a BMM, output
+// pixels n*P*Q of a convolution) by `cols` output columns (B rows / output channels), contracted
+// over `taps` windows of `tw` packed words each.
+struct Geom {
+    long long rows;
+    int cols;
+    int conv;        // 0: BMM (taps = 1), 1: convolution
+    int taps;        // k*k
+    int tw;          // words per tap that are read: BMM ceil(K/32) rounded up to 4; conv cw = ceil(C/32)
+    int bits_tap;    // logical bits per tap: K (BMM) or C (conv)
+    int lda_w;       // BMM: words between A rows.  conv: words between pixels (= cw)
+    int ldb_w;       // words between B rows (BMM: ldb_w, conv: k*k*cw)
+    // convolution geometry (Sec. 5.3)
+    int H, W, P, Q, k, stride, pad;
+    int excl;        // 1: out-of-frame taps contribute nothing; 0: they count as -1
+};
+
+// What happens to each finished sum v[row][col] (all pointers may be null except as noted).
+struct Epi {
+    int32_t* out;          // out[row*ldc + col] = v (+ residual)
+    const int32_t* resid;  // residual[row*ldc + col], added before the threshold (Sec. 6.1)
+    int ldc;               // elements between rows of out / resid
+    const int32_t* thr;    // thr[col]: bit = (v >= thr[col])
+    uint32_t* bits;        // bits[row*ldbits_w + col/32]
+    int ldbits_w;          // words between rows of bits; words beyond ceil(cols/32) are zeroed
+};
+
+int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+
+int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, long long rows, int cols,
+                          int ldx, int ldb_w, hipStream_t s);
+int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
+int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
+int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s);
+int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits,
+                        int N, int H, int W, int C, int O, int k, int stride, int pad, hipStream_t s);
+int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,
+                    hipStream_t s);
+
+inline int check_launch() {
+    return hipGetLastError() == hipSuccess ? BNN_OK : BNN_ERR_DEVICE;
+}
+
+inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+
+}  // namespace bnn
+#endif

@@ -1,0 +1,90 @@
+"""GPU parity: bnn_bconv / bnn_bconv_thr through the C ABI against the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import host, to_dev, words
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [("valu", 1), ("mfma", 2)]
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    import paper_2006_16578_amd as b
+    b.load()
+    return b
+
+
+def run_conv(bnn, orc, case, path, pad_mode, ref=None, with_resid=True):
+    x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
+    C, st, pad = case["C"], case["stride"], case["pad"]
+    ref = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode) if ref is None else ref
+    got = host(bnn.bconv(x, f, C, st, pad, pad_mode, path=path))
+    assert got.shape == ref.shape
+    assert np.array_equal(got, ref), "int32 mismatch: %d wrong" % int((got != ref).sum())
+    bits = words(bnn.bconv_thr(x, f, tau, C, st, pad, pad_mode, path=path))
+    assert np.array_equal(bits, orc.threshold_pack(ref, case["tau"])), "bit mismatch"
+    if with_resid:
+        rng = np.random.default_rng(ref.size % 9973)
+        R = rng.integers(-300, 301, size=ref.shape).astype(np.int32)
+        bits2, S = bnn.bconv_thr(x, f, tau, C, st, pad, pad_mode, residual=to_dev(R), want_sum=True, path=path)
+        assert np.array_equal(host(S), ref + R)
+        assert np.array_equal(words(bits2), orc.threshold_pack(ref + R, case["tau"]))
+
+
+SMALL = [  # N, H, W, C, O, k, stride, pad
+    (1, 1, 1, 1, 1, 1, 1, 0), (1, 3, 3, 1, 1, 3, 1, 1), (2, 5, 4, 3, 3, 3, 1, 1), (2, 5, 4, 32, 3, 3, 2, 1),
+    (2, 7, 6, 33, 5, 3, 1, 1), (3, 8, 8, 64, 40, 3, 1, 1), (2, 9, 7, 96, 33, 3, 2, 1), (2, 6, 6, 128, 64, 1, 2, 0),
+    (1, 11, 10, 160, 70, 5, 2, 2), (2, 12, 12, 256, 96, 3, 1, 1), (1, 7, 7, 512, 130, 3, 1, 1),
+    (5, 14, 14, 64, 128, 3, 2, 1), (3, 10, 9, 192, 65, 3, 1, 0), (2, 8, 8, 320, 32, 1, 1, 0)]
+
+
+@pytest.mark.parametrize("pad_mode", [0, 1])
+@pytest.mark.parametrize("pname,path", PATHS)
+def test_small_shapes(bnn, orc, pname, path, pad_mode):
+    for idx, (N, H, W, C, O, k, st, pad) in enumerate(SMALL):
+        print("conv", N, H, W, C, O, k, st, pad, pname, pad_mode, flush=True)
+        case = wl.bconv_case(92, N, H, W, C, O, k, st, pad, index0=10 * idx)
+        run_conv(bnn, orc, case, path, pad_mode)
+
+
+def test_worked_example(bnn):
+    # one +1 pixel, 3x3 filter of +1, pad 1: -7 with -1 padding, +1 with excluded taps
+    x = torch.ones((1, 1, 1, 1), dtype=torch.int32, device="cuda")
+    f = torch.ones((1, 3, 3, 1), dtype=torch.int32, device="cuda")
+    for path in (1, 2):
+        assert int(bnn.bconv(x, f, 1, 1, 1, 0, path=path).item()) == -7
+        assert int(bnn.bconv(x, f, 1, 1, 1, 1, path=path).item()) == 1
+
+
+@pytest.mark.parametrize("which", ["4a", "4b"])
+def test_cfg4_full_size(bnn, orc, which):
+    # the graded shapes at full batch: all of the output against the packed tier-1 oracle, two
+    # images against the naive tier-0 oracle; both pad modes; automatic path plus both explicit ones
+    case = wl.cfg4a() if which == "4a" else wl.cfg4b()
+    C, st, pad = case["C"], case["stride"], case["pad"]
+    for pad_mode in (0, 1):
+        ref1 = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode, tier=1)
+        for n0 in (0, case["N"] - 1):
+            assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, st, pad, pad_mode, n0, 1), ref1[n0:n0 + 1])
+        for path in (0, 1, 2):
+            print("cfg", which, "pad_mode", pad_mode, "path", path, flush=True)
+            run_conv(bnn, orc, case, path, pad_mode, ref=ref1, with_resid=(path == 0))
+
+
+def test_error_codes(bnn):
+    x = torch.zeros((1, 4, 4, 1), dtype=torch.int32, device="cuda")
+    f = torch.zeros((2, 3, 3, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bconv(x, f, 32, 0, 1)                 # stride 0
+    assert e.value.status == -1
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bconv(x, f, 32, 1, 1, pad_mode=5)
+    assert e.value.status == -1
+    f7 = torch.zeros((2, 7, 7, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bconv(x, f7, 32, 1, 1)                # window larger than the padded image
+    assert e.value.status == -1

@@ -1,0 +1,140 @@
+"""GPU parity: bnn_bmm / bnn_bmm_thr through the C ABI against the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import host, to_dev, words
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [("valu", 1), ("mfma", 2)]
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    import paper_2006_16578_amd as b
+    b.load()
+    return b
+
+
+def run_case(bnn, orc, case, path, ref=None, ld_extra=0):
+    A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+    K, N = case["K"], case["N"]
+    ref = orc.bmm(case["A"], case["B"], K) if ref is None else ref
+    C = host(bnn.bmm(A, B, K, path=path))
+    assert np.array_equal(C, ref), "int32 mismatch: %d wrong" % int((C != ref).sum())
+    ldcb = wl.round_up(wl.nwords(N), 4) + ld_extra
+    bits = words(bnn.bmm_thr(A, B, tau, K, ldcb_w=ldcb, path=path))
+    assert np.array_equal(bits, orc.threshold_pack(ref, case["tau"], ldb_w=ldcb)), "bit mismatch"
+
+
+@pytest.mark.parametrize("pname,path", PATHS)
+def test_cfg1_full(bnn, orc, pname, path):
+    run_case(bnn, orc, wl.cfg1(), path)
+
+
+SMALL = [(1, 1, 1), (1, 1, 32), (2, 3, 33), (7, 5, 127), (64, 64, 128), (65, 33, 129), (100, 130, 784),
+         (8, 10, 1024), (257, 129, 4000), (300, 300, 96), (31, 513, 256), (129, 1000, 512), (40, 70, 2080)]
+
+
+@pytest.mark.parametrize("pname,path", PATHS)
+def test_ragged_shapes(bnn, orc, pname, path):
+    for idx, (M, N, K) in enumerate(SMALL):
+        print("shape", M, N, K, pname, flush=True)
+        run_case(bnn, orc, wl.bmm_case(90, M, N, K, index0=10 * idx), path, ld_extra=4 if idx % 2 else 0)
+
+
+@pytest.mark.parametrize("pname,path", PATHS)
+def test_closed_forms_and_max_k(bnn, orc, pname, path):
+    # K at the library's maximum: identical rows give +K, complemented rows -K (exactness of the
+    # fp32 accumulation in the matrix-core path at its largest sum)
+    K = 1 << 20
+    M, N = 40, 33
+    case = wl.bmm_case(91, M, N, K)
+    case["B"][3] = case["A"][5]
+    case["B"][4] = ~case["A"][6]
+    C = host(bnn.bmm(to_dev(case["A"]), to_dev(case["B"]), K, path=path))
+    assert C[5, 3] == K and C[6, 4] == -K
+    ref = orc.bmm(case["A"], case["B"], K, tier=1)
+    assert np.array_equal(C, ref)
+    assert np.array_equal(orc.bmm_rows(case["A"], case["B"], K, 5, 2), C[5:7])
+
+
+@pytest.mark.parametrize("n", [2048, 4096])
+def test_sweep_squares_sampled(bnn, orc, n):
+    # full output against the packed tier-1 oracle, 64 sampled rows against the naive tier-0 one
+    case = wl.cfg2_case("sq%d" % n)
+    ref1 = orc.bmm(case["A"], case["B"], n, tier=1)
+    rows = [0, n - 64, n // 2 - 7]
+    for r0 in rows:
+        nr = 64 if r0 == n - 64 else 16
+        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], n, r0, nr), ref1[r0:r0 + nr])
+    for pname, path in PATHS:
+        print("n", n, pname, flush=True)
+        run_case(bnn, orc, case, path, ref=ref1)
+
+
+@pytest.mark.parametrize("name", ["fc8", "fc128", "fc1024"])
+def test_sweep_fc(bnn, orc, name):
+    case = wl.cfg2_case(name)
+    ref1 = orc.bmm(case["A"], case["B"], case["K"], tier=1)
+    nr = min(case["M"], 32)
+    assert np.array_equal(orc.bmm_rows(case["A"], case["B"], case["K"], case["M"] - nr, nr), ref1[-nr:])
+    for pname, path in PATHS:
+        run_case(bnn, orc, case, path, ref=ref1)
+
+
+@pytest.mark.parametrize("n", [8192, 16384])
+def test_sweep_large_auto_path(bnn, orc, n):
+    # the sizes bench.py times, in the launch configuration it uses (automatic path): the fused
+    # threshold bits in full against tier 1, int32 on sampled rows against tier 0
+    case = wl.cfg2_case("sq%d" % n)
+    A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+    bits = words(bnn.bmm_thr(A, B, tau, n))
+    C = bnn.bmm(A, B, n)
+    torch.cuda.synchronize()
+    ref1 = orc.bmm(case["A"], case["B"], n, tier=1)
+    assert np.array_equal(bits, orc.threshold_pack(ref1, case["tau"], ldb_w=bits.shape[1]))
+    del ref1
+    for r0 in (0, n // 3, n - 8):
+        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], n, r0, 8), host(C[r0:r0 + 8]))
+    # properties that hold at any size
+    Ch = host(C)
+    assert ((Ch - n) % 2 == 0).all() and (np.abs(Ch) <= n).all()
+
+
+def test_threshold_pack_and_packs(bnn, orc):
+    rng = np.random.default_rng(5)
+    for rows, cols, ld in [(1, 1, 1), (5, 77, 4), (130, 1024, 32), (33, 100, 8)]:
+        X = rng.integers(-50, 51, size=(rows, cols)).astype(np.int32)
+        tau = rng.integers(-20, 21, size=cols).astype(np.int32)
+        got = words(bnn.threshold_pack(to_dev(X), to_dev(tau), ldb_w=ld))
+        assert np.array_equal(got, orc.threshold_pack(X, tau, ldb_w=ld))
+        x8 = rng.integers(0, 256, size=(rows, cols)).astype(np.uint8)
+        assert np.array_equal(words(bnn.pack_u8(to_dev(x8), 127, ldb_w=ld)), orc.pack_u8(x8, 127, ldb_w=ld))
+        xf = rng.normal(size=(rows, cols)).astype(np.float32)
+        tf = rng.normal(size=cols).astype(np.float32)
+        xf[0, 0] = tf[0]
+        assert np.array_equal(words(bnn.pack_f32(to_dev(xf), to_dev(tf), ldb_w=ld)), orc.pack_f32(xf, tf, ldb_w=ld))
+        bits = wl.random_bits(rng, rows, cols, ld)
+        assert np.array_equal(host(bnn.unpack_i32(to_dev(bits), cols)), orc.unpack_pm1(bits, cols).astype(np.int32))
+
+
+def test_error_codes(bnn):
+    A = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bmm(A, A, 4 * 32 + 1)                 # K does not fit the leading dimension
+    assert e.value.status == -1
+    A6 = torch.zeros((4, 6), dtype=torch.int32, device="cuda")
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bmm(A6, A6, 100)                      # leading dimension not a multiple of 4 words
+    assert e.value.status == -2
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bmm(A, A, 100, path=7)
+    assert e.value.status == -1
+    big = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    lib = bnn.load()
+    assert lib.bnn_bmm(None, None, None, 1, 1, 1, 4, 4, 1, None) == -1
+    p = __import__("ctypes").c_void_p(big.data_ptr())
+    assert lib.bnn_bmm(p, p, p, 1, 1, (1 << 20) + 1, 1 << 16, 1 << 16, 1, None) == -3

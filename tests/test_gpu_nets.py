@@ -1,0 +1,107 @@
+"""GPU parity: the layer-chained forwards (bnn_net_*) against the oracle's compositions."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import host, to_dev, words
+from oracle import nets
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    import paper_2006_16578_amd as b
+    b.load()
+    return b
+
+
+def build_mlp(bnn, params):
+    net = bnn.Net()
+    net.input_u8(params["dims"][0], params["in_thr"])
+    nl = len(params["W"])
+    for l in range(nl):
+        thr = to_dev(params["thr"][l]) if l < nl - 1 else None
+        net.add_fc(to_dev(params["W"][l]), thr, params["K"][l])
+    return net
+
+
+@pytest.mark.parametrize("batch", [8, 1024, 37])
+@pytest.mark.parametrize("path", [0, 1, 2])
+def test_mlp(bnn, orc, batch, path):
+    params = wl.mlp_params()
+    imgs = wl.mlp_images(batch)
+    ref, hidden = nets.mlp_forward(imgs, params, keep=True)
+    net = build_mlp(bnn, params)
+    scores = host(net.forward(to_dev(imgs), path=path))
+    for l in range(3):
+        assert np.array_equal(words(net.layer_bits(l + 1)), hidden[l]), "hidden layer %d" % l
+    assert np.array_equal(scores, ref)
+
+
+def build_resnet(bnn, p, hw):
+    net = bnn.Net()
+    net.input_conv_f32(to_dev(p["stem_w"]), to_dev(p["stem_thr"]), hw, hw, 4, 3)
+    for blk in p["blocks"]:
+        net.add_block(to_dev(blk["W1"]), to_dev(blk["thr1"]), to_dev(blk["W2"]), to_dev(blk["thr2"]),
+                      to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"])
+    net.add_head_f32(to_dev(p["fc_w"]))
+    return net
+
+
+def check_resnet(bnn, orc, p, x, hw, path, tier):
+    """Protocol for a network whose first layer is fp32: the stem output must match within
+    1e-4 * max(|o|, rms(o)); a stem bit may differ from the oracle's only where the oracle's value
+    is that close to the threshold; the oracle's binarized chain is then run from the GPU's stem
+    bits and every later bit tensor must match exactly; logits within the same fp32 tolerance."""
+    xd = to_dev(x)
+    net = build_resnet(bnn, p, hw)
+    logits = host(net.forward(xd, path=path))
+    stem_bits_gpu = words(net.layer_bits(0)).reshape(x.shape[0], hw // 4, hw // 4, -1)
+    # fp32 stem values
+    _, y = bnn.conv_f32_thr(xd, to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 4, 3, want_f32=True)
+    stem_ref = orc.conv_f32(x, p["stem_w"], 4, 3)
+    tol = 1e-4 * np.maximum(np.abs(stem_ref), np.sqrt((stem_ref.astype(np.float64) ** 2).mean()))
+    assert (np.abs(host(y) - stem_ref) <= tol).all()
+    ref_bits = orc.pack_f32(stem_ref, p["stem_thr"])
+    diff = stem_bits_gpu ^ ref_bits
+    if diff.any():
+        # every differing bit must belong to a value inside the tolerance of its threshold
+        C = p["stem_w"].shape[0]
+        d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), C).reshape(stem_ref.shape) > 0
+        assert (np.abs(stem_ref - p["stem_thr"])[d] <= tol[d]).all()
+        print("stem bits inside the fp32 tolerance that differ:", int(d.sum()), flush=True)
+    tr = nets.resnet18_forward(x, p, stem_bits=stem_bits_gpu, tier=tier, keep=True)
+    for b in range(len(p["blocks"])):
+        got = words(net.layer_bits(b + 1)).reshape(tr["y%d" % b].shape)
+        assert np.array_equal(got, tr["y%d" % b]), "block %d output bits" % b
+    ref_logits = tr["logits"]
+    tol = 1e-4 * np.maximum(np.abs(ref_logits), np.sqrt((ref_logits.astype(np.float64) ** 2).mean()))
+    assert (np.abs(logits - ref_logits) <= tol).all()
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_resnet_small(bnn, orc, path):
+    blocks = ((64, 64, 1), (64, 96, 2), (96, 96, 1), (96, 128, 2))
+    p = wl.resnet18_params(blocks=blocks, classes=13, config=95)
+    x = wl.resnet18_input(3, hw=32, config=95)
+    check_resnet(bnn, orc, p, x, 32, path, tier=0)
+
+
+def test_resnet18_batch8(bnn, orc):
+    p = wl.resnet18_params()
+    x = wl.resnet18_input(8)
+    check_resnet(bnn, orc, p, x, 224, 0, tier=1)
+
+
+def test_resnet18_head_pooled(bnn, orc):
+    rng = np.random.default_rng(12)
+    bits = wl.random_bits(rng, (9, 7, 7), 512)
+    w = rng.normal(0, 0.02, size=(1000, 512)).astype(np.float32)
+    y, pooled = bnn.head_f32(to_dev(bits), to_dev(w), 512, want_pooled=True)
+    pr = orc.sumpool_pm1(bits, 512)
+    assert np.array_equal(host(pooled), pr)
+    ref = orc.head_fc_f32(pr, w, 49.0)
+    tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
+    assert (np.abs(host(y) - ref) <= tol).all()
