@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the binarized FC / convolution hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass over the BMM sweep of the benchmark configuration (square n = 2048 ... 16384 and
+the FC shapes M in {8, 128, 1024} x 4096 x 4096), every shape once with the fused threshold ->
+packed bits epilogue and once with int32 output; inputs are resident in HBM before the timed
+region.  `value` is the binary-op rate of that whole step (2 ops per +1/-1 multiply-accumulate).
+Timed outside those K steps and reported in the same JSON line: the two BConv layer shapes, the
+binarized MLP (batch 1024 and 8) and the ResNet-18-shaped forward (batch 256), plus the CPU oracle
+on a bounded sample of the sweep.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published dense peaks used as roofline denominators
+PEAK_FP4_MFMA_TFLOPS = 10.1e3      # 4-bit float matrix cores, TFLOP/s (2 flop per MAC)
+PEAK_HBM_GBS = 8000.0
+PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 2080 (context only)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--skip-extras", action="store_true", help="only the BMM sweep (for profiling runs)")
+    ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2006_16578_amd as bnn
+    import workloads as wl
+
+    bnn.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+    # ------------------------------------------------------------------ BMM sweep, resident in HBM
+    shapes = []
+    for name, M, N, K, _ in wl.cfg2_shapes():
+        case = wl.cfg2_case(name)
+        A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+        Cb = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
+        C = torch.empty((M, N), dtype=torch.int32, device=dev)
+        shapes.append({"name": name, "M": M, "N": N, "K": K, "A": A, "B": B, "tau": tau, "Cb": Cb, "C": C,
+                       "kernel": bnn.bmm_kernel_name(M, N, K), "t_thr": [], "t_i32": []})
+    macs_step = sum(2.0 * s["M"] * s["N"] * s["K"] for s in shapes)          # both variants
+
+    def one_step(record: bool):
+        for s in shapes:
+            if record:
+                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0.record()
+            bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"])
+            if record:
+                e1.record()
+            bnn.bmm(s["A"], s["B"], s["K"], out=s["C"])
+            if record:
+                e2.record()
+                s["ev"].append((e0, e1, e2))
+
+    for s in shapes:
+        s["ev"] = []
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value_tops = macs_step * 2.0 / (ms_per_step * 1e-3) / 1e12
+
+    per_shape = []
+    for s in shapes:
+        thr_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]]))
+        i32_ms = float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]]))
+        ops = 2.0 * s["M"] * s["N"] * s["K"]
+        kw = wl.nwords(s["K"]) * 4
+        bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
+        bytes_i32 = s["M"] * kw + s["N"] * kw + s["M"] * s["N"] * 4
+        per_shape.append({"shape": s["name"], "M": s["M"], "N": s["N"], "K": s["K"], "kernel": s["kernel"],
+                          "bits_out_ms": round(thr_ms, 5), "bits_out_tops": round(ops / thr_ms / 1e9, 2),
+                          "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                          "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
+                          "int32_out_ms": round(i32_ms, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
+                          "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1)})
+
+    # roofline of the dominant kernel: the launches (both epilogues) of the kernel variant that
+    # takes the most time in a step
+    by_kernel = {}
+    for s, ps in zip(shapes, per_shape):
+        d = by_kernel.setdefault(s["kernel"], {"ms": 0.0, "flop": 0.0, "launches": 0})
+        d["ms"] += ps["bits_out_ms"] + ps["int32_out_ms"]
+        d["flop"] += 2 * 2.0 * s["M"] * s["N"] * s["K"]
+        d["launches"] += 2
+    dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
+    dk = by_kernel[dom]
+    achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_FP4_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
+                "flop_per_launch": dk["flop"] / dk["launches"],
+                "note": "fp4 (E2M1) matrix-core peak; 1 MAC on +1/-1 = 2 flop = 2 binary ops"}
+
+    extras = {}
+    if not args.skip_extras:
+        extras = run_extras(bnn, wl, np, torch, to_dev, dev)
+    cpu = None
+    if not args.skip_cpu:
+        cpu = cpu_baseline(wl, np)
+
+    line = {
+        "metric": "binary TOPS for BMM/BConv (fraction of roofline); BNN ResNet-18 images/s",
+        "value": round(value_tops, 2), "unit": "binary TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u1 (+1/-1 bits as fp4 E2M1 on the matrix cores, fp32/int32 accumulate)", "data": "synthetic",
+        "config": {"workload": "BMM sweep (config 2): square n in {2048,4096,8192,16384} + FC M in {8,128,1024} x "
+                               "K=4096 x N=4096; each shape with fused threshold->bits and with int32 output; "
+                               "uniform random bits, seeded", "path": "auto"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "bmm_shapes": per_shape,
+    }
+    line.update(extras)
+    print(json.dumps(line))
+    return 0
+
+
+def _time_gpu(torch, fn, iters, warmup=3):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def run_extras(bnn, wl, np, torch, to_dev, dev):
+    out = {}
+    # ---- single BConv layers (config 4)
+    convs = []
+    for name, case in (("conv_56x56_c128_o128_s1", wl.cfg4a()), ("conv_56x56_c64_o128_s2", wl.cfg4b())):
+        x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
+        N, H, W, C, O, k, st, pad = (case[q] for q in ("N", "H", "W", "C", "O", "k", "stride", "pad"))
+        P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+        bits = torch.empty((N, P, Q, wl.nwords(O)), dtype=torch.int32, device=dev)
+        y = torch.empty((N, P, Q, O), dtype=torch.int32, device=dev)
+        ops = 2.0 * N * P * Q * O * k * k * C
+        t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, C, st, pad, bnn.PAD_MINUS_ONE, out=bits), 20)
+        t_i = _time_gpu(torch, lambda: bnn.bconv(x, f, C, st, pad, bnn.PAD_MINUS_ONE, out=y), 20)
+        convs.append({"shape": name, "kernel": bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad),
+                      "bits_out_ms": round(t_b, 5), "bits_out_tops": round(ops / t_b / 1e9, 2),
+                      "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                      "int32_out_ms": round(t_i, 5), "int32_out_tops": round(ops / t_i / 1e9, 2),
+                      "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1)})
+        del x, f, bits, y
+    out["bconv_shapes"] = convs
+    # ---- binarized MLP (config 3)
+    params = wl.mlp_params()
+    net = bnn.Net()
+    net.input_u8(784, 127)
+    for l in range(4):
+        net.add_fc(to_dev(params["W"][l]), to_dev(params["thr"][l]) if l < 3 else None, params["K"][l])
+    mlp = {}
+    for batch in (1024, 8):
+        imgs = to_dev(wl.mlp_images(batch))
+        o = torch.empty((batch, 10), dtype=torch.int32, device=dev)
+        t = _time_gpu(torch, lambda: net.forward(imgs, out=o), 50)
+        mlp["batch%d" % batch] = {"ms": round(t, 5), "images_per_s": round(batch / t * 1e3, 1)}
+    out["mlp_784_1024x3_10"] = mlp
+    # ---- ResNet-18-shaped forward (config 5), batch 256
+    p = wl.resnet18_params()
+    rnet = bnn.Net()
+    rnet.input_conv_f32(to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 224, 224, 4, 3)
+    for blk in p["blocks"]:
+        rnet.add_block(to_dev(blk["W1"]), to_dev(blk["thr1"]), to_dev(blk["W2"]), to_dev(blk["thr2"]),
+                       to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"])
+    rnet.add_head_f32(to_dev(p["fc_w"]))
+    res = {}
+    for batch in (256, 8):
+        x = to_dev(wl.resnet18_input(batch))
+        o = torch.empty((batch, 1000), dtype=torch.float32, device=dev)
+        t = _time_gpu(torch, lambda: rnet.forward(x, out=o), 10 if batch == 256 else 30)
+        res["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+        if batch == 256:
+            xs, w, th = x, to_dev(p["stem_w"]), to_dev(p["stem_thr"])
+            ts = _time_gpu(torch, lambda: bnn.conv_f32_thr(xs, w, th, 4, 3), 5)
+            res["batch256"]["stem_fp32_ms"] = round(ts, 4)
+            res["batch256"]["binarized_layers_tops"] = round(2 * 1.70e9 * batch / max(t - ts, 1e-6) / 1e9, 1)
+        del x
+    res["paper_rtx2080_images_per_s_context_only"] = PAPER_RESNET18_IMG_S
+    out["resnet18_224"] = res
+    return out
+
+
+def cpu_baseline(wl, np):
+    """The CPU oracle (tier 0: naive +1/-1 int8 loops, OpenMP over rows) timed on a bounded sample
+    of the same sweep: the first 96 rows of A of every shape (all rows where M < 96)."""
+    import oracle as orc
+    orc.build()
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    macs = 0.0
+    secs = 0.0
+    for name, M, N, K, _ in wl.cfg2_shapes():
+        case = wl.cfg2_case(name)
+        rows = min(M, 96)
+        t0 = time.perf_counter()
+        orc.bmm_rows(case["A"], case["B"], K, 0, rows)
+        secs += time.perf_counter() - t0
+        macs += float(rows) * N * K
+    return {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "binary TOPS", "cores": cores, "kind": "oracle",
+            "seconds": round(secs, 2),
+            "sample": "tier-0 oracle (unpacked int8 +1/-1, naive loops, includes unpacking B) on the first 96 rows of A "
+                      "of every sweep shape, int32 output"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -56,6 +56,10 @@ typedef enum bnn_status {
 
 const char* bnn_status_string(int status);
 int bnn_version(void);
+/* Name of the kernel variant (path and wave tile) the library launches for a BMM / BConv of this
+ * shape, for profiles and reports; a static string, "invalid" for shapes the calls reject. */
+const char* bnn_bmm_kernel_name(int M, int N, int K, int path);
+const char* bnn_bconv_kernel_name(int N, int H, int W, int C, int O, int k, int stride, int pad, int path);
 
 /* ------------------------------------------------------------------------------------------
  * BMM (Sec. 5.2, Eq. 2): C[i][j] = sum_{k<K} a[i][k] * b[j][k] = K - 2 * popc(A_i xor B_j).

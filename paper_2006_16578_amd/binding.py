@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "conv_f32_thr", "head_f32", "Net", "EXPORTS"]
+           "unpack_i32", "conv_f32_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -22,7 +22,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 # every symbol include/bnn.h declares
-EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
+EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
            "bnn_pack_f32", "bnn_unpack_i32", "bnn_conv_f32_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_add_fc",
@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
         lib = ctypes.CDLL(path)
         lib.bnn_status_string.restype = ctypes.c_char_p
         lib.bnn_status_string.argtypes = [ctypes.c_int]
+        lib.bnn_bmm_kernel_name.restype = ctypes.c_char_p
+        lib.bnn_bconv_kernel_name.restype = ctypes.c_char_p
         for name in EXPORTS:
             getattr(lib, name)          # fail loudly on a missing export
         _lib = lib
@@ -70,6 +72,14 @@ def _status_string(status: int) -> str:
 def _check(status: int, what: str) -> None:
     if status != 0:
         raise BnnError(status, what)
+
+
+def bmm_kernel_name(M: int, N: int, K: int, path: int = PATH_AUTO) -> str:
+    return load().bnn_bmm_kernel_name(int(M), int(N), int(K), int(path)).decode()
+
+
+def bconv_kernel_name(N, H, W, C, O, k, stride, pad, path: int = PATH_AUTO) -> str:
+    return load().bnn_bconv_kernel_name(int(N), int(H), int(W), int(C), int(O), int(k), int(stride), int(pad), int(path)).decode()
 
 
 def nwords(nbits: int) -> int:
@@ -135,6 +145,8 @@ def _conv_dims(x, filt, C, stride, pad):
     O, k, k2, cwf = filt.shape
     if k != k2 or cw != cwf or cw != nwords(C):
         raise ValueError("x [N][H][W][cw], filt [O][k][k][cw] with cw = ceil(C/32) expected")
+    if stride < 1:                       # the library rejects it; keep the shapes computable
+        return N, H, W, O, k, 1, 1
     P = (H + 2 * pad - k) // stride + 1
     Q = (W + 2 * pad - k) // stride + 1
     return N, H, W, O, k, P, Q

@@ -185,6 +185,20 @@ const char* bnn_status_string(int status) {
 
 int bnn_version(void) { return 100; }
 
+const char* bnn_bmm_kernel_name(int M, int N, int K, int path) {
+    if (M < 1 || N < 1 || K < 1 || K > BNN_MAX_K) return "invalid";
+    Geom g = {};
+    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = round4(words(K)); g.bits_tap = K;
+    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g);
+}
+const char* bnn_bconv_kernel_name(int N, int H, int W, int C, int O, int k, int stride, int pad, int path) {
+    int P, Q;
+    if (conv_shape(N, H, W, C, O, k, stride, pad, BNN_PAD_MINUS_ONE, &P, &Q) != BNN_OK) return "invalid";
+    Geom g = {};
+    g.rows = (long long)N * P * Q; g.cols = O; g.conv = 1; g.taps = k * k; g.tw = words(C); g.bits_tap = C;
+    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g);
+}
+
 int bnn_bmm(const uint32_t* A, const uint32_t* B, int32_t* C, int M, int N, int K, int lda_w, int ldb_w, int ldc,
             void* stream) {
     return bnn_bmm_ex(A, B, C, M, N, K, lda_w, ldb_w, ldc, BNN_PATH_AUTO, stream);

@@ -269,14 +269,22 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
     return check_launch();
 }
 
-template <int V, bool CONV, bool GUARD>
-int launch_shape(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
-    // Largest wave tile that still gives every CU work: 256 CUs, one 4-wave workgroup each.
+// Largest wave tile that still gives every CU work: 256 CUs, one 4-wave workgroup each.
+inline int pick_tile(const Geom& g) {
     const long long wg44 = cdiv(g.rows, 256) * cdiv(g.cols, 256);
     const long long wg22 = cdiv(g.rows, 128) * cdiv(g.cols, 128);
-    if (wg44 >= 512) return launch_tile<4, 4, V, CONV, GUARD>(A, B, g, e, s);
-    if (wg22 >= 256) return launch_tile<2, 2, V, CONV, GUARD>(A, B, g, e, s);
-    return launch_tile<1, 1, V, CONV, GUARD>(A, B, g, e, s);
+    if (wg44 >= 512) return 4;
+    if (wg22 >= 256) return 2;
+    return 1;
+}
+
+template <int V, bool CONV, bool GUARD>
+int launch_shape(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    switch (pick_tile(g)) {
+        case 4: return launch_tile<4, 4, V, CONV, GUARD>(A, B, g, e, s);
+        case 2: return launch_tile<2, 2, V, CONV, GUARD>(A, B, g, e, s);
+        default: return launch_tile<1, 1, V, CONV, GUARD>(A, B, g, e, s);
+    }
 }
 
 }  // namespace
@@ -292,6 +300,14 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
     if (g.tw % 4 == 0) return launch_shape<2, true, false>(A, B, g, e, s);
     if (g.tw % 2 == 0) return launch_shape<1, true, false>(A, B, g, e, s);
     return launch_shape<1, true, true>(A, B, g, e, s);
+}
+
+const char* describe_mfma(const Geom& g) {
+    switch (pick_tile(g)) {
+        case 4: return g.conv ? "mfma_fp4_conv_wave128x128" : "mfma_fp4_bmm_wave128x128";
+        case 2: return g.conv ? "mfma_fp4_conv_wave64x64" : "mfma_fp4_bmm_wave64x64";
+        default: return g.conv ? "mfma_fp4_conv_wave32x32" : "mfma_fp4_bmm_wave32x32";
+    }
 }
 
 }  // namespace bnn

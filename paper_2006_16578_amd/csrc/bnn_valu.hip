@@ -134,4 +134,6 @@ int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
     return launch_vw<1, true>(A, B, g, e, s);
 }
 
+const char* describe_valu(const Geom& g) { return g.conv ? "valu_xor_popc_conv" : "valu_xor_popc_bmm"; }
+
 }  // namespace bnn
