@@ -17,7 +17,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbnn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["bnn_api.hip", "bnn_valu.hip", "bnn_mfma.hip", "bnn_aux.hip"]
+SOURCES = ["bnn_api.hip", "bnn_valu.hip", "bnn_mfma.hip", "bnn_mfma_conv_v4.hip", "bnn_mfma_conv_v2.hip",
+           "bnn_mfma_conv_v1.hip", "bnn_aux.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-value",
          # packed fp32 VALU forms are kept off for every device function of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -44,7 +45,7 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = False, jobs: int = 4) -> str:
+def build(force: bool = False, jobs: int = 7) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))

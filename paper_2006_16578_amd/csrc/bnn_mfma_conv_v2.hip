@@ -1,0 +1,10 @@
+// Matrix-core path: convolution instantiations with 2 packed words per lane and load.
+#include "bnn_mfma_kernel.h"
+
+namespace bnn {
+
+int launch_mfma_conv_v2(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    return mfma::launch_shape<2, true, false>(A, B, g, e, s);
+}
+
+}  // namespace bnn

@@ -1,0 +1,375 @@
+// Matrix-core path (kernel template; included by the translation units that instantiate it): +1/-1 products on the CDNA4 MFMA units.
+//
+// gfx950 has no 1-bit matrix type.  Its densest one is the 4-bit float E2M1 of
+// v_mfma_f32_32x32x64_f8f6f4, in which +1.0 is 0b0010 and -1.0 is 0b1010.  A packed word of 32
+// bits becomes the 32 four-bit operands one lane feeds to that instruction with seven VALU
+// operations: nibble i of output register j is 0x2 | (bit(4i+j) << 3).  This maps bit 1 to -1.0
+// and bit 0 to +1.0 in BOTH operands, which leaves every product, hence the dot product of
+// Eq. 2, unchanged ((-a)(-b) = ab) and saves inverting the word.  Which bit lands in which K
+// slot of the instruction does not matter as long as both operands use the same rule.
+// Products are +-1 and are accumulated in fp32, exact while |sum| < 2^24 (K <= 2^20 here).
+//
+// Operand delivery: in the 32x32x64 shape lane l supplies row (l % 32) and the 32 K-values of
+// K-group (l / 32) -- exactly one packed word.  Bits are so dense (64 B per row feed 8 MFMAs of
+// a 128x128 wave tile) that fragments are read straight from global memory / L2 into registers,
+// 16 B per lane at a time, with a register double buffer; there is no LDS stage to conflict on.
+//
+// Tiling: a workgroup is 2 x 2 waves, a wave owns MT x NT accumulator tiles of 32 x 32
+// (MT = NT = 4: 128 x 128 per wave, 256 accumulator registers per lane).
+//
+// Epilogue: in the 32x32 accumulator layout register r of lane l holds row 8*(r/4) + 4*(l/32)
+// + r%4, column l%32.  A threshold compare of one register therefore yields, as a 64-bit wave
+// ballot, the packed output words of two rows; they are collected with v_writelane so that lane
+// m ends up with the word of row m.  int32 sums never go to memory unless asked for.
+#ifndef BNN_MFMA_KERNEL_H
+#define BNN_MFMA_KERNEL_H
+#include <limits.h>
+
+#include "bnn_internal.h"
+
+namespace bnn {
+namespace mfma {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int V> struct WordVec;
+template <> struct WordVec<1> { typedef uint32_t type; };
+template <> struct WordVec<2> { typedef uint2 type; };
+template <> struct WordVec<4> { typedef uint4 type; };
+
+template <int V>
+__device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&a)[V]) {
+    typename WordVec<V>::type v = *reinterpret_cast<const typename WordVec<V>::type*>(p);
+    if constexpr (V == 1) { a[0] = v; }
+    else if constexpr (V == 2) { a[0] = v.x; a[1] = v.y; }
+    else { a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w; }
+}
+
+// 32 packed bits -> 32 E2M1 values in 4 registers (the upper 4 of the 8-register operand are
+// ignored by the instruction for 4-bit formats).  c2 holds 0x22222222 in a VGPR so that each
+// output needs one shift and one v_and_or_b32.
+__device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t c2) {
+    v8i r;
+    r[0] = (int)(((w << 3) & 0x88888888u) | c2);
+    r[1] = (int)(((w << 2) & 0x88888888u) | c2);
+    r[2] = (int)(((w << 1) & 0x88888888u) | c2);
+    r[3] = (int)((w & 0x88888888u) | c2);
+    r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
+    return r;
+}
+
+// v_writelane_b32 through the compiler's own intrinsic (clang has no builtin for it), so that the
+// wait states the hardware needs between a VALU compare that writes an SGPR pair and the
+// v_writelane that reads it are inserted by the compiler: hand-written asm reads a stale value.
+extern "C" __device__ int bnn_llvm_writelane_i32(int val, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
+// Returns `old` with the value of lane `lane` replaced by the wave-uniform `val`.
+__device__ __forceinline__ uint32_t write_lane(uint32_t val, int lane, uint32_t old) {
+    return (uint32_t)bnn_llvm_writelane_i32((int)val, lane, (int)old);
+}
+
+// Workgroup shape: WM x WN waves, each owning MT x NT accumulator tiles of 32 x 32; MINB is the
+// number of workgroups per CU the register allocation is sized for.
+template <int MT_, int NT_, int WM_, int WN_, int MINB_>
+struct Tile {
+    static constexpr int MT = MT_, NT = NT_, WM = WM_, WN = WN_, MINB = MINB_;
+    static constexpr int ROWS = WM_ * MT_ * 32, COLS = WN_ * NT_ * 32;
+};
+typedef Tile<4, 2, 2, 2, 2> TileBig;    // 256 x 128
+typedef Tile<4, 2, 4, 1, 2> TileTall;   // 512 x 64   (at most 64 output columns)
+typedef Tile<2, 2, 2, 2, 4> TileMid;    // 128 x 128
+typedef Tile<1, 1, 2, 2, 4> TileSmall;  // 64 x 64
+
+// Workgroup id -> tile coordinates.  Consecutive workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2: give every XCD one contiguous range of tiles, and inside a range
+// walk groups of 8 row tiles for each column tile, so that the workgroups resident on an XCD at
+// the same time share A rows and B rows in that L2.
+__device__ __forceinline__ bool tile_coords(int gx, int gy, int& bx, int& by) {
+    const int total = gx * gy;
+    const int per_xcd = (total + 7) / 8;
+    const int id = (int)blockIdx.x;
+    const int t = (id & 7) * per_xcd + (id >> 3);
+    if (t >= total) return false;
+    constexpr int GM = 8;
+    const int span = GM * gy;
+    const int group = t / span;
+    const int first = group * GM;
+    const int gsz = min(gx - first, GM);
+    const int in = t - group * span;
+    by = in / gsz;
+    bx = first + (in - by * gsz);
+    return true;
+}
+
+// V: words each lane loads per fragment and chunk (a chunk is 2*V words = V MFMA K-steps);
+// CONV: rows are output pixels gathered through the filter window; EXCL: out-of-frame taps
+// contribute nothing; GUARD: the last chunk of a tap may run past tw.
+template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
+__global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __restrict__ A,
+                                                             const uint32_t* __restrict__ B, Geom g, Epi e,
+                                                             int gx, int gy) {
+    constexpr int MT = TL::MT, NT = TL::NT;
+    int bx, by;
+    if (!tile_coords(gx, gy, bx, by)) return;          // uniform for the workgroup
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const long long m0 = ((long long)bx * TL::WM + (wave / TL::WN)) * (MT * 32);
+    const int n0 = (by * TL::WN + (wave % TL::WN)) * (NT * 32);
+
+    uint32_t c2;
+    asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c2));
+
+    // Row descriptors of the A fragments.
+    const uint32_t* arow[MT];
+    int y0[MT], x0[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        long long row = m0 + 32 * i + l32;
+        if (row > g.rows - 1) row = g.rows - 1;          // clamp: loads stay in bounds, results are dropped
+        if (CONV) {
+            const int pq = g.P * g.Q;
+            const int n = (int)(row / pq);
+            const int rem = (int)(row - (long long)n * pq);
+            const int p = rem / g.Q, q = rem - p * g.Q;
+            y0[i] = p * g.stride - g.pad;
+            x0[i] = q * g.stride - g.pad;
+            arow[i] = A + (long long)n * g.H * g.W * g.lda_w;
+        } else {
+            y0[i] = 0; x0[i] = 0;
+            arow[i] = A + row * g.lda_w;
+        }
+    }
+    const uint32_t* brow[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = min(n0 + 32 * j + l32, g.cols - 1);
+        brow[j] = B + (long long)col * g.ldb_w;
+    }
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int cpt = (g.tw + 2 * V - 1) / (2 * V);   // chunks per tap
+    const int T = g.taps * cpt;                     // chunks in all
+
+    uint32_t ra[2][MT][V], rb[2][NT][V];
+    uint32_t keep[2][MT];                           // EXCL: 0 for an out-of-frame tap
+
+    // Loads chunk cc of tap tt into buffer `buf`.
+    auto load_chunk = [&](int buf, int tt, int cc) {
+        const int wo = cc * 2 * V + half * V;       // this lane's word offset inside the tap
+        const bool wok = !GUARD || (wo < g.tw);     // tw and wo are multiples of V
+        int r = 0, s = 0;
+        if (CONV) { r = tt / g.k; s = tt - r * g.k; }
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const uint32_t* p = arow[i];
+            bool ok = wok;
+            if (CONV) {
+                const int y = y0[i] + r, x = x0[i] + s;
+                const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
+                p += (inside ? (y * g.W + x) : 0) * g.lda_w;
+                ok = ok && inside;
+                keep[buf][i] = inside ? 0xFFFFFFFFu : 0u;
+            }
+            load_words<V>(p + (wok ? wo : 0), ra[buf][i]);
+            if (CONV || GUARD) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) ra[buf][i][v] = ok ? ra[buf][i][v] : 0u;
+            }
+        }
+        const int boff = tt * g.tw + (wok ? wo : 0);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            load_words<V>(brow[j] + boff, rb[buf][j]);
+            if (GUARD) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) rb[buf][j][v] = wok ? rb[buf][j][v] : 0u;
+            }
+        }
+    };
+
+    auto compute_chunk = [&](int buf) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            v8i fa[MT], fb[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                fa[i] = expand_fp4(ra[buf][i][v], c2);
+                if (EXCL) {
+                    fa[i][0] &= (int)keep[buf][i]; fa[i][1] &= (int)keep[buf][i];
+                    fa[i][2] &= (int)keep[buf][i]; fa[i][3] &= (int)keep[buf][i];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) fb[j] = expand_fp4(rb[buf][j][v], c2);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], 4 /*A: E2M1*/, 4 /*B: E2M1*/, 0, 0, 0, 0);
+        }
+    };
+
+    int tt = 0, cc = 0;
+    load_chunk(0, 0, 0);
+    for (int t = 0; t < T; t += 2) {
+        // unrolled by two so that the double buffer indices are compile-time constants
+        int t1 = tt, c1 = cc + 1;
+        if (c1 == cpt) { c1 = 0; ++t1; }
+        if (t + 1 < T) load_chunk(1, t1, c1);
+        compute_chunk(0);
+        if (t + 1 < T) {
+            int t2 = t1, c2n = c1 + 1;
+            if (c2n == cpt) { c2n = 0; ++t2; }
+            if (t + 2 < T) load_chunk(0, t2, c2n);
+            compute_chunk(1);
+            tt = t2; cc = c2n;
+        }
+    }
+
+    // ---- epilogue --------------------------------------------------------------------------
+    // Every processed bit position beyond the logical width is a 0 bit in both operands and has
+    // contributed (+1)(+1) = +1: remove them.  In exclude mode only in-frame taps did.
+    const int pad_tap = cpt * 2 * V * 32 - g.bits_tap;
+    const int corr_all = g.taps * pad_tap;
+    const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
+
+    int thi[NT];           // threshold of this lane's column; INT_MAX (never reached) outside the matrix
+    bool cok[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < g.cols;
+        thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
+    }
+
+    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && !row_corr) {
+        // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
+        // by the pad correction; one v_cmp per accumulator register gives two packed words.
+        float thf[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)(thi[j] + corr_all) : __builtin_inff();
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const long long rbase = m0 + 32 * i;
+            if (rbase >= g.rows) break;                          // uniform per wave
+            uint32_t wout[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lo_row = 8 * (r >> 2) + (r & 3);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(acc[i][j][r] >= thf[j]);
+                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+                }
+            }
+            const long long row = rbase + lane;
+            if (lane < 32 && row < g.rows) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                }
+            }
+        }
+        return;
+    }
+
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wout[j] = 0u;
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= g.rows) break;                              // uniform per wave
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rloc = 8 * (r >> 2) + 4 * half + (r & 3);
+            const long long row = rbase + rloc;
+            const bool rok = row < g.rows;
+            int corr = corr_all;
+            if (row_corr) {
+                const long long rr = rok ? row : g.rows - 1;
+                const int pq = g.P * g.Q;
+                const int rem = (int)(rr % pq);
+                const int p = rem / g.Q, q = rem - p * g.Q;
+                const int ylo = p * g.stride - g.pad, xlo = q * g.stride - g.pad;
+                const int vy = min(ylo + g.k, g.H) - max(ylo, 0);
+                const int vx = min(xlo + g.k, g.W) - max(xlo, 0);
+                corr = vy * vx * pad_tap;
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int col = n0 + 32 * j + l32;
+                int v = (int)acc[i][j][r] - corr;
+                const long long idx = row * (long long)e.ldc + col;
+                if (e.resid != nullptr && rok && cok[j]) v += e.resid[idx];
+                if (e.out != nullptr && rok && cok[j]) e.out[idx] = v;
+                if (e.bits != nullptr) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
+                    const int lo_row = 8 * (r >> 2) + (r & 3);
+                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+                }
+            }
+        }
+        if (e.bits != nullptr && lane < 32) {
+            const long long row = rbase + lane;
+            if (row < g.rows) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                }
+            }
+        }
+    }
+}
+
+template <class TL, int V, bool CONV, bool GUARD>
+int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    const int col_span = (e.bits != nullptr) ? max(g.cols, e.ldbits_w * 32) : g.cols;
+    const int gx = (int)cdiv(g.rows, TL::ROWS), gy = (int)cdiv(col_span, TL::COLS);
+    const unsigned nwg = (unsigned)(cdiv((long long)gx * gy, 8) * 8);
+    if (CONV && g.excl)
+        hipLaunchKernelGGL((mfma_kernel<TL, V, CONV, CONV, GUARD>), dim3(nwg), dim3(256), 0, s, A, B, g, e, gx, gy);
+    else
+        hipLaunchKernelGGL((mfma_kernel<TL, V, CONV, false, GUARD>), dim3(nwg), dim3(256), 0, s, A, B, g, e, gx, gy);
+    return check_launch();
+}
+
+// 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
+// CUs (two workgroups each for the big tiles) enough workgroups.
+inline int pick_tile(const Geom& g) {
+    if (g.cols <= 64) return (cdiv(g.rows, TileTall::ROWS) >= 256) ? 1 : 3;
+    if (cdiv(g.rows, TileBig::ROWS) * cdiv(g.cols, TileBig::COLS) >= 384) return 0;
+    if (cdiv(g.rows, TileMid::ROWS) * cdiv(g.cols, TileMid::COLS) >= 256) return 2;
+    return 3;
+}
+
+template <int V, bool CONV, bool GUARD>
+int launch_shape(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    switch (pick_tile(g)) {
+        case 0: return launch_tile<TileBig, V, CONV, GUARD>(A, B, g, e, s);
+        case 1: return launch_tile<TileTall, V, CONV, GUARD>(A, B, g, e, s);
+        case 2: return launch_tile<TileMid, V, CONV, GUARD>(A, B, g, e, s);
+        default: return launch_tile<TileSmall, V, CONV, GUARD>(A, B, g, e, s);
+    }
+}
+
+}  // namespace mfma
+}  // namespace bnn
+#endif
