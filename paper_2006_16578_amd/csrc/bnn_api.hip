@@ -54,9 +54,11 @@ int conv_shape(int N, int H, int W, int C, int O, int k, int stride, int pad, in
     return BNN_OK;
 }
 
+// resid_bits (internal, used by the layer chain): a packed [N][P][Q][ceil(O/32)] tensor whose +1/-1
+// values are the residual, instead of an int32 tensor.
 int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const int32_t* resid,
                  const int32_t* thr, uint32_t* bits, int N, int H, int W, int C, int O, int k, int stride,
-                 int pad, int pad_mode, int path, void* stream) {
+                 int pad, int pad_mode, int path, void* stream, const uint32_t* resid_bits = nullptr) {
     if (!in || !filt) return BNN_ERR_INVALID_ARG;
     if (!out && !bits) return BNN_ERR_INVALID_ARG;
     if (bits && !thr) return BNN_ERR_INVALID_ARG;
@@ -74,6 +76,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
     g.excl = (pad_mode == BNN_PAD_EXCLUDE) ? 1 : 0;
     Epi e = {};
     e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O);
+    e.resid_bits = resid ? nullptr : resid_bits; e.ld_resid_bits_w = words(O);
     return dispatch(in, filt, g, e, path, static_cast<hipStream_t>(stream));
 }
 
@@ -412,29 +415,29 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 uint32_t* hbits = obits;                                     // first half of the slot
                 uint32_t* ybits = obits + (size_t)batch * L.H * L.W * L.words_per_row;
                 int32_t* Rnew = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 1) % 3]);
-                const int32_t* shortcut;
+                // the block's sum is kept only if the next layer is a block that adds it back
+                const bool keep_sum = (i + 1 < net->layers.size()) && net->layers[i + 1].kind == bnn_net::BLOCK &&
+                                      net->layers[i + 1].w2 == nullptr;
+                const int32_t* shortcut = nullptr;
+                const uint32_t* shortcut_bits = nullptr;
                 if (L.w2) {     // 1x1 binarized downsample of the block input (int32)
                     int32_t* sc = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 2) % 3]);
                     rc = bnn_bconv_ex(cur, static_cast<const uint32_t*>(L.w2), sc, batch, curH, curW, curC, L.b, 1,
                                       L.stride, 0, L.pad_mode, path, stream);
                     if (rc != BNN_OK) return rc;
                     shortcut = sc;
-                } else {
-                    if (!R) {   // first block: seed the residual with the +1/-1 values of its input
-                        int32_t* R0 = reinterpret_cast<int32_t*>(ws + pl.resid_off[rslot]);
-                        rc = bnn_unpack_i32(cur, R0, (long long)batch * curH * curW, curC, cur_ld, curC, stream);
-                        if (rc != BNN_OK) return rc;
-                        R = R0;
-                    }
+                } else if (R) {
                     shortcut = R;
+                } else {        // first block of a chain: the residual is the +1/-1 values of its input bits
+                    shortcut_bits = cur;
                 }
                 rc = bnn_bconv_thr_ex(cur, static_cast<const uint32_t*>(L.w0), nullptr, nullptr,
                                       static_cast<const int32_t*>(L.t0), hbits, batch, curH, curW, curC, L.b, 3,
                                       L.stride, 1, L.pad_mode, path, stream);
                 if (rc != BNN_OK) return rc;
-                rc = bnn_bconv_thr_ex(hbits, static_cast<const uint32_t*>(L.w1), shortcut, Rnew,
-                                      static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
-                                      L.pad_mode, path, stream);
+                rc = bconv_common(hbits, static_cast<const uint32_t*>(L.w1), keep_sum ? Rnew : nullptr, shortcut,
+                                  static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
+                                  L.pad_mode, path, stream, shortcut_bits);
                 R = Rnew; rslot = (rslot + 1) % 3;
                 obits = ybits;
                 break;

@@ -43,75 +43,129 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     }
 }
 
-// First layer: fp32 convolution, zero padding, then per-channel threshold -> bits.
-// One lane per output pixel, one wave per group of 16 output channels (weights of a wave are
-// uniform and come through the scalar cache); the 4 waves of a workgroup cover 64 channels of the
-// same 64 pixels.  Weights are read in the caller's [O][k][k][C] order.
+// First layer: fp32 convolution with zero padding, then per-channel threshold -> bits, as an
+// implicit GEMM on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): rows are output pixels,
+// columns output channels, and K runs over the k filter rows times the k*C contiguous floats of
+// one filter row -- contiguous in the NHWC input as well, so lane l of a wave reads element
+// 2*t + l/32 of the row segment of pixel l%32 with no index arithmetic beyond one bounds test.
+// A wave owns 2 x 2 accumulator tiles (64 pixels x 64 channels), a workgroup 256 pixels.
+typedef float v16f_aux __attribute__((ext_vector_type(16)));
+extern "C" __device__ int bnn_aux_writelane_i32(int val, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
+constexpr int STEM_MT = 2, STEM_NT = 2;
+
 __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                        const float* __restrict__ thr, float* __restrict__ y,
                                                        uint32_t* __restrict__ bits, int N, int H, int W, int C,
                                                        int O, int k, int stride, int pad, int P, int Q) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5, wave = threadIdx.x >> 6;
     const long long npix = (long long)N * P * Q;
-    const long long pix_raw = (long long)blockIdx.x * 64 + lane;
-    const bool pix_ok = pix_raw < npix;
-    const long long pix = pix_ok ? pix_raw : npix - 1;
-    const int o0 = ((int)blockIdx.y * 4 + wave) * 16;
-    if (o0 >= O) return;
-    const int n = (int)(pix / (P * Q));
-    const int rem = (int)(pix - (long long)n * P * Q);
-    const int p = rem / Q, q = rem - p * Q;
-    const int y0 = p * stride - pad, x0 = q * stride - pad;
-    float acc[16];
+    const long long m0 = ((long long)blockIdx.x * 4 + wave) * (STEM_MT * 32);
+    const int n0 = (int)blockIdx.y * (STEM_NT * 32);
+    if (m0 >= npix) return;                                  // uniform per wave
+    const int seg = k * C;                                   // floats in one filter row
+    const int steps = (seg + 1) / 2;
+    const int rowlen = W * C;
+
+    const float* xrow[STEM_MT];     // start of input row y0 of this lane's pixel
+    int xoff[STEM_MT], ytop[STEM_MT];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-    const int kkc = k * k * C;
+    for (int i = 0; i < STEM_MT; ++i) {
+        long long pix = m0 + 32 * i + l32;
+        if (pix > npix - 1) pix = npix - 1;
+        const int n = (int)(pix / (P * Q));
+        const int rem = (int)(pix - (long long)n * P * Q);
+        const int p = rem / Q, q = rem - p * Q;
+        ytop[i] = p * stride - pad;
+        xoff[i] = (q * stride - pad) * C;
+        xrow[i] = x + (long long)n * H * rowlen;
+    }
+    const float* wrow[STEM_NT];
+#pragma unroll
+    for (int j = 0; j < STEM_NT; ++j) wrow[j] = w + (long long)min(n0 + 32 * j + l32, O - 1) * k * seg;
+
+    v16f_aux acc[STEM_MT][STEM_NT];
+#pragma unroll
+    for (int i = 0; i < STEM_MT; ++i)
+#pragma unroll
+        for (int j = 0; j < STEM_NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
     for (int r = 0; r < k; ++r) {
-        for (int s = 0; s < k; ++s) {
-            const int yy = y0 + r, xx = x0 + s;
-            const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
-            const float* xp = x + (((long long)n * H + (inside ? yy : 0)) * W + (inside ? xx : 0)) * C;
-            const float* wp = w + (r * k + s) * C;
-            for (int c = 0; c < C; ++c) {
-                const float xv = inside ? xp[c] : 0.f;
+        for (int t = 0; t < steps; ++t) {
+            const int e = 2 * t + half;
+            const bool eok = e < seg;
+            float a[STEM_MT], b[STEM_NT];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int o = min(o0 + j, O - 1);
-                    acc[j] = fmaf(xv, wp[(long long)o * kkc + c], acc[j]);
+            for (int i = 0; i < STEM_MT; ++i) {
+                const int yy = ytop[i] + r;
+                const int xe = xoff[i] + e;
+                const bool ok = eok && (unsigned)yy < (unsigned)H && (unsigned)xe < (unsigned)rowlen;
+                const float v = xrow[i][ok ? (long long)yy * rowlen + xe : 0];
+                a[i] = ok ? v : 0.f;                         // zero padding
+            }
+#pragma unroll
+            for (int j = 0; j < STEM_NT; ++j) {
+                const float v = wrow[j][eok ? r * seg + e : 0];
+                b[j] = eok ? v : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < STEM_MT; ++i)
+#pragma unroll
+                for (int j = 0; j < STEM_NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    float th[STEM_NT];
+    bool cok[STEM_NT];
+#pragma unroll
+    for (int j = 0; j < STEM_NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < O;
+        th[j] = (bits != nullptr && cok[j]) ? thr[col] : __builtin_inff();
+    }
+    const int ow = (O + 31) / 32;
+#pragma unroll
+    for (int i = 0; i < STEM_MT; ++i) {
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= npix) break;
+        uint32_t wout[STEM_NT];
+#pragma unroll
+        for (int j = 0; j < STEM_NT; ++j) wout[j] = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int lo_row = 8 * (r >> 2) + (r & 3);
+            const long long row = rbase + lo_row + 4 * half;
+#pragma unroll
+            for (int j = 0; j < STEM_NT; ++j) {
+                const float v = acc[i][j][r];
+                if (y != nullptr && row < npix && cok[j]) y[row * O + n0 + 32 * j + l32] = v;
+                if (bits != nullptr) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= th[j]);
+                    wout[j] = (uint32_t)bnn_aux_writelane_i32((int)(uint32_t)ball, lo_row, (int)wout[j]);
+                    wout[j] = (uint32_t)bnn_aux_writelane_i32((int)(uint32_t)(ball >> 32), lo_row + 4, (int)wout[j]);
                 }
             }
         }
-    }
-    if (!pix_ok) return;
-    uint32_t word = 0u;
+        const long long row = rbase + lane;
+        if (bits != nullptr && lane < 32 && row < npix) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int o = o0 + j;
-        if (o < O) {
-            if (y != nullptr) y[pix * O + o] = acc[j];
-            if (bits != nullptr && acc[j] >= thr[o]) word |= (1u << j);
+            for (int j = 0; j < STEM_NT; ++j) {
+                const int wi = (n0 >> 5) + j;
+                if (wi < ow) bits[row * ow + wi] = wout[j];
+            }
         }
     }
-    if (bits != nullptr) {
-        // 16 channels = one half word; the two halves of a word are written by different waves
-        uint16_t* hb = reinterpret_cast<uint16_t*>(bits + pix * (long long)((O + 31) / 32));
-        hb[o0 >> 4] = (uint16_t)word;
-    }
 }
 
-// When O is not a multiple of 32 the upper half word of the last word may belong to no wave.
-__global__ void conv_f32_padfix_kernel(uint32_t* bits, long long npix, int O) {
-    const long long pix = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pix >= npix) return;
-    uint16_t* hb = reinterpret_cast<uint16_t*>(bits + pix * (long long)((O + 31) / 32));
-    hb[((O + 31) / 32) * 2 - 1] = 0;
-}
-
-// Head: exact integer sum-pool of +1/-1 over HW positions, then fp32 FC.  One workgroup handles
-// IMGS images so that each weight row is read once per IMGS images; one wave per output row j,
-// lanes stride over channels, wave reduction at the end.
+// Head: exact integer sum-pool of +1/-1 over HW positions, then fp32 FC.  A workgroup handles
+// HEAD_IMGS images and HEAD_OUTS output rows: it pools its images into LDS (cheap: a few KB of
+// bits), then each wave takes output rows in turn, lanes stride over channels, and a butterfly
+// reduction finishes each dot product.
 constexpr int HEAD_IMGS = 8;
+constexpr int HEAD_OUTS = 32;
 constexpr int HEAD_MAXC = 1024;
 
 __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ bits, const float* __restrict__ w,
@@ -119,6 +173,7 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
                                                    int N, int HW, int C, int J) {
     __shared__ float pooled[HEAD_IMGS][HEAD_MAXC];
     const int n0 = blockIdx.x * HEAD_IMGS;
+    const int j0 = blockIdx.y * HEAD_OUTS;
     const int cw = (C + 31) / 32;
     const float inv = (float)HW;
     for (int idx = threadIdx.x; idx < HEAD_IMGS * C; idx += blockDim.x) {
@@ -128,13 +183,13 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
         if (n < N) {
             const uint32_t* b = bits + (long long)n * HW * cw + (c >> 5);
             for (int i = 0; i < HW; ++i) s += ((b[(long long)i * cw] >> (c & 31)) & 1u) ? 1 : -1;
-            if (pooled_out != nullptr) pooled_out[(long long)n * C + c] = s;
+            if (pooled_out != nullptr && blockIdx.y == 0) pooled_out[(long long)n * C + c] = s;
         }
         pooled[im][c] = (float)s / inv;
     }
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int j = wave; j < J; j += 4) {
+    for (int j = j0 + wave; j < min(j0 + HEAD_OUTS, J); j += 4) {
         float part[HEAD_IMGS];
 #pragma unroll
         for (int im = 0; im < HEAD_IMGS; ++im) part[im] = 0.f;
@@ -183,20 +238,16 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
                         int N, int H, int W, int C, int O, int k, int stride, int pad, hipStream_t s) {
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
     const long long npix = (long long)N * P * Q;
-    dim3 grid((unsigned)cdiv(npix, 64), (unsigned)cdiv(O, 64));
+    dim3 grid((unsigned)cdiv(npix, 4 * STEM_MT * 32), (unsigned)cdiv(O, STEM_NT * 32));
     hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), 0, s, x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q);
-    int rc = check_launch();
-    if (rc == BNN_OK && bits != nullptr && (O % 32) != 0 && (O % 32) <= 16) {
-        hipLaunchKernelGGL(conv_f32_padfix_kernel, dim3((unsigned)cdiv(npix, 256)), dim3(256), 0, s, bits, npix, O);
-        rc = check_launch();
-    }
-    return rc;
+    return check_launch();
 }
 
 int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,
                     hipStream_t s) {
     if (C > HEAD_MAXC) return BNN_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)cdiv(N, HEAD_IMGS)), dim3(256), 0, s, bits, w, y, pooled, N, HW, C, J);
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)cdiv(N, HEAD_IMGS), (unsigned)cdiv(J, HEAD_OUTS)), dim3(256), 0, s, bits, w, y,
+                       pooled, N, HW, C, J);
     return check_launch();
 }
 

@@ -30,6 +30,8 @@ struct Geom {
 struct Epi {
     int32_t* out;          // out[row*ldc + col] = v (+ residual)
     const int32_t* resid;  // residual[row*ldc + col], added before the threshold (Sec. 6.1)
+    const uint32_t* resid_bits;  // alternative residual: +1/-1 of bit col of resid_bits[row*ld_resid_bits_w + col/32]
+    int ld_resid_bits_w;
     int ldc;               // elements between rows of out / resid
     const int32_t* thr;    // thr[col]: bit = (v >= thr[col])
     uint32_t* bits;        // bits[row*ldbits_w + col/32]

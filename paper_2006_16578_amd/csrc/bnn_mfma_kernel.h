@@ -253,7 +253,7 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
         thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
     }
 
-    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && !row_corr) {
+    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && e.resid_bits == nullptr && !row_corr) {
         // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
         // by the pad correction; one v_cmp per accumulator register gives two packed words.
         float thf[NT];
@@ -295,6 +295,35 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
         for (int j = 0; j < NT; ++j) wout[j] = 0u;
         const long long rbase = m0 + 32 * i;
         if (rbase >= g.rows) break;                              // uniform per wave
+        // Residual of this 32-row slab: every load is issued before the first store, so the
+        // memory latency is paid once per slab and not once per element.  (sum_out may alias
+        // residual_in: each element is still read before the same thread writes it.)
+        int rv[16][NT];
+        if (e.resid != nullptr || e.resid_bits != nullptr) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
+                const bool rok = row < g.rows;
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int col = n0 + 32 * j + l32;
+                    rv[r][j] = 0;
+                    if (rok && cok[j]) {
+                        if (e.resid != nullptr) {
+                            rv[r][j] = e.resid[row * (long long)e.ldc + col];
+                        } else {       // +1/-1 taken from a packed tensor (first residual of a chain)
+                            const uint32_t w = e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)];
+                            rv[r][j] = ((w >> (col & 31)) & 1u) ? 1 : -1;
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) rv[r][j] = 0;
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int rloc = 8 * (r >> 2) + 4 * half + (r & 3);
@@ -314,10 +343,8 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 const int col = n0 + 32 * j + l32;
-                int v = (int)acc[i][j][r] - corr;
-                const long long idx = row * (long long)e.ldc + col;
-                if (e.resid != nullptr && rok && cok[j]) v += e.resid[idx];
-                if (e.out != nullptr && rok && cok[j]) e.out[idx] = v;
+                const int v = (int)acc[i][j][r] - corr + rv[r][j];
+                if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = v;
                 if (e.bits != nullptr) {
                     const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
                     const int lo_row = 8 * (r >> 2) + (r & 3);

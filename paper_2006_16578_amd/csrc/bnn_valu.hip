@@ -109,6 +109,8 @@ __global__ __launch_bounds__(256) void valu_kernel(const uint32_t* __restrict__ 
         if (col < g.cols) {
             int v = nbits - 2 * (int)acc[j];
             if (e.resid != nullptr) v += e.resid[obase + col];
+            else if (e.resid_bits != nullptr)
+                v += ((e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)] >> (col & 31)) & 1u) ? 1 : -1;
             if (e.out != nullptr) e.out[obase + col] = v;
             if (e.thr != nullptr && v >= e.thr[col]) word |= (1u << j);
         }

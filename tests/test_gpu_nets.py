@@ -105,3 +105,20 @@ def test_resnet18_head_pooled(bnn, orc):
     ref = orc.head_fc_f32(pr, w, 49.0)
     tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
     assert (np.abs(host(y) - ref) <= tol).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
+                                   (2, 32, 32, 3, 64, 7, 4, 3), (1, 8, 8, 2, 33, 1, 1, 0)])
+def test_conv_f32_shapes(bnn, orc, shape):
+    N, H, W, C, O, k, st, pad = shape
+    rng = np.random.default_rng(sum(shape))
+    x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
+    w = rng.normal(0, 0.05, size=(O, k, k, C)).astype(np.float32)
+    thr = rng.normal(0, 0.05, size=O).astype(np.float32)
+    bits, y = bnn.conv_f32_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad, want_f32=True)
+    ref = orc.conv_f32(x, w, st, pad)
+    tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
+    assert host(y).shape == ref.shape
+    assert (np.abs(host(y) - ref) <= tol).all()
+    # the bits are exactly the GPU's own fp32 values thresholded, pad bits zero
+    assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
