@@ -36,6 +36,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-extras", action="store_true", help="only the BMM sweep (for profiling runs)")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--path", choices=["auto", "valu", "mfma"], default="auto", help="arithmetic path (profiling runs)")
+    ap.add_argument("--shapes", default="", help="comma-separated subset of the sweep, e.g. sq8192 (profiling runs)")
+    ap.add_argument("--variant", choices=["both", "bits", "int32"], default="both", help="epilogues to run (profiling runs)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="only run a plain device copy of this many MiB three times (calibrates the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
@@ -57,26 +62,44 @@ def main() -> int:
         a = np.ascontiguousarray(a)
         return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
 
+    if args.calib_copy_mib > 0:
+        n = args.calib_copy_mib << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read": n, "bytes_written": n, "launches": 3}))
+        return 0
+
     # ------------------------------------------------------------------ BMM sweep, resident in HBM
+    path = {"auto": bnn.PATH_AUTO, "valu": bnn.PATH_VALU, "mfma": bnn.PATH_MFMA}[args.path]
+    only = [t for t in args.shapes.split(",") if t]
+    do_bits, do_i32 = args.variant in ("both", "bits"), args.variant in ("both", "int32")
     shapes = []
     for name, M, N, K, _ in wl.cfg2_shapes():
+        if only and name not in only:
+            continue
         case = wl.cfg2_case(name)
         A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
         Cb = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
         C = torch.empty((M, N), dtype=torch.int32, device=dev)
         shapes.append({"name": name, "M": M, "N": N, "K": K, "A": A, "B": B, "tau": tau, "Cb": Cb, "C": C,
-                       "kernel": bnn.bmm_kernel_name(M, N, K), "t_thr": [], "t_i32": []})
-    macs_step = sum(2.0 * s["M"] * s["N"] * s["K"] for s in shapes)          # both variants
+                       "kernel": bnn.bmm_kernel_name(M, N, K, path), "t_thr": [], "t_i32": []})
+    macs_step = sum((do_bits + do_i32) * float(s["M"]) * s["N"] * s["K"] for s in shapes)
 
     def one_step(record: bool):
         for s in shapes:
             if record:
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record()
-            bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"])
+            if do_bits:
+                bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path)
             if record:
                 e1.record()
-            bnn.bmm(s["A"], s["B"], s["K"], out=s["C"])
+            if do_i32:
+                bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path)
             if record:
                 e2.record()
                 s["ev"].append((e0, e1, e2))
@@ -96,8 +119,8 @@ def main() -> int:
 
     per_shape = []
     for s in shapes:
-        thr_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]]))
-        i32_ms = float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]]))
+        thr_ms = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9)
+        i32_ms = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9)
         ops = 2.0 * s["M"] * s["N"] * s["K"]
         kw = wl.nwords(s["K"]) * 4
         bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
@@ -114,9 +137,9 @@ def main() -> int:
     by_kernel = {}
     for s, ps in zip(shapes, per_shape):
         d = by_kernel.setdefault(s["kernel"], {"ms": 0.0, "flop": 0.0, "launches": 0})
-        d["ms"] += ps["bits_out_ms"] + ps["int32_out_ms"]
-        d["flop"] += 2 * 2.0 * s["M"] * s["N"] * s["K"]
-        d["launches"] += 2
+        d["ms"] += do_bits * ps["bits_out_ms"] + do_i32 * ps["int32_out_ms"]
+        d["flop"] += (do_bits + do_i32) * 2.0 * s["M"] * s["N"] * s["K"]
+        d["launches"] += do_bits + do_i32
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     dk = by_kernel[dom]
     achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
@@ -141,7 +164,8 @@ def main() -> int:
         "dtype": "u1 (+1/-1 bits as fp4 E2M1 on the matrix cores, fp32/int32 accumulate)", "data": "synthetic",
         "config": {"workload": "BMM sweep (config 2): square n in {2048,4096,8192,16384} + FC M in {8,128,1024} x "
                                "K=4096 x N=4096; each shape with fused threshold->bits and with int32 output; "
-                               "uniform random bits, seeded", "path": "auto"},
+                               "uniform random bits, seeded", "path": args.path,
+                   "shapes": args.shapes or "all", "variant": args.variant},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "bmm_shapes": per_shape,
