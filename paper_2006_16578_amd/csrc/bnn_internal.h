@@ -40,6 +40,7 @@ struct Epi {
 
 int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+int launch_mfma_conv_staged(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v4(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v2(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v1(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);

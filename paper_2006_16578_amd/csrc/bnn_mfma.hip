@@ -1,25 +1,54 @@
-// Matrix-core path, dispatch and the BMM instantiations (the kernel is in bnn_mfma_kernel.h).
-#include "bnn_mfma_kernel.h"
+// Matrix-core path: dispatch and the BMM instantiations (kernels are in bnn_mfma_kernel.h and
+// bnn_mfma_staged.h).
+#include "bnn_mfma_staged.h"
 
 namespace bnn {
 
+namespace {
+
+// The LDS-staged kernel covers every BMM (rows are padded to 128 bits) and the convolutions whose
+// pixels are 8 bytes or a multiple of 16 bytes with -1 padding; the smallest tile, exclude
+// padding and other channel counts use the direct kernel.
+bool staged_ok(const Geom& g, int tile) {
+    if (tile == 3) return false;
+    if (!g.conv) return true;
+    // short K (few slabs): the direct kernel has less fixed cost per workgroup
+    return !g.excl && g.bits_tap == g.tw * 32 && (g.tw % 4 == 0 || g.tw == 2) && g.taps * g.tw >= 64;
+}
+
+}  // namespace
+
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    const int tile = mfma::pick_tile(g);
     if (!g.conv) {
+        if (staged_ok(g, tile)) {
+            switch (tile) {
+                case 0: return mfma::launch_staged_tile<mfma::TileBig, 16, false>(A, B, g, e, s);
+                case 1: return mfma::launch_staged_tile<mfma::TileTall, 16, false>(A, B, g, e, s);
+                default: return mfma::launch_staged_tile<mfma::TileMid, 16, false>(A, B, g, e, s);
+            }
+        }
         // tw is a multiple of 4 words; a chunk is 8 words, so an odd number of 4-word groups
         // leaves the upper half-wave without data in the last chunk -> guarded variant
         if (g.tw % 8 == 0) return mfma::launch_shape<4, false, false>(A, B, g, e, s);
         return mfma::launch_shape<4, false, true>(A, B, g, e, s);
     }
+    if (staged_ok(g, tile)) return launch_mfma_conv_staged(A, B, g, e, s);
     if (g.tw % 8 == 0) return launch_mfma_conv_v4(A, B, g, e, s);
     if (g.tw % 4 == 0) return launch_mfma_conv_v2(A, B, g, e, s);
     return launch_mfma_conv_v1(A, B, g, e, s);
 }
 
 const char* describe_mfma(const Geom& g) {
-    switch (mfma::pick_tile(g)) {
-        case 0: return g.conv ? "mfma_fp4_conv_wg256x128" : "mfma_fp4_bmm_wg256x128";
-        case 1: return g.conv ? "mfma_fp4_conv_wg512x64" : "mfma_fp4_bmm_wg512x64";
-        case 2: return g.conv ? "mfma_fp4_conv_wg128x128" : "mfma_fp4_bmm_wg128x128";
+    const int tile = mfma::pick_tile(g);
+    const bool st = staged_ok(g, tile);
+    switch (tile) {
+        case 0: return g.conv ? (st ? "mfma_fp4_conv_lds_wg256x128" : "mfma_fp4_conv_wg256x128")
+                              : "mfma_fp4_bmm_lds_wg256x128";
+        case 1: return g.conv ? (st ? "mfma_fp4_conv_lds_wg512x64" : "mfma_fp4_conv_wg512x64")
+                              : "mfma_fp4_bmm_lds_wg512x64";
+        case 2: return g.conv ? (st ? "mfma_fp4_conv_lds_wg128x128" : "mfma_fp4_conv_wg128x128")
+                              : "mfma_fp4_bmm_lds_wg128x128";
         default: return g.conv ? "mfma_fp4_conv_wg64x64" : "mfma_fp4_bmm_wg64x64";
     }
 }

@@ -78,7 +78,7 @@ struct Tile {
 };
 typedef Tile<4, 2, 2, 2, 2> TileBig;    // 256 x 128
 typedef Tile<4, 2, 4, 1, 2> TileTall;   // 512 x 64   (at most 64 output columns)
-typedef Tile<2, 2, 2, 2, 4> TileMid;    // 128 x 128
+typedef Tile<2, 2, 2, 2, 3> TileMid;    // 128 x 128
 typedef Tile<1, 1, 2, 2, 4> TileSmall;  // 64 x 64
 
 // Workgroup id -> tile coordinates.  Consecutive workgroup ids are dealt round-robin to the 8
@@ -100,6 +100,152 @@ __device__ __forceinline__ bool tile_coords(int gx, int gy, int& bx, int& by) {
     by = in / gsz;
     bx = first + (in - by * gsz);
     return true;
+}
+
+// Generic epilogue body: optional residual (int32 tensor or +1/-1 from packed bits), optional int32
+// store, optional threshold + pack.
+template <int MT, int NT, bool CONV, bool EXCL, bool HAS_RESID>
+__device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
+                                                 const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
+                                                 const int (&thi)[NT], const bool (&cok)[NT], const bool row_corr) {
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wout[j] = 0u;
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= g.rows) break;                              // uniform per wave
+        // Residual of this 32-row slab: every load is issued before the first store, so the
+        // memory latency is paid once per slab and not once per element.  (sum_out may alias
+        // residual_in: each element is still read before the same thread writes it.)
+        int rv[16][NT];
+        if (HAS_RESID) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
+                const bool rok = row < g.rows;
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int col = n0 + 32 * j + l32;
+                    rv[r][j] = 0;
+                    if (rok && cok[j]) {
+                        if (e.resid != nullptr) {
+                            rv[r][j] = e.resid[row * (long long)e.ldc + col];
+                        } else {       // +1/-1 taken from a packed tensor (first residual of a chain)
+                            const uint32_t w = e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)];
+                            rv[r][j] = ((w >> (col & 31)) & 1u) ? 1 : -1;
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) rv[r][j] = 0;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rloc = 8 * (r >> 2) + 4 * half + (r & 3);
+            const long long row = rbase + rloc;
+            const bool rok = row < g.rows;
+            int corr = corr_all;
+            if (row_corr) {
+                const long long rr = rok ? row : g.rows - 1;
+                const int pq = g.P * g.Q;
+                const int rem = (int)(rr % pq);
+                const int p = rem / g.Q, q = rem - p * g.Q;
+                const int ylo = p * g.stride - g.pad, xlo = q * g.stride - g.pad;
+                const int vy = min(ylo + g.k, g.H) - max(ylo, 0);
+                const int vx = min(xlo + g.k, g.W) - max(xlo, 0);
+                corr = vy * vx * pad_tap;
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int col = n0 + 32 * j + l32;
+                const int v = (int)acc[i][j][r] - corr + (HAS_RESID ? rv[r][j] : 0);
+                if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = v;
+                if (e.bits != nullptr) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
+                    const int lo_row = 8 * (r >> 2) + (r & 3);
+                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+                }
+            }
+        }
+        if (e.bits != nullptr && lane < 32) {
+            const long long row = rbase + lane;
+            if (row < g.rows) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                }
+            }
+        }
+    }
+}
+
+// Epilogue shared by the matrix-core kernels.  acc holds, as exact integers in fp32, the sums
+// over every processed bit position; positions beyond the logical width are 0 bits in both
+// operands and have contributed (+1)(+1) = +1 each: corr_all of them per output (in exclude mode
+// only in-frame taps did: pad_tap per in-frame tap).  Then: optional residual add and int32
+// store, threshold compare, and packing through wave ballots.
+template <int MT, int NT, bool CONV, bool EXCL>
+__device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
+                                         const Geom& g, const Epi& e, const int corr_all, const int pad_tap) {
+    const int l32 = lane & 31;
+    const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
+
+    int thi[NT];           // threshold of this lane's column; INT_MAX (never reached) outside the matrix
+    bool cok[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < g.cols;
+        thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
+    }
+
+    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && e.resid_bits == nullptr && !row_corr) {
+        // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
+        // by the pad correction; one v_cmp per accumulator register gives two packed words.
+        float thf[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)(thi[j] + corr_all) : __builtin_inff();
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const long long rbase = m0 + 32 * i;
+            if (rbase >= g.rows) break;                          // uniform per wave
+            uint32_t wout[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lo_row = 8 * (r >> 2) + (r & 3);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(acc[i][j][r] >= thf[j]);
+                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+                }
+            }
+            const long long row = rbase + lane;
+            if (lane < 32 && row < g.rows) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                }
+            }
+        }
+        return;
+    }
+    if (e.resid != nullptr || e.resid_bits != nullptr)
+        epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
+    else
+        epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
 }
 
 // V: words each lane loads per fragment and chunk (a chunk is 2*V words = V MFMA K-steps);
@@ -237,133 +383,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
         }
     }
 
-    // ---- epilogue --------------------------------------------------------------------------
-    // Every processed bit position beyond the logical width is a 0 bit in both operands and has
-    // contributed (+1)(+1) = +1: remove them.  In exclude mode only in-frame taps did.
+    // Every processed bit position beyond the logical width is a 0 bit in both operands.
     const int pad_tap = cpt * 2 * V * 32 - g.bits_tap;
-    const int corr_all = g.taps * pad_tap;
-    const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
-
-    int thi[NT];           // threshold of this lane's column; INT_MAX (never reached) outside the matrix
-    bool cok[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int col = n0 + 32 * j + l32;
-        cok[j] = col < g.cols;
-        thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
-    }
-
-    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && e.resid_bits == nullptr && !row_corr) {
-        // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
-        // by the pad correction; one v_cmp per accumulator register gives two packed words.
-        float thf[NT];
-#pragma unroll
-        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)(thi[j] + corr_all) : __builtin_inff();
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            const long long rbase = m0 + 32 * i;
-            if (rbase >= g.rows) break;                          // uniform per wave
-            uint32_t wout[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) wout[j] = 0u;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lo_row = 8 * (r >> 2) + (r & 3);
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(acc[i][j][r] >= thf[j]);
-                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
-                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
-                }
-            }
-            const long long row = rbase + lane;
-            if (lane < 32 && row < g.rows) {
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const int wi = (n0 >> 5) + j;
-                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
-                }
-            }
-        }
-        return;
-    }
-
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        uint32_t wout[NT];
-#pragma unroll
-        for (int j = 0; j < NT; ++j) wout[j] = 0u;
-        const long long rbase = m0 + 32 * i;
-        if (rbase >= g.rows) break;                              // uniform per wave
-        // Residual of this 32-row slab: every load is issued before the first store, so the
-        // memory latency is paid once per slab and not once per element.  (sum_out may alias
-        // residual_in: each element is still read before the same thread writes it.)
-        int rv[16][NT];
-        if (e.resid != nullptr || e.resid_bits != nullptr) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
-                const bool rok = row < g.rows;
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const int col = n0 + 32 * j + l32;
-                    rv[r][j] = 0;
-                    if (rok && cok[j]) {
-                        if (e.resid != nullptr) {
-                            rv[r][j] = e.resid[row * (long long)e.ldc + col];
-                        } else {       // +1/-1 taken from a packed tensor (first residual of a chain)
-                            const uint32_t w = e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)];
-                            rv[r][j] = ((w >> (col & 31)) & 1u) ? 1 : -1;
-                        }
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-#pragma unroll
-                for (int j = 0; j < NT; ++j) rv[r][j] = 0;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int rloc = 8 * (r >> 2) + 4 * half + (r & 3);
-            const long long row = rbase + rloc;
-            const bool rok = row < g.rows;
-            int corr = corr_all;
-            if (row_corr) {
-                const long long rr = rok ? row : g.rows - 1;
-                const int pq = g.P * g.Q;
-                const int rem = (int)(rr % pq);
-                const int p = rem / g.Q, q = rem - p * g.Q;
-                const int ylo = p * g.stride - g.pad, xlo = q * g.stride - g.pad;
-                const int vy = min(ylo + g.k, g.H) - max(ylo, 0);
-                const int vx = min(xlo + g.k, g.W) - max(xlo, 0);
-                corr = vy * vx * pad_tap;
-            }
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const int col = n0 + 32 * j + l32;
-                const int v = (int)acc[i][j][r] - corr + rv[r][j];
-                if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = v;
-                if (e.bits != nullptr) {
-                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
-                    const int lo_row = 8 * (r >> 2) + (r & 3);
-                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
-                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
-                }
-            }
-        }
-        if (e.bits != nullptr && lane < 32) {
-            const long long row = rbase + lane;
-            if (row < g.rows) {
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const int wi = (n0 >> 5) + j;
-                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
-                }
-            }
-        }
-    }
+    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap, pad_tap);
 }
 
 template <class TL, int V, bool CONV, bool GUARD>

@@ -95,6 +95,15 @@ def test_resnet18_batch8(bnn, orc):
     check_resnet(bnn, orc, p, x, 224, 0, tier=1)
 
 
+def test_resnet18_batch256(bnn, orc):
+    # the configuration bench.py times (batch 256, automatic path); full comparison of every
+    # block's bits against the packed tier-1 oracle chain (tier 1 == tier 0 is pinned on CPU and
+    # re-checked above at batch 8 sizes by the small-network test)
+    p = wl.resnet18_params()
+    x = wl.resnet18_input(256)
+    check_resnet(bnn, orc, p, x, 224, 0, tier=1)
+
+
 def test_resnet18_head_pooled(bnn, orc):
     rng = np.random.default_rng(12)
     bits = wl.random_bits(rng, (9, 7, 7), 512)
