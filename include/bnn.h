@@ -138,7 +138,8 @@ int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_
                      int N, int H, int W, int C, int O, int k, int stride, int pad, void* stream);
 /* pooled[n][c] = sum over HW positions of the +1/-1 value of channel c (exact integer);
  * y[n][j] = sum_c (pooled[n][c] / HW) * w[j][c].
- *   bits [N][HW][ceil(C/32)], w [J][C] fp32, y [N][J] fp32, pooled_out [N][C] int32 or NULL. */
+ *   bits [N][HW][ceil(C/32)], w [J][C] fp32, y [N][J] fp32, pooled_out [N][C] int32 or NULL.
+ *   HW <= 255 and C <= 1024, else BNN_ERR_UNSUPPORTED. */
 int bnn_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled_out,
                  int N, int HW, int C, int J, void* stream);
 
@@ -166,7 +167,9 @@ int bnn_net_add_conv(bnn_net* net, const uint32_t* filt, const int32_t* thr,
                      int C, int O, int k, int stride, int pad, int pad_mode);
 /* Residual basic block: h = thr1(conv3x3(x, W1, stride, pad 1)); S = conv3x3(h, W2, 1, pad 1) + shortcut;
  * y = (S >= thr2); the running residual becomes S.  shortcut = running residual when Wd == NULL
- * (needs stride 1, cin == cout), else conv1x1(x, Wd, stride, pad 0). */
+ * (needs stride 1, cin == cout; the first such block of a chain uses the +1/-1 values of its input
+ * bits), else conv1x1(x, Wd [cout][1][1][ceil(cin/32)], stride, pad 0), which is computed inside the
+ * second convolution's kernel as extra terms of the same sums. */
 int bnn_net_add_block(bnn_net* net, const uint32_t* W1, const int32_t* thr1,
                       const uint32_t* W2, const int32_t* thr2, const uint32_t* Wd,
                       int cin, int cout, int stride, int pad_mode);

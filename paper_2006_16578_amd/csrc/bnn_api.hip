@@ -58,7 +58,9 @@ int conv_shape(int N, int H, int W, int C, int O, int k, int stride, int pad, in
 // values are the residual, instead of an int32 tensor.
 int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const int32_t* resid,
                  const int32_t* thr, uint32_t* bits, int N, int H, int W, int C, int O, int k, int stride,
-                 int pad, int pad_mode, int path, void* stream, const uint32_t* resid_bits = nullptr) {
+                 int pad, int pad_mode, int path, void* stream, const uint32_t* resid_bits = nullptr,
+                 const uint32_t* x2 = nullptr, const uint32_t* filt2 = nullptr, int H2 = 0, int W2 = 0, int C2 = 0,
+                 int stride2 = 1) {
     if (!in || !filt) return BNN_ERR_INVALID_ARG;
     if (!out && !bits) return BNN_ERR_INVALID_ARG;
     if (bits && !thr) return BNN_ERR_INVALID_ARG;
@@ -74,6 +76,10 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
     g.lda_w = cw; g.ldb_w = k * k * cw;
     g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad;
     g.excl = (pad_mode == BNN_PAD_EXCLUDE) ? 1 : 0;
+    if (x2 != nullptr) {    // fused 1x1 shortcut convolution (internal callers only; shapes already checked)
+        if (!filt2 || C2 < 1 || stride2 < 1 || (P - 1) * stride2 >= H2 || (Q - 1) * stride2 >= W2) return BNN_ERR_INVALID_ARG;
+        g.A2 = x2; g.B2 = filt2; g.H2 = H2; g.W2 = W2; g.cw2 = words(C2); g.stride2 = stride2; g.bits2 = C2;
+    }
     Epi e = {};
     e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O);
     e.resid_bits = resid ? nullptr : resid_bits; e.ld_resid_bits_w = words(O);
@@ -420,12 +426,9 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                                       net->layers[i + 1].w2 == nullptr;
                 const int32_t* shortcut = nullptr;
                 const uint32_t* shortcut_bits = nullptr;
-                if (L.w2) {     // 1x1 binarized downsample of the block input (int32)
-                    int32_t* sc = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 2) % 3]);
-                    rc = bnn_bconv_ex(cur, static_cast<const uint32_t*>(L.w2), sc, batch, curH, curW, curC, L.b, 1,
-                                      L.stride, 0, L.pad_mode, path, stream);
-                    if (rc != BNN_OK) return rc;
-                    shortcut = sc;
+                const uint32_t* x2 = nullptr;
+                if (L.w2) {     // 1x1 binarized downsample of the block input: fused into the second conv
+                    x2 = cur;
                 } else if (R) {
                     shortcut = R;
                 } else {        // first block of a chain: the residual is the +1/-1 values of its input bits
@@ -437,8 +440,9 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 if (rc != BNN_OK) return rc;
                 rc = bconv_common(hbits, static_cast<const uint32_t*>(L.w1), keep_sum ? Rnew : nullptr, shortcut,
                                   static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
-                                  L.pad_mode, path, stream, shortcut_bits);
-                R = Rnew; rslot = (rslot + 1) % 3;
+                                  L.pad_mode, path, stream, shortcut_bits, x2, static_cast<const uint32_t*>(L.w2), curH, curW,
+                                  curC, L.stride);
+                R = keep_sum ? Rnew : nullptr; rslot = (rslot + 1) % 3;
                 obits = ybits;
                 break;
             }

@@ -161,11 +161,12 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
 }
 
 // Head: exact integer sum-pool of +1/-1 over HW positions, then fp32 FC.  A workgroup handles
-// HEAD_IMGS images and HEAD_OUTS output rows: it pools its images into LDS (cheap: a few KB of
-// bits), then each wave takes output rows in turn, lanes stride over channels, and a butterfly
-// reduction finishes each dot product.
-constexpr int HEAD_IMGS = 8;
-constexpr int HEAD_OUTS = 32;
+// HEAD_IMGS images and HEAD_OUTS output rows.  Pooling: a thread owns one packed word (32
+// channels) of one image and counts set bits per channel over the HW positions, 4 channels at a
+// time in the bytes of one register (HW <= 255); the sum of +1/-1 is 2 * count - HW.  FC: a wave
+// per output row, lanes stride over channels, butterfly reduction.
+constexpr int HEAD_IMGS = 4;
+constexpr int HEAD_OUTS = 128;
 constexpr int HEAD_MAXC = 1024;
 
 __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ bits, const float* __restrict__ w,
@@ -176,16 +177,32 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
     const int j0 = blockIdx.y * HEAD_OUTS;
     const int cw = (C + 31) / 32;
     const float inv = (float)HW;
-    for (int idx = threadIdx.x; idx < HEAD_IMGS * C; idx += blockDim.x) {
-        const int im = idx / C, c = idx - im * C;
+    for (int idx = threadIdx.x; idx < HEAD_IMGS * cw; idx += blockDim.x) {
+        const int im = idx / cw, wi = idx - im * cw;
         const int n = n0 + im;
-        int s = 0;
+        uint32_t cnt[8];                       // cnt[q] byte b = number of set bits of channel 4*q... see below
+#pragma unroll
+        for (int q = 0; q < 8; ++q) cnt[q] = 0u;
         if (n < N) {
-            const uint32_t* b = bits + (long long)n * HW * cw + (c >> 5);
-            for (int i = 0; i < HW; ++i) s += ((b[(long long)i * cw] >> (c & 31)) & 1u) ? 1 : -1;
-            if (pooled_out != nullptr && blockIdx.y == 0) pooled_out[(long long)n * C + c] = s;
+            const uint32_t* b = bits + (long long)n * HW * cw + wi;
+            for (int i = 0; i < HW; ++i) {
+                const uint32_t v = b[(long long)i * cw];
+                // bit (q + 8*t) of v is added to byte t of cnt[q]
+#pragma unroll
+                for (int q = 0; q < 8; ++q) cnt[q] += (v >> q) & 0x01010101u;
+            }
         }
-        pooled[im][c] = (float)s / inv;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = wi * 32 + q + 8 * t;
+                if (c < C) {
+                    const int s = (n < N) ? 2 * (int)((cnt[q] >> (8 * t)) & 0xFFu) - HW : 0;
+                    if (pooled_out != nullptr && blockIdx.y == 0 && n < N) pooled_out[(long long)n * C + c] = s;
+                    pooled[im][c] = (float)s / inv;
+                }
+            }
     }
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -245,7 +262,7 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
 
 int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,
                     hipStream_t s) {
-    if (C > HEAD_MAXC) return BNN_ERR_UNSUPPORTED;
+    if (C > HEAD_MAXC || HW > 255) return BNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(head_kernel, dim3((unsigned)cdiv(N, HEAD_IMGS), (unsigned)cdiv(J, HEAD_OUTS)), dim3(256), 0, s, bits, w, y,
                        pooled, N, HW, C, J);
     return check_launch();

@@ -24,6 +24,13 @@ struct Geom {
     // convolution geometry (Sec. 5.3)
     int H, W, P, Q, k, stride, pad;
     int excl;        // 1: out-of-frame taps contribute nothing; 0: they count as -1
+    // Optional second source, accumulated into the same sums: a 1x1 convolution (no padding) of
+    // a second packed tensor A2 [N][H2][W2][cw2] sampled at (p*stride2, q*stride2) with filters
+    // B2 [cols][cw2] -- the binarized downsample shortcut of a residual block, fused so that its
+    // int32 output never exists in memory.  A2 == nullptr: none.
+    const uint32_t* A2;
+    const uint32_t* B2;
+    int H2, W2, cw2, stride2, bits2;
 };
 
 // What happens to each finished sum v[row][col] (all pointers may be null except as noted).

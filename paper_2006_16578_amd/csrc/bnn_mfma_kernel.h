@@ -248,6 +248,45 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
 }
 
+// The optional second source of a Geom (fused 1x1 downsample shortcut): a handful of K-steps read
+// straight from global memory.  Returns the number of bit positions it multiplied.
+template <int MT, int NT>
+__device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, const long long m0, const int n0,
+                                            const int lane, const uint32_t c2) {
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+    const uint32_t* ar[MT];
+    const uint32_t* br[NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        long long row = m0 + 32 * i + l32;
+        if (row > g.rows - 1) row = g.rows - 1;
+        const int pq = g.P * g.Q;
+        const int n = (int)(row / pq);
+        const int rem = (int)(row - (long long)n * pq);
+        const int p = rem / g.Q, q = rem - p * g.Q;
+        ar[i] = g.A2 + (((long long)n * g.H2 + p * g.stride2) * g.W2 + q * g.stride2) * g.cw2;
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) br[j] = g.B2 + (long long)min(n0 + 32 * j + l32, g.cols - 1) * g.cw2;
+    const int steps = (g.cw2 + 1) / 2;
+    for (int ks = 0; ks < steps; ++ks) {
+        const int wo = 2 * ks + half;
+        const bool ok = wo < g.cw2;
+        v8i ea[MT], eb[NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) { const uint32_t w = ar[i][ok ? wo : 0]; ea[i] = expand_fp4(ok ? w : 0u, c2); }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) { const uint32_t w = br[j][ok ? wo : 0]; eb[j] = expand_fp4(ok ? w : 0u, c2); }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 0, 0, 0);
+    }
+    return steps * 64;
+}
+
 // V: words each lane loads per fragment and chunk (a chunk is 2*V words = V MFMA K-steps);
 // CONV: rows are output pixels gathered through the filter window; EXCL: out-of-frame taps
 // contribute nothing; GUARD: the last chunk of a tap may run past tw.
@@ -385,7 +424,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
 
     // Every processed bit position beyond the logical width is a 0 bit in both operands.
     const int pad_tap = cpt * 2 * V * 32 - g.bits_tap;
-    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap, pad_tap);
+    int corr2 = 0;
+    if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
+    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap);
 }
 
 template <class TL, int V, bool CONV, bool GUARD>

@@ -222,7 +222,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
     const int n0 = n_base + wn * (NT * 32);
     // bit positions multiplied in all: 64 per K-step
     const int processed = (nslabs - 1) * 512 + (last0 + last1) * 64;
-    epilogue<MT, NT, CONV, false>(acc, m0, n0, lane, g, e, processed - g.taps * g.bits_tap, 0);
+    int corr2 = 0;
+    if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
+    epilogue<MT, NT, CONV, false>(acc, m0, n0, lane, g, e, processed - g.taps * g.bits_tap + corr2, 0);
 }
 
 template <class TL, int U, bool CONV>

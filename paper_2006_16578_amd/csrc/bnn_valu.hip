@@ -98,8 +98,25 @@ __global__ __launch_bounds__(256) void valu_kernel(const uint32_t* __restrict__ 
         }
     }
 
+    int nbits2 = 0;
+    if (CONV && g.A2 != nullptr) {      // fused 1x1 shortcut convolution of a second tensor, always in frame
+        const int pq = g.P * g.Q;
+        const int n = (int)(row / pq);
+        const int rem = (int)(row - (long long)n * pq);
+        const int p = rem / g.Q, q = rem - p * g.Q;
+        const uint32_t* a2 = g.A2 + (((long long)n * g.H2 + p * g.stride2) * g.W2 + q * g.stride2) * g.cw2;
+        for (int w = 0; w < g.cw2; ++w) {
+            const uint32_t a = a2[w];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int col = min(col0 + j, g.cols - 1);
+                acc[j] += __builtin_popcount(a ^ g.B2[(long long)col * g.cw2 + w]);
+            }
+        }
+        nbits2 = g.bits2;
+    }
     // v = n - 2 * popc  (Eq. 2); n counts only in-frame taps in exclude mode (Sec. 5.3)
-    const int nbits = (EXCL ? nvalid : g.taps) * g.bits_tap;
+    const int nbits = (EXCL ? nvalid : g.taps) * g.bits_tap + nbits2;
     if (!row_ok) return;
     const long long obase = row * (long long)e.ldc;
     uint32_t word = 0u;
