@@ -46,13 +46,17 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
 // First layer: fp32 convolution with zero padding, then per-channel threshold -> bits, as an
 // implicit GEMM on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): rows are output pixels,
 // columns output channels, and K runs over the k filter rows times the k*C contiguous floats of
-// one filter row -- contiguous in the NHWC input as well, so lane l of a wave reads element
-// 2*t + l/32 of the row segment of pixel l%32 with no index arithmetic beyond one bounds test.
-// A wave owns 2 x 2 accumulator tiles (64 pixels x 64 channels), a workgroup 256 pixels.
+// one filter row, which are contiguous in the NHWC input as well.  That segment is cut in blocks
+// of 24 floats; in a block the lower half-wave takes floats 0..11 and the upper one 12..23 (any
+// pairing of K indices is fine as long as both operands use it), so every lane reads a run of 12
+// consecutive floats with three 16-byte loads, a whole block ahead of the MFMAs that use it.
+// The 64 x k*k*C weights of the workgroup live in LDS.  A wave owns 2 x 2 accumulator tiles
+// (64 pixels x 64 channels), a workgroup 256 pixels.
 typedef float v16f_aux __attribute__((ext_vector_type(16)));
+typedef float float4_u __attribute__((ext_vector_type(4), aligned(4)));
 extern "C" __device__ int bnn_aux_writelane_i32(int val, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
 
-constexpr int STEM_MT = 2, STEM_NT = 2;
+constexpr int STEM_MT = 2, STEM_NT = 2, STEM_RUN = 12;
 
 __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                        const float* __restrict__ thr, float* __restrict__ y,
@@ -60,14 +64,44 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
                                                        int O, int k, int stride, int pad, int P, int Q) {
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5, wave = threadIdx.x >> 6;
     const long long npix = (long long)N * P * Q;
-    const long long m0 = ((long long)blockIdx.x * 4 + wave) * (STEM_MT * 32);
     const int n0 = (int)blockIdx.y * (STEM_NT * 32);
-    if (m0 >= npix) return;                                  // uniform per wave
     const int seg = k * C;                                   // floats in one filter row
-    const int steps = (seg + 1) / 2;
+    const int nblk = (seg + 2 * STEM_RUN - 1) / (2 * STEM_RUN);
     const int rowlen = W * C;
+    const long long total = (long long)N * H * rowlen;       // floats in x
 
-    const float* xrow[STEM_MT];     // start of input row y0 of this lane's pixel
+    // weights of this workgroup's 64 output channels -> LDS (row stride odd: 32 channels, 32 banks)
+    extern __shared__ float wlds[];
+    const int kkc = k * seg;
+    const int wstride = kkc | 1;
+    {
+        // 8 independent loads in flight per thread; channels past O repeat the last valid floats
+        // (their results are dropped)
+        const long long wbase = (long long)n0 * kkc, wlast = (long long)O * kkc - 1;
+        const int nelem = STEM_NT * 32 * kkc;
+        for (int base = 0; base < nelem; base += 8 * 256) {
+            float tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                tmp[u] = w[min(wbase + min(idx, nelem - 1), wlast)];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                if (idx < nelem) {
+                    const int c = idx / kkc;
+                    wlds[c * wstride + (idx - c * kkc)] = tmp[u];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    const long long m0 = ((long long)blockIdx.x * 4 + wave) * (STEM_MT * 32);
+    if (m0 >= npix) return;                                  // uniform per wave, after the barrier
+
+    long long xbase[STEM_MT];       // float index of input row 0 of this lane's image
     int xoff[STEM_MT], ytop[STEM_MT];
 #pragma unroll
     for (int i = 0; i < STEM_MT; ++i) {
@@ -78,11 +112,8 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
         const int p = rem / Q, q = rem - p * Q;
         ytop[i] = p * stride - pad;
         xoff[i] = (q * stride - pad) * C;
-        xrow[i] = x + (long long)n * H * rowlen;
+        xbase[i] = (long long)n * H * rowlen;
     }
-    const float* wrow[STEM_NT];
-#pragma unroll
-    for (int j = 0; j < STEM_NT; ++j) wrow[j] = w + (long long)min(n0 + 32 * j + l32, O - 1) * k * seg;
 
     v16f_aux acc[STEM_MT][STEM_NT];
 #pragma unroll
@@ -92,29 +123,82 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    for (int r = 0; r < k; ++r) {
-        for (int t = 0; t < steps; ++t) {
-            const int e = 2 * t + half;
-            const bool eok = e < seg;
-            float a[STEM_MT], b[STEM_NT];
+    // Loads the run of floats of filter row r, block blk, for every A fragment; positions that are
+    // padding (outside the image) become 0.  A block covers bl <= 24 floats of the segment, split
+    // evenly: the lower half-wave takes the first hs = ceil(bl/2), the upper one the rest.
+    auto fetch = [&](int r, int blk, float (&run)[STEM_MT][STEM_RUN]) {
+        const int bl = min(2 * STEM_RUN, seg - blk * (2 * STEM_RUN));
+        const int hs = (bl + 1) >> 1;
+        const int e0 = blk * (2 * STEM_RUN) + half * hs;             // first float of this lane's run
+        const int cnt = half ? bl - hs : hs;                         // floats of the run that exist
 #pragma unroll
-            for (int i = 0; i < STEM_MT; ++i) {
-                const int yy = ytop[i] + r;
-                const int xe = xoff[i] + e;
-                const bool ok = eok && (unsigned)yy < (unsigned)H && (unsigned)xe < (unsigned)rowlen;
-                const float v = xrow[i][ok ? (long long)yy * rowlen + xe : 0];
-                a[i] = ok ? v : 0.f;                         // zero padding
+        for (int i = 0; i < STEM_MT; ++i) {
+            const int yy = ytop[i] + r;
+            const bool yok = (unsigned)yy < (unsigned)H;
+            const long long start = xbase[i] + (long long)(yok ? yy : 0) * rowlen + xoff[i] + e0;
+            if (start >= 0 && start + STEM_RUN <= total) {           // the whole run lies inside the tensor
+                const float4_u v0 = *reinterpret_cast<const float4_u*>(x + start);
+                const float4_u v1 = *reinterpret_cast<const float4_u*>(x + start + 4);
+                const float4_u v2 = *reinterpret_cast<const float4_u*>(x + start + 8);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) { run[i][t] = v0[t]; run[i][4 + t] = v1[t]; run[i][8 + t] = v2[t]; }
+            } else {                                                 // first / last pixels of the tensor
+#pragma unroll
+                for (int t = 0; t < STEM_RUN; ++t) {
+                    const long long idx = start + t;
+                    run[i][t] = (idx >= 0 && idx < total) ? x[idx] : 0.f;
+                }
             }
+            // zero padding; skipped when every lane of the wave has its whole run inside the image
+            const int xs = xoff[i] + e0;
+            const bool inside = yok && xs >= 0 && xs + cnt <= rowlen && cnt == hs;
+            if (__builtin_amdgcn_ballot_w64(inside) != ~0ull) {
 #pragma unroll
-            for (int j = 0; j < STEM_NT; ++j) {
-                const float v = wrow[j][eok ? r * seg + e : 0];
-                b[j] = eok ? v : 0.f;
+                for (int t = 0; t < STEM_RUN; ++t) {
+                    const bool ok = yok && t < cnt && (unsigned)(xs + t) < (unsigned)rowlen;
+                    run[i][t] = ok ? run[i][t] : 0.f;
+                }
             }
+        }
+    };
+
+    // Weights come from LDS unmasked: where a K index is padding the A value is 0.
+    auto multiply = [&](int r, int blk, const float (&run)[STEM_MT][STEM_RUN]) {
+        const int bl = min(2 * STEM_RUN, seg - blk * (2 * STEM_RUN));
+        const int hs = (bl + 1) >> 1;                                // K-steps of this block (uniform)
+        const float* wp[STEM_NT];
 #pragma unroll
-            for (int i = 0; i < STEM_MT; ++i)
+        for (int j = 0; j < STEM_NT; ++j) wp[j] = wlds + (32 * j + l32) * wstride + r * seg + blk * (2 * STEM_RUN) + half * hs;
 #pragma unroll
-                for (int j = 0; j < STEM_NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int t = 0; t < STEM_RUN; ++t) {
+            if (t < hs) {
+                float b[STEM_NT];
+#pragma unroll
+                for (int j = 0; j < STEM_NT; ++j) b[j] = wp[j][t];
+#pragma unroll
+                for (int i = 0; i < STEM_MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < STEM_NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(run[i][t], b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    const int total_blocks = k * nblk;
+    float run0[STEM_MT][STEM_RUN], run1[STEM_MT][STEM_RUN];
+    fetch(0, 0, run0);
+    int r = 0, blk = 0;
+    for (int it = 0; it < total_blocks; it += 2) {
+        int r1 = r, b1 = blk + 1;
+        if (b1 == nblk) { b1 = 0; ++r1; }
+        if (it + 1 < total_blocks) fetch(r1, b1, run1);
+        multiply(r, blk, run0);
+        if (it + 1 < total_blocks) {
+            int r2 = r1, b2 = b1 + 1;
+            if (b2 == nblk) { b2 = 0; ++r2; }
+            if (it + 2 < total_blocks) fetch(r2, b2, run0);
+            multiply(r1, b1, run1);
+            r = r2; blk = b2;
         }
     }
 
@@ -256,7 +340,11 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
     const long long npix = (long long)N * P * Q;
     dim3 grid((unsigned)cdiv(npix, 4 * STEM_MT * 32), (unsigned)cdiv(O, STEM_NT * 32));
-    hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), 0, s, x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q);
+    // + slack: the unmasked weight reads of a padded K index may run a few floats past the last row
+    const size_t lds_bytes = ((size_t)STEM_NT * 32 * ((k * k * C) | 1) + 2 * STEM_RUN) * sizeof(float);
+    if (lds_bytes > 64 * 1024) return BNN_ERR_UNSUPPORTED;   // filter of more than 255 taps*channels per output
+    hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), lds_bytes, s, x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P,
+                       Q);
     return check_launch();
 }
 
