@@ -60,7 +60,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
                  const int32_t* thr, uint32_t* bits, int N, int H, int W, int C, int O, int k, int stride,
                  int pad, int pad_mode, int path, void* stream, const uint32_t* resid_bits = nullptr,
                  const uint32_t* x2 = nullptr, const uint32_t* filt2 = nullptr, int H2 = 0, int W2 = 0, int C2 = 0,
-                 int stride2 = 1) {
+                 int stride2 = 1, bool sums16 = false) {
     if (!in || !filt) return BNN_ERR_INVALID_ARG;
     if (!out && !bits) return BNN_ERR_INVALID_ARG;
     if (bits && !thr) return BNN_ERR_INVALID_ARG;
@@ -83,6 +83,10 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
     Epi e = {};
     e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O);
     e.resid_bits = resid ? nullptr : resid_bits; e.ld_resid_bits_w = words(O);
+    if (sums16) {       // internal callers: out / resid point at 16-bit storage of the same values
+        e.out16 = reinterpret_cast<int16_t*>(out); e.out = nullptr;
+        e.resid16 = reinterpret_cast<const int16_t*>(resid); e.resid = nullptr;
+    }
     return dispatch(in, filt, g, e, path, static_cast<hipStream_t>(stream));
 }
 
@@ -99,6 +103,7 @@ struct bnn_net {
         // filled by plan(): spatial size and channels of the output, where its bits live
         int H = 1, W = 1, C = 0;
         size_t bits_off = 0; int words_per_row = 0; long long rows_per_image = 1;
+        long long sum_bound = 0;      // BLOCK: largest |S| this block can produce
     };
     std::vector<Layer> layers;
     // results of the last forward, for bnn_net_layer_bits
@@ -113,6 +118,7 @@ inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 // output bits get their own slot (they are small: 1 bit per activation), int32 residuals use
 // three rotating slots sized for the largest residual tensor.
 struct Plan {
+    bool sums16 = false;     // every block sum fits 16 bits: residuals are stored as int16
     size_t total = 0;
     size_t resid_off[3] = {0, 0, 0};
     size_t resid_bytes = 0;
@@ -125,6 +131,7 @@ Plan plan(bnn_net* net, int batch) {
     int H = 1, W = 1, C = 0;
     size_t max_resid = 0;
     bool have_resid = false;
+    long long chain_bound = 1, max_bound = 0;     // |running residual| <= chain_bound
     for (size_t i = 0; i < net->layers.size(); ++i) {
         bnn_net::Layer& L = net->layers[i];
         if ((i == 0) != (L.kind == bnn_net::IN_U8 || L.kind == bnn_net::IN_BITS || L.kind == bnn_net::IN_CONV_F32)) {
@@ -150,6 +157,13 @@ Plan plan(bnn_net* net, int batch) {
                 H = (H + 2 - 3) / L.stride + 1; W = (W + 2 - 3) / L.stride + 1; C = L.b;
                 L.words_per_row = words(C);
                 have_resid = true;
+                // |S| <= |conv3x3(h)| + |shortcut|: 9*cout + (cin for a 1x1 downsample, else the running bound,
+                // which restarts at 1 (+1/-1 input bits) at the head of a chain)
+                if (L.w2) chain_bound = L.a;
+                else if (i == 0 || net->layers[i - 1].kind != bnn_net::BLOCK) chain_bound = 1;
+                chain_bound += 9LL * L.b;
+                L.sum_bound = chain_bound;
+                max_bound = max(max_bound, chain_bound);
                 break;
             case bnn_net::HEAD:
                 if (i + 1 != net->layers.size()) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
@@ -168,6 +182,7 @@ Plan plan(bnn_net* net, int batch) {
         if (L.kind == bnn_net::BLOCK || L.kind == bnn_net::IN_CONV_F32 || L.kind == bnn_net::CONV)
             max_resid = max(max_resid, (size_t)batch * H * W * C * 4);
     }
+    pl.sums16 = have_resid && max_bound <= 32767;
     if (have_resid) {
         pl.resid_bytes = align256(max_resid);
         for (int r = 0; r < 3; ++r) { pl.resid_off[r] = off; off += pl.resid_bytes; }
@@ -441,7 +456,7 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 rc = bconv_common(hbits, static_cast<const uint32_t*>(L.w1), keep_sum ? Rnew : nullptr, shortcut,
                                   static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
                                   L.pad_mode, path, stream, shortcut_bits, x2, static_cast<const uint32_t*>(L.w2), curH, curW,
-                                  curC, L.stride);
+                                  curC, L.stride, pl.sums16);
                 R = keep_sum ? Rnew : nullptr; rslot = (rslot + 1) % 3;
                 obits = ybits;
                 break;

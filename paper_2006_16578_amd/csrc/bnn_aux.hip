@@ -95,6 +95,9 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
                 }
             }
         }
+        // the slack after the last row is read (times an A value of 0) by padded K indices: keep it finite
+        if (threadIdx.x < 2 * STEM_RUN) wlds[STEM_NT * 32 * wstride + threadIdx.x] = 0.f;
+        if (wstride > kkc && threadIdx.x < STEM_NT * 32) wlds[threadIdx.x * wstride + kkc] = 0.f;   // row pad
     }
     __syncthreads();
 
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
 // time in the bytes of one register (HW <= 255); the sum of +1/-1 is 2 * count - HW.  FC: a wave
 // per output row, lanes stride over channels, butterfly reduction.
 constexpr int HEAD_IMGS = 4;
-constexpr int HEAD_OUTS = 128;
+constexpr int HEAD_OUTS = 32;
 constexpr int HEAD_MAXC = 1024;
 
 __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ bits, const float* __restrict__ w,
@@ -269,11 +272,15 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
         for (int q = 0; q < 8; ++q) cnt[q] = 0u;
         if (n < N) {
             const uint32_t* b = bits + (long long)n * HW * cw + wi;
-            for (int i = 0; i < HW; ++i) {
-                const uint32_t v = b[(long long)i * cw];
-                // bit (q + 8*t) of v is added to byte t of cnt[q]
+            for (int i0 = 0; i0 < HW; i0 += 8) {            // 8 independent loads in flight
+                uint32_t v[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) cnt[q] += (v >> q) & 0x01010101u;
+                for (int u = 0; u < 8; ++u) v[u] = (i0 + u < HW) ? b[(long long)(i0 + u) * cw] : 0u;
+                // bit (q + 8*t) of a word is added to byte t of cnt[q]
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) cnt[q] += (v[u] >> q) & 0x01010101u;
             }
         }
 #pragma unroll
@@ -294,10 +301,16 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
         float part[HEAD_IMGS];
 #pragma unroll
         for (int im = 0; im < HEAD_IMGS; ++im) part[im] = 0.f;
-        for (int c = lane; c < C; c += 64) {
-            const float wv = w[(long long)j * C + c];
+        float wv[HEAD_MAXC / 64];                       // the whole weight row in flight at once
 #pragma unroll
-            for (int im = 0; im < HEAD_IMGS; ++im) part[im] = fmaf(pooled[im][c], wv, part[im]);
+        for (int u = 0; u < HEAD_MAXC / 64; ++u) wv[u] = (lane + 64 * u < C) ? w[(long long)j * C + lane + 64 * u] : 0.f;
+#pragma unroll
+        for (int u = 0; u < HEAD_MAXC / 64; ++u) {
+            if (64 * u < C) {
+                const int c = min(lane + 64 * u, C - 1);
+#pragma unroll
+                for (int im = 0; im < HEAD_IMGS; ++im) part[im] = fmaf(pooled[im][c], wv[u], part[im]);
+            }
         }
 #pragma unroll
         for (int im = 0; im < HEAD_IMGS; ++im) {

@@ -39,6 +39,10 @@ struct Epi {
     const int32_t* resid;  // residual[row*ldc + col], added before the threshold (Sec. 6.1)
     const uint32_t* resid_bits;  // alternative residual: +1/-1 of bit col of resid_bits[row*ld_resid_bits_w + col/32]
     int ld_resid_bits_w;
+    // 16-bit storage of the same int32 values (row stride ldc), used by the layer chain when the
+    // sums provably fit: the arithmetic stays int32, only the bytes in memory are halved
+    const int16_t* resid16;
+    int16_t* out16;
     int ldc;               // elements between rows of out / resid
     const int32_t* thr;    // thr[col]: bit = (v >= thr[col])
     uint32_t* bits;        // bits[row*ldbits_w + col/32]

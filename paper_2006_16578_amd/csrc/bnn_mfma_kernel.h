@@ -133,6 +133,8 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
                     if (rok && cok[j]) {
                         if (e.resid != nullptr) {
                             rv[r][j] = e.resid[row * (long long)e.ldc + col];
+                        } else if (e.resid16 != nullptr) {
+                            rv[r][j] = (int)e.resid16[row * (long long)e.ldc + col];
                         } else {       // +1/-1 taken from a packed tensor (first residual of a chain)
                             const uint32_t w = e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)];
                             rv[r][j] = ((w >> (col & 31)) & 1u) ? 1 : -1;
@@ -167,6 +169,7 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
                 const int col = n0 + 32 * j + l32;
                 const int v = (int)acc[i][j][r] - corr + (HAS_RESID ? rv[r][j] : 0);
                 if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = v;
+                if (e.out16 != nullptr && rok && cok[j]) e.out16[row * (long long)e.ldc + col] = (int16_t)v;
                 if (e.bits != nullptr) {
                     const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
                     const int lo_row = 8 * (r >> 2) + (r & 3);
@@ -208,7 +211,8 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
     }
 
-    if (e.bits != nullptr && e.out == nullptr && e.resid == nullptr && e.resid_bits == nullptr && !row_corr) {
+    if (e.bits != nullptr && e.out == nullptr && e.out16 == nullptr && e.resid == nullptr && e.resid16 == nullptr &&
+        e.resid_bits == nullptr && !row_corr) {
         // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
         // by the pad correction; one v_cmp per accumulator register gives two packed words.
         float thf[NT];
@@ -242,7 +246,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         }
         return;
     }
-    if (e.resid != nullptr || e.resid_bits != nullptr)
+    if (e.resid != nullptr || e.resid16 != nullptr || e.resid_bits != nullptr)
         epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
     else
         epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
