@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 PEAK_FP4_MFMA_TFLOPS = 10.1e3      # 4-bit float matrix cores, TFLOP/s (2 flop per MAC)
 PEAK_HBM_GBS = 8000.0
 PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 2080 (context only)
+# Memory-side bytes per launch of the dominant kernel of the default sweep, from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
+# read hardware counters itself, so the measured figure is carried here and reported only for that kernel
+# in the default configuration.
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_lds_wg256x128": 7.162e8}
 
 
 def main() -> int:
@@ -144,7 +149,13 @@ def main() -> int:
     dk = by_kernel[dom]
     achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_FP4_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4),
+                "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
+                            else None),
+                "algorithmic_bytes_per_launch": round(sum(
+                    (do_bits * (2 * s["M"] * wl.nwords(s["K"]) * 4 + s["M"] * wl.nwords(s["N"]) * 4)
+                     + do_i32 * (2 * s["M"] * wl.nwords(s["K"]) * 4 + 4 * s["M"] * s["N"]))
+                    for s in shapes if s["kernel"] == dom) / max(dk["launches"], 1)),
                 "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
                 "flop_per_launch": dk["flop"] / dk["launches"],
                 "note": "fp4 (E2M1) matrix-core peak; 1 MAC on +1/-1 = 2 flop = 2 binary ops"}

@@ -51,6 +51,25 @@ def test_small_shapes(bnn, orc, pname, path, pad_mode):
         run_conv(bnn, orc, case, path, pad_mode)
 
 
+# ragged shapes that select the LDS-staged convolution kernels (16-byte pixels and 8-byte pixels)
+STAGED = [(5, 60, 60, 256, 130, 3, 1, 1, "mfma_fp4_conv_lds_wg128x128"),
+          (8, 70, 70, 64, 100, 7, 1, 3, "mfma_fp4_conv_lds_wg128x128"),
+          (9, 57, 57, 512, 300, 3, 2, 1, "mfma_fp4_conv_wg64x64"),
+          (33, 40, 40, 384, 70, 3, 1, 1, "mfma_fp4_conv_lds_wg128x128"),
+          (70, 58, 58, 256, 40, 3, 1, 1, "mfma_fp4_conv_lds_wg512x64")]
+
+
+@pytest.mark.parametrize("shape", STAGED)
+def test_ragged_shapes_staged_tiles(bnn, orc, shape):
+    N, H, W, C, O, k, st, pad, kernel = shape
+    assert bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad) == kernel
+    case = wl.bconv_case(94, N, H, W, C, O, k, st, pad, index0=C % 89)
+    for pad_mode in (0, 1):
+        ref1 = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode, tier=1)
+        assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, st, pad, pad_mode, N - 1, 1), ref1[N - 1:])
+        run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)
+
+
 def test_worked_example(bnn):
     # one +1 pixel, 3x3 filter of +1, pad 1: -7 with -1 padding, +1 with excluded taps
     x = torch.ones((1, 1, 1, 1), dtype=torch.int32, device="cuda")

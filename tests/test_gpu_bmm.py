@@ -45,6 +45,21 @@ def test_ragged_shapes(bnn, orc, pname, path):
         run_case(bnn, orc, wl.bmm_case(90, M, N, K, index0=10 * idx), path, ld_extra=4 if idx % 2 else 0)
 
 
+# ragged shapes large enough to select each LDS-staged tile of the matrix-core path
+STAGED = [(3000, 2500, 1000, "mfma_fp4_bmm_lds_wg128x128"), (5000, 5100, 1234, "mfma_fp4_bmm_lds_wg256x128"),
+          (131100, 50, 200, "mfma_fp4_bmm_lds_wg512x64"), (4097, 3001, 4100, "mfma_fp4_bmm_lds_wg256x128")]
+
+
+@pytest.mark.parametrize("M,N,K,kernel", STAGED)
+def test_ragged_shapes_staged_tiles(bnn, orc, M, N, K, kernel):
+    assert bnn.bmm_kernel_name(M, N, K) == kernel
+    case = wl.bmm_case(93, M, N, K, index0=M % 97)
+    ref1 = orc.bmm(case["A"], case["B"], K, tier=1)
+    for r0 in (0, M - 40):
+        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], K, r0, 40), ref1[r0:r0 + 40])
+    run_case(bnn, orc, case, 0, ref=ref1, ld_extra=4)
+
+
 @pytest.mark.parametrize("pname,path", PATHS)
 def test_closed_forms_and_max_k(bnn, orc, pname, path):
     # K at the library's maximum: identical rows give +K, complemented rows -K (exactness of the
