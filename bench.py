@@ -153,8 +153,8 @@ def main() -> int:
                 "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
                             else None),
                 "algorithmic_bytes_per_launch": round(sum(
-                    (do_bits * (2 * s["M"] * wl.nwords(s["K"]) * 4 + s["M"] * wl.nwords(s["N"]) * 4)
-                     + do_i32 * (2 * s["M"] * wl.nwords(s["K"]) * 4 + 4 * s["M"] * s["N"]))
+                    (do_bits * ((s["M"] + s["N"]) * wl.nwords(s["K"]) * 4 + s["M"] * wl.nwords(s["N"]) * 4)
+                     + do_i32 * ((s["M"] + s["N"]) * wl.nwords(s["K"]) * 4 + 4 * s["M"] * s["N"]))
                     for s in shapes if s["kernel"] == dom) / max(dk["launches"], 1)),
                 "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
                 "flop_per_launch": dk["flop"] / dk["launches"],
@@ -199,6 +199,17 @@ def _time_gpu(torch, fn, iters, warmup=3):
     return e0.elapsed_time(e1) / iters
 
 
+def _time_graph(torch, fn, iters):
+    """The same call captured once into a HIP graph and replayed: per-layer launch cost without the host."""
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    torch.cuda.synchronize()
+    return _time_gpu(torch, g.replay, iters)
+
+
 def run_extras(bnn, wl, np, torch, to_dev, dev):
     out = {}
     # ---- single BConv layers (config 4)
@@ -231,6 +242,9 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
         o = torch.empty((batch, 10), dtype=torch.int32, device=dev)
         t = _time_gpu(torch, lambda: net.forward(imgs, out=o), 50)
         mlp["batch%d" % batch] = {"ms": round(t, 5), "images_per_s": round(batch / t * 1e3, 1)}
+        if batch == 8:
+            tg = _time_graph(torch, lambda: net.forward(imgs, out=o), 50)
+            mlp["batch8"]["hip_graph_replay_ms"] = round(tg, 5)
     out["mlp_784_1024x3_10"] = mlp
     # ---- ResNet-18-shaped forward (config 5), batch 256
     p = wl.resnet18_params()
@@ -246,6 +260,9 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
         o = torch.empty((batch, 1000), dtype=torch.float32, device=dev)
         t = _time_gpu(torch, lambda: rnet.forward(x, out=o), 10 if batch == 256 else 30)
         res["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+        if batch == 8:
+            tg = _time_graph(torch, lambda: rnet.forward(x, out=o), 30)
+            res["batch8"]["hip_graph_replay_ms"] = round(tg, 4)
         if batch == 256:
             xs, w, th = x, to_dev(p["stem_w"]), to_dev(p["stem_thr"])
             ts = _time_gpu(torch, lambda: bnn.conv_f32_thr(xs, w, th, 4, 3), 5)
@@ -259,7 +276,7 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
 
 def cpu_baseline(wl, np):
     """The CPU oracle (tier 0: naive +1/-1 int8 loops, OpenMP over rows) timed on a bounded sample
-    of the same sweep: the first 96 rows of A of every shape (all rows where M < 96)."""
+    of the same sweep: the first 768 rows of A of every shape (all rows where M < 768)."""
     import oracle as orc
     orc.build()
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -267,15 +284,15 @@ def cpu_baseline(wl, np):
     secs = 0.0
     for name, M, N, K, _ in wl.cfg2_shapes():
         case = wl.cfg2_case(name)
-        rows = min(M, 96)
+        rows = min(M, 768)
         t0 = time.perf_counter()
         orc.bmm_rows(case["A"], case["B"], K, 0, rows)
         secs += time.perf_counter() - t0
         macs += float(rows) * N * K
     return {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "binary TOPS", "cores": cores, "kind": "oracle",
             "seconds": round(secs, 2),
-            "sample": "tier-0 oracle (unpacked int8 +1/-1, naive loops, includes unpacking B) on the first 96 rows of A "
-                      "of every sweep shape, int32 output"}
+            "sample": "tier-0 oracle (unpacked int8 +1/-1, naive loops, includes unpacking B) on the first 768 rows of A "
+                      "of every sweep shape (all rows where M < 768), int32 output"}
 
 
 if __name__ == "__main__":
