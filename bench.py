@@ -230,6 +230,19 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
                       "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1)})
         del x, f, bits, y
     out["bconv_shapes"] = convs
+    # ---- the paper's BConv sweep (Sec. 7.3): batch 16, 64x64 input, 3x3, stride 1, C = O
+    sweep = []
+    for ch in (128, 256, 512, 640, 1024, 2048):
+        case = wl.bconv_case(6, 16, 64, 64, ch, ch, 3, 1, 1, index0=ch % 97)
+        x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
+        bits = torch.empty((16, 64, 64, wl.nwords(ch)), dtype=torch.int32, device=dev)
+        ops = 2.0 * 16 * 64 * 64 * ch * 9 * ch
+        t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, ch, 1, 1, bnn.PAD_MINUS_ONE, out=bits), 10)
+        sweep.append({"C=O": ch, "kernel": bnn.bconv_kernel_name(16, 64, 64, ch, ch, 3, 1, 1), "bits_out_ms": round(t_b, 5),
+                      "bits_out_tops": round(ops / t_b / 1e9, 1),
+                      "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4)})
+        del x, f, bits
+    out["bconv_sweep_batch16_64x64_3x3"] = sweep
     # ---- binarized MLP (config 3)
     params = wl.mlp_params()
     net = bnn.Net()

@@ -36,7 +36,8 @@ int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* 
     Geom g = {};
     g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = kw4; g.bits_tap = K;
     g.lda_w = lda_w; g.ldb_w = ldb_w;
-    g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0;
+    g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0; g.kinv = 65536;
+    g.div_pq = make_fastdiv(1u); g.div_q = make_fastdiv(1u);
     Epi e = {};
     e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w;
     return dispatch(A, B, g, e, path, static_cast<hipStream_t>(stream));
@@ -46,11 +47,11 @@ int conv_shape(int N, int H, int W, int C, int O, int k, int stride, int pad, in
     if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0) return BNN_ERR_INVALID_ARG;
     if (pad_mode != BNN_PAD_MINUS_ONE && pad_mode != BNN_PAD_EXCLUDE) return BNN_ERR_INVALID_ARG;
     if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
-    if (pad >= k) return BNN_ERR_UNSUPPORTED;          // a window entirely out of frame
+    if (pad >= k || k > 32) return BNN_ERR_UNSUPPORTED;    // a window entirely out of frame; tap index arithmetic
     if ((long long)k * k * C > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
     *P = (H + 2 * pad - k) / stride + 1;
     *Q = (W + 2 * pad - k) / stride + 1;
-    if ((long long)N * *P * *Q * O > (1LL << 40)) return BNN_ERR_UNSUPPORTED;
+    if ((long long)N * *P * *Q * O > (1LL << 40) || (long long)N * *P * *Q >= (1LL << 31)) return BNN_ERR_UNSUPPORTED;
     return BNN_OK;
 }
 
@@ -74,7 +75,8 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
     Geom g = {};
     g.rows = (long long)N * P * Q; g.cols = O; g.conv = 1; g.taps = k * k; g.tw = cw; g.bits_tap = C;
     g.lda_w = cw; g.ldb_w = k * k * cw;
-    g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad;
+    g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad; g.kinv = (65536 + k - 1) / k;
+    g.div_pq = make_fastdiv((uint32_t)(P * Q)); g.div_q = make_fastdiv((uint32_t)Q);
     g.excl = (pad_mode == BNN_PAD_EXCLUDE) ? 1 : 0;
     if (x2 != nullptr) {    // fused 1x1 shortcut convolution (internal callers only; shapes already checked)
         if (!filt2 || C2 < 1 || stride2 < 1 || (P - 1) * stride2 >= H2 || (Q - 1) * stride2 >= W2) return BNN_ERR_INVALID_ARG;

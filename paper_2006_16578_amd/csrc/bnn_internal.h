@@ -9,6 +9,31 @@
 
 namespace bnn {
 
+// Division of 0 <= n < 2^31 by a runtime constant d >= 1 without a divide: one 32x32 high multiply
+// and a shift (m == 0 marks a power of two: shift only).  For d not a power of two, with
+// L = ceil(log2 d): sh = L - 1, m = floor(2^(32+sh) / d) + 1 < 2^32, and mulhi(n, m) >> sh == n / d
+// for every n < 2^31 (the excess of m over the exact reciprocal contributes less than 1/d).
+struct FastDiv {
+    uint32_t m;
+    int sh;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    int L = 0;
+    while ((1ull << L) < d) ++L;
+    if ((1ull << L) == d) { f.m = 0u; f.sh = L; return f; }
+    f.sh = L - 1;
+    f.m = (uint32_t)(((1ull << (32 + f.sh)) / d) + 1ull);
+    return f;
+}
+__host__ __device__ inline int fast_div(int n, const FastDiv& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return f.m == 0u ? (n >> f.sh) : (int)(__umulhi((uint32_t)n, f.m) >> f.sh);
+#else
+    return f.m == 0u ? (n >> f.sh) : (int)((((unsigned long long)(uint32_t)n * f.m) >> 32) >> f.sh);
+#endif
+}
+
 // One +1/-1 contraction seen as an implicit GEMM: `rows` output rows (A rows of a BMM, output
 // pixels n*P*Q of a convolution) by `cols` output columns (B rows / output channels), contracted
 // over `taps` windows of `tw` packed words each.
@@ -23,6 +48,8 @@ struct Geom {
     int ldb_w;       // words between B rows (BMM: ldb_w, conv: k*k*cw)
     // convolution geometry (Sec. 5.3)
     int H, W, P, Q, k, stride, pad;
+    FastDiv div_pq, div_q;   // divisions by P*Q and by Q (row -> image, pixel row, pixel column); rows < 2^31
+    int kinv;        // ceil(65536 / k): tap / k == (tap * kinv) >> 16 for every tap < k*k + 64 (checked for k <= 42; k <= 32 accepted)
     int excl;        // 1: out-of-frame taps contribute nothing; 0: they count as -1
     // Optional second source, accumulated into the same sums: a 1x1 convolution (no padding) of
     // a second packed tensor A2 [N][H2][W2][cw2] sampled at (p*stride2, q*stride2) with filters

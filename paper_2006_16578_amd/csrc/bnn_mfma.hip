@@ -12,6 +12,7 @@ namespace {
 bool staged_ok(const Geom& g, int tile) {
     if (tile == 3) return false;
     if (!g.conv) return true;
+    if (tile == 1 && g.tw == 2) return false;    // 512 loader rows of 8-byte pixels: too many registers
     // short K (few slabs): the direct kernel has less fixed cost per workgroup
     return !g.excl && g.bits_tap == g.tw * 32 && (g.tw % 4 == 0 || g.tw == 2) && g.taps * g.tw >= 64;
 }
@@ -19,7 +20,7 @@ bool staged_ok(const Geom& g, int tile) {
 }  // namespace
 
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
-    const int tile = mfma::pick_tile(g);
+    const int tile = mfma::pick_tile(g, &e);
     if (!g.conv) {
         if (staged_ok(g, tile)) {
             switch (tile) {

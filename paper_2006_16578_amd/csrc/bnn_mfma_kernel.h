@@ -155,10 +155,9 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
             const bool rok = row < g.rows;
             int corr = corr_all;
             if (row_corr) {
-                const long long rr = rok ? row : g.rows - 1;
-                const int pq = g.P * g.Q;
-                const int rem = (int)(rr % pq);
-                const int p = rem / g.Q, q = rem - p * g.Q;
+                const int rr = (int)(rok ? row : g.rows - 1);
+                const int rem = rr - fast_div(rr, g.div_pq) * (g.P * g.Q);
+                const int p = fast_div(rem, g.div_q), q = rem - p * g.Q;
                 const int ylo = p * g.stride - g.pad, xlo = q * g.stride - g.pad;
                 const int vy = min(ylo + g.k, g.H) - max(ylo, 0);
                 const int vx = min(xlo + g.k, g.W) - max(xlo, 0);
@@ -265,10 +264,9 @@ __device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, 
     for (int i = 0; i < MT; ++i) {
         long long row = m0 + 32 * i + l32;
         if (row > g.rows - 1) row = g.rows - 1;
-        const int pq = g.P * g.Q;
-        const int n = (int)(row / pq);
-        const int rem = (int)(row - (long long)n * pq);
-        const int p = rem / g.Q, q = rem - p * g.Q;
+        const int n = fast_div((int)row, g.div_pq);
+        const int rem = (int)row - n * (g.P * g.Q);
+        const int p = fast_div(rem, g.div_q), q = rem - p * g.Q;
         ar[i] = g.A2 + (((long long)n * g.H2 + p * g.stride2) * g.W2 + q * g.stride2) * g.cw2;
     }
 #pragma unroll
@@ -319,10 +317,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
         long long row = m0 + 32 * i + l32;
         if (row > g.rows - 1) row = g.rows - 1;          // clamp: loads stay in bounds, results are dropped
         if (CONV) {
-            const int pq = g.P * g.Q;
-            const int n = (int)(row / pq);
-            const int rem = (int)(row - (long long)n * pq);
-            const int p = rem / g.Q, q = rem - p * g.Q;
+            const int n = fast_div((int)row, g.div_pq);
+            const int rem = (int)row - n * (g.P * g.Q);
+            const int p = fast_div(rem, g.div_q), q = rem - p * g.Q;
             y0[i] = p * g.stride - g.pad;
             x0[i] = q * g.stride - g.pad;
             arow[i] = A + (long long)n * g.H * g.W * g.lda_w;
@@ -357,7 +354,7 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
         const int wo = cc * 2 * V + half * V;       // this lane's word offset inside the tap
         const bool wok = !GUARD || (wo < g.tw);     // tw and wo are multiples of V
         int r = 0, s = 0;
-        if (CONV) { r = tt / g.k; s = tt - r * g.k; }
+        if (CONV) { r = (tt * g.kinv) >> 16; s = tt - r * g.k; }
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             const uint32_t* p = arow[i];
@@ -446,8 +443,18 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 }
 
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
-// CUs (two workgroups each for the big tiles) enough workgroups.
-inline int pick_tile(const Geom& g) {
+// CUs (two workgroups each for the big tiles) enough workgroups -- unless the epilogue moves full
+// precision sums (residual in, sum out) and K is short: then the call is bound by that traffic
+// (about 2.5 P MAC/s against 4.5 TB/s: K < ~500 bits per byte moved per output), and the small tile,
+// with four times the resident workgroups, overlaps it with the matrix work of other workgroups.
+inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
+    if (e != nullptr) {
+        const int bytes = 4 * (e->resid != nullptr) + 4 * (e->out != nullptr) + 2 * (e->resid16 != nullptr) +
+                          2 * (e->out16 != nullptr);
+        if (bytes > 0 && (long long)g.taps * g.bits_tap < 500LL * bytes &&
+            cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
+            return 3;
+    }
     if (g.cols <= 64) return (cdiv(g.rows, TileTall::ROWS) >= 256) ? 1 : 3;
     if (cdiv(g.rows, TileBig::ROWS) * cdiv(g.cols, TileBig::COLS) >= 384) return 0;
     if (cdiv(g.rows, TileMid::ROWS) * cdiv(g.cols, TileMid::COLS) >= 256) return 2;
@@ -456,7 +463,7 @@ inline int pick_tile(const Geom& g) {
 
 template <int V, bool CONV, bool GUARD>
 int launch_shape(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
-    switch (pick_tile(g)) {
+    switch (pick_tile(g, &e)) {
         case 0: return launch_tile<TileBig, V, CONV, GUARD>(A, B, g, e, s);
         case 1: return launch_tile<TileTall, V, CONV, GUARD>(A, B, g, e, s);
         case 2: return launch_tile<TileMid, V, CONV, GUARD>(A, B, g, e, s);

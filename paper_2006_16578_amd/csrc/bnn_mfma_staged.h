@@ -57,10 +57,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
         long long row = m_base + r4 + 64 * q;
         if (row > g.rows - 1) row = g.rows - 1;          // clamp: loads stay in bounds, results are dropped
         if (CONV) {
-            const int pq = g.P * g.Q;
-            const int n = (int)(row / pq);
-            const int rem = (int)(row - (long long)n * pq);
-            const int p = rem / g.Q, qq = rem - p * g.Q;
+            const int n = fast_div((int)row, g.div_pq);
+            const int rem = (int)row - n * (g.P * g.Q);
+            const int p = fast_div(rem, g.div_q), qq = rem - p * g.Q;
             ay0[q] = p * g.stride - g.pad;
             ax0[q] = qq * g.stride - g.pad;
             ap[q] = A + (long long)n * g.H * g.W * g.lda_w;
@@ -95,9 +94,15 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
                 if (!ok) sb[q] = make_uint4(0u, 0u, 0u, 0u);
             }
         } else if (U == 16) {
-            const int tap = wq / g.tw, off = wq - tap * g.tw;     // tw is a multiple of 4 here
+            // tap and offset of this granule without a vector division: the slab's first word is
+            // wave-uniform (scalar division), the lane adds at most 12 words and wraps a few times
+            const int w0 = s * 16;
+            int tap = w0 / g.tw, off = w0 - tap * g.tw + g4 * 4;  // tw is a multiple of 4 here
+#pragma unroll
+            for (int it = 0; it < 3; ++it)
+                if (off >= g.tw) { off -= g.tw; ++tap; }
             const bool ok = wq < kwords;
-            const int r = tap / g.k, sx = tap - r * g.k;
+            const int r = (tap * g.kinv) >> 16, sx = tap - r * g.k;
 #pragma unroll
             for (int q = 0; q < LA; ++q) {
                 const int y = ay0[q] + r, x = ax0[q] + sx;
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
             for (int h = 0; h < 2; ++h) {
                 const int tap = (wq >> 1) + h;
                 const bool ok = tap < g.taps;
-                const int r = tap / g.k, sx = tap - r * g.k;
+                const int r = (tap * g.kinv) >> 16, sx = tap - r * g.k;
 #pragma unroll
                 for (int q = 0; q < LA; ++q) {
                     const int y = ay0[q] + r, x = ax0[q] + sx;

@@ -70,6 +70,14 @@ def test_ragged_shapes_staged_tiles(bnn, orc, shape):
         run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)
 
 
+def test_paper_sweep_shape_c640(bnn, orc):
+    # one shape of the paper's BConv sweep (batch 16, 64x64, 3x3, C = O = 640), as bench.py runs it
+    case = wl.bconv_case(6, 16, 64, 64, 640, 640, 3, 1, 1, index0=640 % 97)
+    ref1 = orc.bconv(case["x"], case["filt"], 640, 1, 1, 0, tier=1)
+    assert np.array_equal(orc.bconv_images(case["x"], case["filt"], 640, 1, 1, 0, 15, 1), ref1[15:])
+    run_conv(bnn, orc, case, 0, 0, ref=ref1, with_resid=False)
+
+
 def test_worked_example(bnn):
     # one +1 pixel, 3x3 filter of +1, pad 1: -7 with -1 padding, +1 with excluded taps
     x = torch.ones((1, 1, 1, 1), dtype=torch.int32, device="cuda")
