@@ -127,6 +127,11 @@ int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows,
  * residual chain from a bit tensor. */
 int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream);
 
+/* Max-pooling of packed +1/-1 activations: behind the threshold the maximum over a window is the
+ * bitwise OR of the packed words (Sec. 6.1).  in [N][H][W][cw] -> out [N][P][Q][cw],
+ * P = (H - win)/stride + 1, Q likewise (no padding; partial windows are dropped).  win <= H, W. */
+int bnn_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Full-precision end layers of a network whose inner layers are binarized (Sec. 6.1: the first
  * layer keeps full-precision input).  fp32 arithmetic, not bit-exact: 1e-4 relative.
@@ -165,6 +170,8 @@ int bnn_net_add_fc(bnn_net* net, const uint32_t* W, const int32_t* thr, int K, i
 /* Binarized convolution + threshold. */
 int bnn_net_add_conv(bnn_net* net, const uint32_t* filt, const int32_t* thr,
                      int C, int O, int k, int stride, int pad, int pad_mode);
+/* Max-pooling (OR) of the current packed activation. */
+int bnn_net_add_pool(bnn_net* net, int win, int stride);
 /* Residual basic block: h = thr1(conv3x3(x, W1, stride, pad 1)); S = conv3x3(h, W2, 1, pad 1) + shortcut;
  * y = (S >= thr2); the running residual becomes S.  shortcut = running residual when Wd == NULL
  * (needs stride 1, cin == cout; the first such block of a chain uses the +1/-1 values of its input

@@ -174,6 +174,18 @@ def pack_f32(x, tau, ldb_w: int | None = None) -> np.ndarray:
     return bits.reshape(x.shape[:-1] + (ldb_w,))
 
 
+def maxpool_pm1(bits, C: int, win: int, stride: int) -> np.ndarray:
+    """bits [N][H][W][cw] -> [N][P][Q][cw]: maximum of the +1/-1 values over win x win windows."""
+    bits = _words(bits, 4)
+    N, H, W, cw = bits.shape
+    assert cw == nwords(C)
+    P, Q = (H - win) // stride + 1, (W - win) // stride + 1
+    out = np.empty((N, P, Q, cw), dtype=np.uint32)
+    _check(lib().orc_maxpool_pm1(_p(bits), _p(out), _i64(N), _i64(H), _i64(W), _i64(C), _i64(win), _i64(stride)),
+           "maxpool")
+    return out
+
+
 # ----------------------------------------------------------------------------- fp32 ends
 def conv_f32(x, w, stride: int, pad: int) -> np.ndarray:
     """x [N][H][W][C] fp32 (zero padded), w [O][k][k][C] -> fp32 [N][P][Q][O]; double accumulation."""

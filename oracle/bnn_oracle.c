@@ -178,6 +178,35 @@ int orc_pack_f32(const float* x, const float* tau, uint32_t* bits, int64_t rows,
 }
 
 /* ---------------------------------------------------------------------------------------
+ * Max-pooling of +1/-1 activations (Sec. 6.1: for inference the pooling is moved behind the
+ * threshold, where the maximum of +1/-1 values is the logical OR of their bits).  Here it is the
+ * definition: the maximum over the window of the unpacked values, then re-packed.
+ * in [N][H][W][cw] -> out [N][P][Q][cw], P = (H - win)/stride + 1 (no padding, partial windows dropped).
+ * ------------------------------------------------------------------------------------- */
+int orc_maxpool_pm1(const uint32_t* in, uint32_t* out, int64_t N, int64_t H, int64_t W, int64_t C,
+                    int64_t win, int64_t stride) {
+    if (!in || !out || N < 0 || H <= 0 || W <= 0 || C <= 0 || win <= 0 || stride <= 0 || H < win || W < win) return 2;
+    const int64_t cw = (C + 31) / 32;
+    const int64_t P = (H - win) / stride + 1, Q = (W - win) / stride + 1;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q) {
+                uint32_t* o = out + ((n * P + p) * Q + q) * cw;
+                for (int64_t i = 0; i < cw; ++i) o[i] = 0u;
+                for (int64_t c = 0; c < C; ++c) {
+                    int best = -1;
+                    for (int64_t r = 0; r < win; ++r)
+                        for (int64_t t = 0; t < win; ++t) {
+                            const int v = bit_at(in + ((n * H + p * stride + r) * W + q * stride + t) * cw, c) ? 1 : -1;
+                            if (v > best) best = v;
+                        }
+                    if (best > 0) o[c >> 5] |= (1u << (c & 31));
+                }
+            }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
  * Full-precision first and last layers of the ResNet-18-shaped network (Sec. 6.1: the first
  * layer is not binarized).  Accumulated in double, rounded to fp32 once.
  * ------------------------------------------------------------------------------------- */

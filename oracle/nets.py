@@ -79,3 +79,69 @@ def resnet18_forward(x_f32: np.ndarray, params: dict, stem_bits: np.ndarray | No
     logits = orc.head_fc_f32(pooled, params["fc_w"], float(HW))
     trace["logits"] = logits
     return trace if keep else logits
+
+
+def cnn_forward(x_f32: np.ndarray, layers: list, stem_bits: np.ndarray | None = None, tier: int = 0, keep: bool = False):
+    """Sequential binarized CNN in the inference order of Sec. 6.1 (thrd -> bconv -> thrd -> pool ...),
+    as used for the Cifar-10 VGG / ResNet-14 and ImageNet AlexNet / VGG-16 shapes of the paper's Table 5.
+
+    ``layers`` is a list of dicts, one per layer:
+      {"op": "conv_f32", "w", "thr", "stride", "pad"}          first layer: fp32 conv (zero pad) then x >= thr
+      {"op": "bconv", "W", "thr", "C", "stride", "pad"}        binarized conv (-1 padding) + threshold
+      {"op": "pool", "win", "stride"}                          max-pooling of +1/-1 values
+      {"op": "block", "W1","thr1","W2","thr2",["Wd"],"cin","cout","stride"}   residual block as in resnet18_forward
+      {"op": "fc", "W", "thr" | None, "K"}                      binarized FC on the flattened NHWC bits; thr None: int32 scores
+    Returns the last layer's output (int32 scores), or a list with every layer's output if ``keep``.
+    """
+    outs = []
+    x = None           # current packed activation [N][H][W][cw] or [N][ldw]
+    C = 0
+    R = None
+    for li, L in enumerate(layers):
+        op = L["op"]
+        if op == "conv_f32":
+            y = orc.conv_f32(x_f32, L["w"], L["stride"], L["pad"])
+            x = orc.pack_f32(y, L["thr"]) if stem_bits is None else np.ascontiguousarray(stem_bits, np.uint32)
+            C = L["w"].shape[0]
+            R = None
+            outs.append(x)
+        elif op == "bconv":
+            v = orc.bconv(x, L["W"], L["C"], L["stride"], L["pad"], orc.PAD_MINUS_ONE, tier=tier)
+            x = orc.threshold_pack(v, L["thr"])
+            C = L["W"].shape[0]
+            R = None
+            outs.append(x)
+        elif op == "pool":
+            x = orc.maxpool_pm1(x, C, L["win"], L["stride"])
+            R = None
+            outs.append(x)
+        elif op == "block":
+            cin, cout, stride = L["cin"], L["cout"], L["stride"]
+            if R is None and "Wd" not in L:
+                N, H, W_, cw = x.shape
+                R = orc.unpack_pm1(x.reshape(-1, cw), cin).astype(np.int32).reshape(N, H, W_, cin)
+            v1 = orc.bconv(x, L["W1"], cin, stride, 1, orc.PAD_MINUS_ONE, tier=tier)
+            h = orc.threshold_pack(v1, L["thr1"])
+            v2 = orc.bconv(h, L["W2"], cout, 1, 1, orc.PAD_MINUS_ONE, tier=tier)
+            sc = orc.bconv(x, L["Wd"], cin, stride, 0, orc.PAD_MINUS_ONE, tier=tier) if "Wd" in L else R
+            S = v2 + sc
+            x = orc.threshold_pack(S, L["thr2"])
+            R = S
+            C = cout
+            outs.append(x)
+        elif op == "fc":
+            if x.ndim == 4:                                   # flatten NHWC: K index = (h*W + w)*C + c
+                assert C % 32 == 0
+                x = x.reshape(x.shape[0], -1)
+            v = orc.bmm(x, L["W"], L["K"], tier=tier)
+            if L["thr"] is None:
+                outs.append(v)
+                x = None
+            else:
+                x = orc.threshold_pack(v, L["thr"], ldb_w=(orc.nwords(v.shape[1]) + 3) // 4 * 4)
+                C = v.shape[1]
+                outs.append(x)
+            R = None
+        else:
+            raise ValueError(op)
+    return outs if keep else outs[-1]

@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "conv_f32_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "maxpool_or", "conv_f32_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,9 +24,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_unpack_i32", "bnn_conv_f32_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_pack_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_add_fc",
-           "bnn_net_add_conv", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
+           "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
            "bnn_net_forward", "bnn_net_layer_bits"]
 
 
@@ -225,6 +225,19 @@ def unpack_i32(bits, cols: int):
     return out
 
 
+def maxpool_or(bits, C: int, win: int, stride: int):
+    """bits [N][H][W][cw] -> [N][P][Q][cw]: max-pooling of +1/-1 activations as a bitwise OR."""
+    _dev(bits, _BITS, 4, "bits")
+    N, H, W, cw = bits.shape
+    ok = stride >= 1 and 1 <= win <= min(H, W)          # anything else is left for the library to reject
+    P, Q = ((H - win) // stride + 1, (W - win) // stride + 1) if ok else (1, 1)
+    out = torch.empty((N, P, Q, cw), dtype=_BITS, device=bits.device)
+    with torch.cuda.device(bits.device):
+        _check(load().bnn_maxpool_or(_ptr(bits), _ptr(out), N, H, W, int(C), int(win), int(stride), _stream(bits)),
+               "bnn_maxpool_or")
+    return out
+
+
 def conv_f32_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False):
     """fp32 first layer: x [N][H][W][C], w [O][k][k][C], thr [O] -> bits [N][P][Q][ow] (and fp32 y)."""
     _dev(x, torch.float32, 4, "x"); _dev(w, torch.float32, 4, "w"); _dev(thr, torch.float32, 1, "thr")
@@ -310,6 +323,10 @@ class Net:
                "bnn_net_add_conv")
         self._added(filt, thr)
 
+    def add_pool(self, win: int, stride: int):
+        _check(load().bnn_net_add_pool(self._h, int(win), int(stride)), "bnn_net_add_pool")
+        self._added()
+
     def add_block(self, W1, thr1, W2, thr2, Wd, cin: int, cout: int, stride: int, pad_mode: int = PAD_MINUS_ONE):
         for t in (W1, W2):
             _dev(t, _BITS, 4, "W")
@@ -322,6 +339,34 @@ class Net:
         _check(load().bnn_net_add_head_f32(self._h, _ptr(w), w.shape[0]), "bnn_net_add_head_f32")
         self._out_kind, self._out_cols = torch.float32, w.shape[0]
         self._added(w)
+
+    @classmethod
+    def from_layers(cls, layers, in_hw: int, device="cuda"):
+        """Builds a net from a list of layer dicts holding numpy arrays (the description the seeded
+        generators and the CPU oracle use): conv_f32 first, then bconv / pool / block / fc."""
+        import numpy as np
+
+        def dev(a):
+            a = np.ascontiguousarray(a)
+            return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(device)
+
+        net = cls()
+        for L in layers:
+            op = L["op"]
+            if op == "conv_f32":
+                net.input_conv_f32(dev(L["w"]), dev(L["thr"]), in_hw, in_hw, L["stride"], L["pad"])
+            elif op == "bconv":
+                net.add_conv(dev(L["W"]), dev(L["thr"]), L["C"], L["stride"], L["pad"])
+            elif op == "pool":
+                net.add_pool(L["win"], L["stride"])
+            elif op == "block":
+                net.add_block(dev(L["W1"]), dev(L["thr1"]), dev(L["W2"]), dev(L["thr2"]),
+                              dev(L["Wd"]) if "Wd" in L else None, L["cin"], L["cout"], L["stride"])
+            elif op == "fc":
+                net.add_fc(dev(L["W"]), None if L["thr"] is None else dev(L["thr"]), L["K"])
+            else:
+                raise ValueError(op)
+        return net
 
     def workspace_bytes(self, batch: int) -> int:
         n = ctypes.c_size_t()

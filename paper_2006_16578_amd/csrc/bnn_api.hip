@@ -96,7 +96,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
 
 // ------------------------------------------------------------------------------------------ net
 struct bnn_net {
-    enum Kind { IN_U8, IN_BITS, IN_CONV_F32, FC, CONV, BLOCK, HEAD };
+    enum Kind { IN_U8, IN_BITS, IN_CONV_F32, FC, CONV, POOL, BLOCK, HEAD };
     struct Layer {
         Kind kind;
         const void* w0 = nullptr; const void* w1 = nullptr; const void* w2 = nullptr;   // weights
@@ -152,6 +152,10 @@ Plan plan(bnn_net* net, int batch) {
             case bnn_net::CONV:
                 if (C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
                 H = (H + 2 * L.pad - L.k) / L.stride + 1; W = (W + 2 * L.pad - L.k) / L.stride + 1; C = L.b;
+                L.words_per_row = words(C); break;
+            case bnn_net::POOL:
+                if (H < L.k || W < L.k) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                H = (H - L.k) / L.stride + 1; W = (W - L.k) / L.stride + 1;
                 L.words_per_row = words(C); break;
             case bnn_net::BLOCK:
                 if (C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
@@ -288,6 +292,12 @@ int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, i
     return launch_unpack_i32(bits, out, rows, cols, ldb_w, ldo, static_cast<hipStream_t>(stream));
 }
 
+int bnn_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, void* stream) {
+    if (!in || !out || N < 1 || H < 1 || W < 1 || C < 1 || win < 1 || stride < 1 || win > H || win > W)
+        return BNN_ERR_INVALID_ARG;
+    return launch_maxpool_or(in, out, N, H, W, C, win, stride, static_cast<hipStream_t>(stream));
+}
+
 int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits, int N, int H,
                      int W, int C, int O, int k, int stride, int pad, void* stream) {
     if (!x || !w || (!y_f32 && !bits) || (bits && !thr)) return BNN_ERR_INVALID_ARG;
@@ -350,6 +360,12 @@ int bnn_net_add_conv(bnn_net* net, const uint32_t* filt, const int32_t* thr, int
     if (!aligned16(filt) || !aligned16(thr)) return BNN_ERR_ALIGNMENT;
     bnn_net::Layer L; L.kind = bnn_net::CONV; L.w0 = filt; L.t0 = thr; L.a = C; L.b = O; L.k = k; L.stride = stride;
     L.pad = pad; L.pad_mode = pad_mode;
+    net->layers.push_back(L);
+    return BNN_OK;
+}
+int bnn_net_add_pool(bnn_net* net, int win, int stride) {
+    if (!net || win < 1 || stride < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    bnn_net::Layer L; L.kind = bnn_net::POOL; L.k = win; L.stride = stride;
     net->layers.push_back(L);
     return BNN_OK;
 }
@@ -432,6 +448,10 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 rc = bnn_bconv_thr_ex(cur, static_cast<const uint32_t*>(L.w0), nullptr, nullptr,
                                       static_cast<const int32_t*>(L.t0), obits, batch, curH, curW, curC, L.b, L.k,
                                       L.stride, L.pad, L.pad_mode, path, stream);
+                R = nullptr;
+                break;
+            case bnn_net::POOL:
+                rc = bnn_maxpool_or(cur, obits, batch, curH, curW, curC, L.k, L.stride, stream);
                 R = nullptr;
                 break;
             case bnn_net::BLOCK: {

@@ -43,6 +43,25 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     }
 }
 
+// Max-pooling of +1/-1 activations after the threshold = bitwise OR of the packed words of the
+// window (Sec. 6.1).  One thread per output word.
+__global__ __launch_bounds__(256) void maxpool_or_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                         long long nwords_out, int H, int W, int cw, int P, int Q,
+                                                         int win, int stride) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nwords_out) return;
+    const int wi = (int)(idx % cw);
+    long long pix = idx / cw;
+    const int q = (int)(pix % Q); pix /= Q;
+    const int p = (int)(pix % P);
+    const long long n = pix / P;
+    const uint32_t* base = in + ((n * H + (long long)p * stride) * W + (long long)q * stride) * cw + wi;
+    uint32_t v = 0u;
+    for (int r = 0; r < win; ++r)
+        for (int t = 0; t < win; ++t) v |= base[((long long)r * W + t) * cw];
+    out[idx] = v;
+}
+
 // First layer: fp32 convolution with zero padding, then per-channel threshold -> bits, as an
 // implicit GEMM on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): rows are output pixels,
 // columns output channels, and K runs over the k filter rows times the k*C contiguous floats of
@@ -348,6 +367,13 @@ int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int co
     return check_launch();
 }
 
+int launch_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, hipStream_t s) {
+    const int P = (H - win) / stride + 1, Q = (W - win) / stride + 1, cw = (C + 31) / 32;
+    const long long n = (long long)N * P * Q * cw;
+    hipLaunchKernelGGL(maxpool_or_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, in, out, n, H, W, cw, P, Q, win, stride);
+    return check_launch();
+}
+
 int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits,
                         int N, int H, int W, int C, int O, int k, int stride, int pad, hipStream_t s) {
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
@@ -355,7 +381,12 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
     dim3 grid((unsigned)cdiv(npix, 4 * STEM_MT * 32), (unsigned)cdiv(O, STEM_NT * 32));
     // + slack: the unmasked weight reads of a padded K index may run a few floats past the last row
     const size_t lds_bytes = ((size_t)STEM_NT * 32 * ((k * k * C) | 1) + 2 * STEM_RUN) * sizeof(float);
-    if (lds_bytes > 64 * 1024) return BNN_ERR_UNSUPPORTED;   // filter of more than 255 taps*channels per output
+    if (lds_bytes > 160 * 1024) return BNN_ERR_UNSUPPORTED;  // more than ~630 filter taps*channels per output
+    if (lds_bytes > 64 * 1024) {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_f32_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    }
     hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), lds_bytes, s, x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P,
                        Q);
     return check_launch();

@@ -91,6 +91,7 @@ int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, 
 int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s);
+int launch_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, hipStream_t s);
 int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits,
                         int N, int H, int W, int C, int O, int k, int stride, int pad, hipStream_t s);
 int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,

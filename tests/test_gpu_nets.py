@@ -131,3 +131,55 @@ def test_conv_f32_shapes(bnn, orc, shape):
     assert (np.abs(host(y) - ref) <= tol).all()
     # the bits are exactly the GPU's own fp32 values thresholded, pad bits zero
     assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
+
+
+# ------------------------------------------------------------------ max-pooling and the other Table-5 networks
+@pytest.mark.parametrize("shape", [(2, 8, 8, 40, 2, 2), (1, 7, 9, 64, 2, 2), (3, 6, 6, 33, 3, 1), (1, 5, 5, 1, 2, 1),
+                                   (5, 27, 27, 256, 2, 2), (2, 13, 13, 512, 3, 2), (1, 2, 2, 1024, 2, 2),
+                                   (3, 17, 5, 96, 2, 1)])
+def test_maxpool_or(bnn, orc, shape):
+    N, H, W, C, win, st = shape
+    bits = wl.random_bits(np.random.default_rng(sum(shape)), (N, H, W), C)
+    got = words(bnn.maxpool_or(to_dev(bits), C, win, st))
+    assert np.array_equal(got, orc.maxpool_pm1(bits, C, win, st))
+
+
+def test_maxpool_or_errors(bnn):
+    bits = to_dev(wl.random_bits(np.random.default_rng(0), (1, 4, 4), 32))
+    for win, st in ((0, 1), (5, 1), (2, 0)):
+        with pytest.raises(bnn.BnnError):
+            bnn.maxpool_or(bits, 32, win, st)
+
+
+def check_cnn(bnn, orc, spec, x, path, tier):
+    layers, hw = spec["layers"], spec["in_hw"]
+    net = bnn.Net.from_layers(layers, hw)
+    xd = to_dev(x)
+    scores = host(net.forward(xd, path=path))
+    L0 = layers[0]
+    _, y = bnn.conv_f32_thr(xd, to_dev(L0["w"]), to_dev(L0["thr"]), L0["stride"], L0["pad"], want_f32=True)
+    ref0 = orc.conv_f32(x, L0["w"], L0["stride"], L0["pad"])
+    tol = 1e-4 * np.maximum(np.abs(ref0), np.sqrt((ref0.astype(np.float64) ** 2).mean()))
+    assert (np.abs(host(y) - ref0) <= tol).all()
+    ref_bits = orc.pack_f32(ref0, L0["thr"])
+    bits0 = words(net.layer_bits(0)).reshape(ref_bits.shape)
+    diff = bits0 ^ ref_bits
+    if diff.any():
+        C = L0["w"].shape[0]
+        d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), C).reshape(ref0.shape) > 0
+        assert (np.abs(ref0 - L0["thr"])[d] <= tol[d]).all()
+        print("first-layer bits inside the fp32 tolerance that differ:", int(d.sum()), flush=True)
+    outs = nets.cnn_forward(x, layers, stem_bits=bits0, tier=tier, keep=True)
+    for i in range(1, len(layers) - 1):
+        got = words(net.layer_bits(i)).reshape(outs[i].shape)
+        assert np.array_equal(got, outs[i]), "layer %d (%s) output bits" % (i, layers[i]["op"])
+    assert scores.dtype == np.int32 and np.array_equal(scores, outs[-1])
+
+
+@pytest.mark.parametrize("name,batch,path,tier", [("cifar_vgg", 5, 1, 0), ("cifar_vgg", 5, 2, 0), ("cifar_vgg", 64, 0, 1),
+                                                  ("cifar_resnet14", 5, 1, 0), ("cifar_resnet14", 5, 2, 0),
+                                                  ("cifar_resnet14", 64, 0, 1),
+                                                  ("alexnet", 3, 2, 1), ("alexnet", 16, 0, 1),
+                                                  ("vgg16", 2, 0, 1)])
+def test_table5_networks(bnn, orc, name, batch, path, tier):
+    check_cnn(bnn, orc, wl.cnn_layers(name), wl.cnn_input(name, batch), path, tier)

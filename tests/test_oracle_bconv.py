@@ -163,3 +163,21 @@ def test_sumpool_and_head(orc):
     y = orc.head_fc_f32(pooled, w, 49.0)
     yref = (pooled.astype(np.float64) / 49.0) @ w.astype(np.float64).T
     np.testing.assert_allclose(y, yref, rtol=1e-5, atol=1e-7)
+
+
+def test_maxpool_vs_torch_and_closed_forms(orc):
+    rng = np.random.default_rng(21)
+    for (N, H, W, C, win, st) in [(2, 8, 8, 40, 2, 2), (1, 7, 9, 64, 2, 2), (3, 6, 6, 33, 3, 1), (1, 5, 5, 1, 2, 1)]:
+        bits = wl.random_bits(rng, (N, H, W), C)
+        got = orc.maxpool_pm1(bits, C, win, st)
+        v = torch.from_numpy(unpack4(bits, C).astype(np.float64)).permute(0, 3, 1, 2)
+        ref = torch.nn.functional.max_pool2d(v, win, st).permute(0, 2, 3, 1).numpy()
+        assert unpack4(got, C).shape == ref.shape
+        assert (unpack4(got, C) == ref).all()
+        assert (unpack4(got, wl.nwords(C) * 32)[..., C:] < 0).all()          # pad bits stay 0
+    # all -1 stays -1; a single +1 anywhere in a window makes that window +1
+    z = np.zeros((1, 4, 4, 1), np.uint32)
+    assert (orc.maxpool_pm1(z, 32, 2, 2) == 0).all()
+    z[0, 3, 2, 0] = 1 << 7
+    o = orc.maxpool_pm1(z, 32, 2, 2)
+    assert o[0, 1, 1, 0] == 1 << 7 and o.sum() == 1 << 7

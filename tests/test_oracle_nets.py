@@ -72,3 +72,35 @@ def test_resnet_small_vs_torch(orc):
     x0[0, 0, 0, 0] ^= np.uint32(1)
     tr2 = nets.resnet18_forward(x, p, stem_bits=x0, keep=True)
     assert not np.array_equal(tr2["S0"], tr["S0"])
+
+
+def test_cnn_forward_vgg_like_vs_torch(orc):
+    # conv_f32 -> bconv -> pool -> bconv -> pool -> fc -> fc against an independent torch / numpy chain
+    rng = np.random.default_rng(31)
+    L = [{"op": "conv_f32", "w": rng.normal(0, 0.05, size=(64, 3, 3, 3)).astype(np.float32),
+          "thr": np.zeros(64, np.float32), "stride": 1, "pad": 1},
+         {"op": "bconv", "W": wl.random_bits(rng, (64, 3, 3), 64), "thr": wl.random_thresholds(rng, 64, -30, 30), "C": 64, "stride": 1, "pad": 1},
+         {"op": "pool", "win": 2, "stride": 2},
+         {"op": "bconv", "W": wl.random_bits(rng, (96, 3, 3), 64), "thr": wl.random_thresholds(rng, 96, -30, 30), "C": 64, "stride": 1, "pad": 1},
+         {"op": "pool", "win": 2, "stride": 2},
+         {"op": "fc", "W": wl.random_bits(rng, 40, 2 * 2 * 96, 12), "thr": wl.random_thresholds(rng, 40, -10, 10), "K": 2 * 2 * 96},
+         {"op": "fc", "W": wl.random_bits(rng, 7, 40, 4), "thr": None, "K": 40}]
+    x = rng.uniform(-1, 1, size=(3, 8, 8, 3)).astype(np.float32)
+    outs = nets.cnn_forward(x, L, keep=True)
+    stem = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2),
+                                      torch.from_numpy(L[0]["w"]).double().permute(0, 3, 1, 2), padding=1).permute(0, 2, 3, 1).numpy()
+    assert np.abs(stem).min() > 1e-6
+    a = np.where(stem >= 0, 1, -1).astype(np.int64)
+    assert (unpack4(outs[0], 64) == a).all()
+    a = np.where(_torch_bconv(a, L[1]["W"], 64, 1, 1) >= L[1]["thr"], 1, -1)
+    assert (unpack4(outs[1], 64) == a).all()
+    a = a.reshape(3, 4, 2, 4, 2, 64).max(axis=(2, 4))
+    assert (unpack4(outs[2], 64) == a).all()
+    a = np.where(_torch_bconv(a, L[3]["W"], 64, 1, 1) >= L[3]["thr"], 1, -1)
+    a = a.reshape(3, 2, 2, 2, 2, 96).max(axis=(2, 4))
+    assert (unpack4(outs[4], 96) == a).all()
+    flat = a.reshape(3, -1)                                           # NHWC flatten
+    v = flat @ np_unpack_pm1(L[5]["W"], 384).T
+    a = np.where(v >= L[5]["thr"], 1, -1)
+    assert (np_unpack_pm1(outs[5], 40) == a).all() and (outs[5][:, 2:] == 0).all()
+    assert (outs[6] == a @ np_unpack_pm1(L[6]["W"], 40).T).all()

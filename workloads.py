@@ -154,3 +154,69 @@ def resnet18_params(blocks=RESNET18_BLOCKS, classes: int = 1000, config: int = 5
 def resnet18_input(batch: int, hw: int = 224, config: int = 5) -> np.ndarray:
     """Synthetic images [batch][hw][hw][3] fp32 uniform in [-1, 1]; stands in for ImageNet crops."""
     return _rng(config, 0).uniform(-1.0, 1.0, size=(batch, hw, hw, 3)).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------------ Table-5 networks
+def _conv_f32_layer(rng_w, cin, cout, k, stride, pad, scale=0.05):
+    return {"op": "conv_f32", "w": rng_w.normal(0.0, scale, size=(cout, k, k, cin)).astype(np.float32),
+            "thr": np.zeros(cout, dtype=np.float32), "stride": stride, "pad": pad}
+
+
+def cnn_layers(name: str, config: int = 7) -> dict:
+    """Layer lists with the shapes of the paper's Table 5 (Cifar-10 VGG and ResNet-14, ImageNet AlexNet
+    and VGG-16); random +1/-1 weights, conv thresholds uniform integers in [-64, 64], FC thresholds in
+    [-32, 32], fp32 first layer ~ N(0, 0.05) with threshold 0.  "k x nFC" is read as k - 1 hidden layers of n
+    neurons followed by the output layer, as the benchmark configuration reads the MLP.
+    Returns {"layers", "in_hw", "classes"}."""
+    idx = [0]
+
+    def rng():
+        idx[0] += 1
+        return _rng(config, {"cifar_vgg": 100, "cifar_resnet14": 300, "alexnet": 500, "vgg16": 700}[name] + idx[0])
+
+    def bconv(cin, cout, k=3, stride=1, pad=1):
+        return {"op": "bconv", "W": random_bits(rng(), (cout, k, k), cin), "thr": random_thresholds(rng(), cout, -64, 64),
+                "C": cin, "stride": stride, "pad": pad}
+
+    def pool():
+        return {"op": "pool", "win": 2, "stride": 2}
+
+    def fc(k, n, last=False):
+        return {"op": "fc", "W": random_bits(rng(), n, k, round_up(nwords(k), 4)),
+                "thr": None if last else random_thresholds(rng(), n, -32, 32), "K": k}
+
+    def block(cin, cout, stride):
+        b = {"op": "block", "cin": cin, "cout": cout, "stride": stride,
+             "W1": random_bits(rng(), (cout, 3, 3), cin), "thr1": random_thresholds(rng(), cout, -64, 64),
+             "W2": random_bits(rng(), (cout, 3, 3), cout), "thr2": random_thresholds(rng(), cout, -64, 64)}
+        if stride != 1 or cin != cout:
+            b["Wd"] = random_bits(rng(), (cout, 1, 1), cin)
+        return b
+
+    if name == "cifar_vgg":          # (2x128C3)-MP2-(2x256C3)-MP2-(2x512C3)-MP2-(3x1024FC), 32x32x3 -> 10
+        L = [_conv_f32_layer(rng(), 3, 128, 3, 1, 1), bconv(128, 128), pool(), bconv(128, 256), bconv(256, 256), pool(),
+             bconv(256, 512), bconv(512, 512), pool(), fc(4 * 4 * 512, 1024), fc(1024, 1024), fc(1024, 10, last=True)]
+        return {"layers": L, "in_hw": 32, "classes": 10}
+    if name == "cifar_resnet14":     # 128C3/2-4x128C3-4x256C3-4x512C3-(2x512FC), 32x32x3 -> 10
+        L = [_conv_f32_layer(rng(), 3, 128, 3, 2, 1), block(128, 128, 1), block(128, 128, 1), block(128, 256, 2),
+             block(256, 256, 1), block(256, 512, 2), block(512, 512, 1), fc(4 * 4 * 512, 512), fc(512, 10, last=True)]
+        return {"layers": L, "in_hw": 32, "classes": 10}
+    if name == "alexnet":            # (128C11/4)-P2-(256C5)-P2-(3x256C3)-P2-(3x4096FC), 224x224x3 -> 1000
+        L = [_conv_f32_layer(rng(), 3, 128, 11, 4, 2, scale=0.02), pool(), bconv(128, 256, 5, 1, 2), pool(),
+             bconv(256, 256), bconv(256, 256), bconv(256, 256), pool(),
+             fc(6 * 6 * 256, 4096), fc(4096, 4096), fc(4096, 1000, last=True)]
+        return {"layers": L, "in_hw": 224, "classes": 1000}
+    if name == "vgg16":              # (2x64C3)-P2-(2x128C3)-P2-(3x256C3)-P2-2x(3x512C3-P2)-(3x4096FC), 224x224x3 -> 1000
+        L = [_conv_f32_layer(rng(), 3, 64, 3, 1, 1), bconv(64, 64), pool(), bconv(64, 128), bconv(128, 128), pool(),
+             bconv(128, 256), bconv(256, 256), bconv(256, 256), pool(),
+             bconv(256, 512), bconv(512, 512), bconv(512, 512), pool(),
+             bconv(512, 512), bconv(512, 512), bconv(512, 512), pool(),
+             fc(7 * 7 * 512, 4096), fc(4096, 4096), fc(4096, 1000, last=True)]
+        return {"layers": L, "in_hw": 224, "classes": 1000}
+    raise KeyError(name)
+
+
+def cnn_input(name: str, batch: int, config: int = 7) -> np.ndarray:
+    hw = 32 if name.startswith("cifar") else 224
+    return _rng(config, {"cifar_vgg": 1, "cifar_resnet14": 2, "alexnet": 3, "vgg16": 4}[name]).uniform(
+        -1.0, 1.0, size=(batch, hw, hw, 3)).astype(np.float32)
