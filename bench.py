@@ -34,6 +34,13 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_lds_wg256x128": 7.162e8}
 
 
+# Table 6 of the paper, BTC-FMT row (RTX 2080; trained weights, real data): context only
+PAPER_TABLE6_RTX2080 = {"cifar_vgg": {"latency8_ms": 0.338, "images_per_s": 3.85e4},
+                        "cifar_resnet14": {"latency8_ms": 0.724, "images_per_s": 1.71e4},
+                        "alexnet": {"latency8_ms": 2.326, "images_per_s": 3.77e3},
+                        "vgg16": {"latency8_ms": 7.021, "images_per_s": 1.34e3}}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -284,6 +291,28 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
         del x
     res["paper_rtx2080_images_per_s_context_only"] = PAPER_RESNET18_IMG_S
     out["resnet18_224"] = res
+    del rnet
+    # ---- the other network shapes of the paper's Table 5: 8-image latency and throughput at the paper's batch sizes
+    t5 = {}
+    for name, big in (("cifar_vgg", 1024), ("cifar_resnet14", 1024), ("alexnet", 512), ("vgg16", 512)):
+        spec = wl.cnn_layers(name)
+        net5 = bnn.Net.from_layers(spec["layers"], spec["in_hw"], device=dev)
+        r = {}
+        for batch in (big, 8):
+            x = to_dev(wl.cnn_input(name, batch))
+            o = torch.empty((batch, spec["classes"]), dtype=torch.int32, device=dev)
+            t = _time_gpu(torch, lambda: net5.forward(x, out=o), 5 if batch == big else 20)
+            r["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+            if batch == big:
+                L0 = spec["layers"][0]
+                w0, t0 = to_dev(L0["w"]), to_dev(L0["thr"])
+                ts = _time_gpu(torch, lambda: bnn.conv_f32_thr(x, w0, t0, L0["stride"], L0["pad"]), 3)
+                r["batch%d" % batch]["first_layer_fp32_ms"] = round(ts, 4)
+            del x, o
+        r["paper_rtx2080_btc_fmt_context_only"] = PAPER_TABLE6_RTX2080[name]
+        t5[name] = r
+        del net5
+    out["table5_networks"] = t5
     return out
 
 
