@@ -201,6 +201,42 @@ def conv_f32(x, w, stride: int, pad: int) -> np.ndarray:
     return y
 
 
+def bwn_conv_f32(x, wbits, C: int, stride: int, pad: int) -> np.ndarray:
+    """First layer with binarized weights (Sec. 6.1): x [N][H][W][C] fp32 (zero padded), wbits [O][k][k][cw]
+    -> fp32 [N][P][Q][O]; each input element is added or subtracted according to its weight bit."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    wbits = _words(wbits, 4)
+    N, H, W, C2 = x.shape
+    O, k, k2, cw = wbits.shape
+    assert k == k2 and C == C2 and cw == nwords(C)
+    P, Q = conv_out_size(H, k, stride, pad), conv_out_size(W, k, stride, pad)
+    y = np.empty((N, P, Q, O), dtype=np.float32)
+    _check(lib().orc_bwn_conv_f32(_p(x), _p(wbits), _p(y), _i64(N), _i64(H), _i64(W), _i64(C), _i64(O),
+                                  _i64(k), _i64(stride), _i64(pad)), "bwn_conv_f32")
+    return y
+
+
+def general_bmm_f32(A, B) -> np.ndarray:
+    """The "general" BMM of Sec. 7.2: real-valued A [M][K] and B [N][K] are binarized by Eq. 1 (x >= 0 -> +1),
+    multiplied as +1/-1 matrices (Eq. 2), and the result is returned as real values [M][N]."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    K = A.shape[1]
+    assert B.shape[1] == K
+    zero = np.zeros(K, dtype=np.float32)
+    return bmm(pack_f32(A, zero), pack_f32(B, zero), K).astype(np.float32)
+
+
+def general_bconv_f32(x, filt, stride: int, pad: int, pad_mode: int = PAD_MINUS_ONE) -> np.ndarray:
+    """The "general" BConv of Sec. 7.3: real-valued x [N][H][W][C] and filt [O][k][k][C] are binarized by
+    Eq. 1, convolved as +1/-1 tensors, and the result is returned as real values [N][P][Q][O]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    filt = np.ascontiguousarray(filt, dtype=np.float32)
+    C = x.shape[-1]
+    zero = np.zeros(C, dtype=np.float32)
+    return bconv(pack_f32(x, zero), pack_f32(filt, zero), C, stride, pad, pad_mode).astype(np.float32)
+
+
 def sumpool_pm1(bits, C: int) -> np.ndarray:
     """bits [N][H][W][cw] -> int32 [N][C]: sum of +1/-1 over all H*W positions."""
     bits = _words(bits, 4)

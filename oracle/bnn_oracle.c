@@ -238,6 +238,40 @@ int orc_conv_f32(const float* x, const float* w, float* y,
     return 0;
 }
 
+/* First layer with binarized weights only (Sec. 6.1, "BWN"): the input stays real-valued, every weight
+ * is one bit, and the bit decides whether the input element is added (bit 1, +1) or subtracted (bit 0,
+ * -1).  x [N][H][W][C] fp32, out-of-frame positions contribute nothing (zero padding of a real-valued
+ * image); wbits [O][k][k][cw] packed along C; y [N][P][Q][O] fp32, accumulated in double. */
+int orc_bwn_conv_f32(const float* x, const uint32_t* wbits, float* y,
+                     int64_t N, int64_t H, int64_t W, int64_t C, int64_t O,
+                     int64_t k, int64_t stride, int64_t pad) {
+    if (!x || !wbits || !y || N < 0 || H <= 0 || W <= 0 || C <= 0 || O <= 0 || k <= 0 || stride <= 0 || pad < 0) return 2;
+    const int64_t P = (H + 2 * pad - k) / stride + 1;
+    const int64_t Q = (W + 2 * pad - k) / stride + 1;
+    const int64_t cw = (C + 31) / 32;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                for (int64_t o = 0; o < O; ++o) {
+                    double s = 0.0;
+                    for (int64_t r = 0; r < k; ++r)
+                        for (int64_t t = 0; t < k; ++t) {
+                            const int64_t yy = p * stride - pad + r;
+                            const int64_t xx = q * stride - pad + t;
+                            if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+                            const float* xv = x + ((n * H + yy) * W + xx) * C;
+                            const uint32_t* wv = wbits + ((o * k + r) * k + t) * cw;
+                            for (int64_t c = 0; c < C; ++c) {
+                                if (bit_at(wv, c)) s += (double)xv[c];
+                                else s -= (double)xv[c];
+                            }
+                        }
+                    y[((n * P + p) * Q + q) * O + o] = (float)s;
+                }
+    return 0;
+}
+
 /* Sum of +1/-1 over the HW positions of each channel: bits [N][HW][cw] -> pooled [N][C] int32 */
 int orc_sumpool_pm1(const uint32_t* bits, int32_t* pooled, int64_t N, int64_t HW, int64_t C) {
     if (!bits || !pooled || N < 0 || HW <= 0 || C <= 0) return 2;

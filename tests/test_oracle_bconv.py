@@ -181,3 +181,43 @@ def test_maxpool_vs_torch_and_closed_forms(orc):
     z[0, 3, 2, 0] = 1 << 7
     o = orc.maxpool_pm1(z, 32, 2, 2)
     assert o[0, 1, 1, 0] == 1 << 7 and o.sum() == 1 << 7
+
+
+def test_bwn_first_layer_vs_torch_and_closed_forms(orc):
+    rng = np.random.default_rng(77)
+    for (N, H, W, C, O, k, st, pad) in [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 8, 3, 40, 3, 1, 1), (2, 23, 23, 3, 7, 11, 4, 2),
+                                        (1, 6, 6, 35, 3, 3, 2, 1), (1, 5, 5, 1, 2, 1, 1, 0)]:
+        x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
+        wb = wl.random_bits(rng, (O, k, k), C)
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2),
+                                         torch.from_numpy(unpack4(wb, C).astype(np.float64)).permute(0, 3, 1, 2),
+                                         stride=st, padding=pad).permute(0, 2, 3, 1).numpy()
+        got = orc.bwn_conv_f32(x, wb, C, st, pad)
+        assert got.shape == ref.shape
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-6)
+        # same numbers as the real-valued convolution with the weights written out as +1.0 / -1.0
+        np.testing.assert_allclose(got, orc.conv_f32(x, unpack4(wb, C).astype(np.float32), st, pad), rtol=1e-6, atol=1e-6)
+    # all-ones weight bits: a box sum over the in-frame window; all-zero bits: its negation
+    x = rng.uniform(-1, 1, size=(1, 6, 7, 3)).astype(np.float32)
+    ones = np.full((1, 3, 3, 1), 0b111, np.uint32)
+    xp = np.zeros((8, 9, 3))
+    xp[1:-1, 1:-1] = x[0]
+    box = sum(xp[r:r + 6, s:s + 7].sum(axis=2) for r in range(3) for s in range(3))
+    np.testing.assert_allclose(orc.bwn_conv_f32(x, ones, 3, 1, 1)[0, :, :, 0], box, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(orc.bwn_conv_f32(x, np.zeros_like(ones), 3, 1, 1)[0, :, :, 0], -box, rtol=1e-6, atol=1e-6)
+
+
+def test_general_forms_vs_numpy_sign(orc):
+    rng = np.random.default_rng(78)
+    A = rng.normal(size=(9, 70)).astype(np.float32)
+    B = rng.normal(size=(5, 70)).astype(np.float32)
+    A[0, 0] = 0.0                                         # Eq. 1: zero binarizes to +1
+    B[1, 3] = -0.0
+    sa, sb = np.where(A >= 0, 1, -1), np.where(B >= 0, 1, -1)
+    got = orc.general_bmm_f32(A, B)
+    assert got.dtype == np.float32 and (got == sa @ sb.T).all()
+    x = rng.normal(size=(2, 6, 5, 40)).astype(np.float32)
+    f = rng.normal(size=(3, 3, 3, 40)).astype(np.float32)
+    for pm, pv in ((0, -1), (1, 0)):
+        ref = conv_by_padding(np.where(x >= 0, 1, -1), np.where(f >= 0, 1, -1), 1, 1, pv)
+        assert (orc.general_bconv_f32(x, f, 1, 1, pm) == ref).all()
