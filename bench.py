@@ -304,10 +304,21 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
             t = _time_gpu(torch, lambda: net5.forward(x, out=o), 5 if batch == big else 20)
             r["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
             if batch == big:
+                # the first layer alone: binarized weights on the bf16 matrix cores (what the network uses, Sec. 6.1),
+                # and the same shape with real-valued weights on the fp32 matrix cores
                 L0 = spec["layers"][0]
-                w0, t0 = to_dev(L0["w"]), to_dev(L0["thr"])
-                ts = _time_gpu(torch, lambda: bnn.conv_f32_thr(x, w0, t0, L0["stride"], L0["pad"]), 3)
-                r["batch%d" % batch]["first_layer_fp32_ms"] = round(ts, 4)
+                wb, t0 = to_dev(L0["W"]), to_dev(L0["thr"])
+                O0, k0 = L0["W"].shape[0], L0["W"].shape[1]
+                wf = torch.randn((O0, k0, k0, L0["C"]), dtype=torch.float32, device=dev) * 0.05
+                tb = _time_gpu(torch, lambda: bnn.bwn_conv_thr(x, wb, t0, L0["C"], L0["stride"], L0["pad"]), 5)
+                tf = _time_gpu(torch, lambda: bnn.conv_f32_thr(x, wf, t0, L0["stride"], L0["pad"]), 3)
+                hw0 = (spec["in_hw"] + 2 * L0["pad"] - k0) // L0["stride"] + 1
+                flop = 2.0 * batch * hw0 * hw0 * O0 * k0 * k0 * L0["C"]
+                r["batch%d" % batch]["first_layer_bwn_ms"] = round(tb, 4)
+                r["batch%d" % batch]["first_layer_bwn_tflops"] = round(flop / tb / 1e9, 1)
+                r["batch%d" % batch]["first_layer_bwn_hbm_gbs"] = round(
+                    (x.numel() * 4 + batch * hw0 * hw0 * O0 / 8) / tb / 1e6, 1)
+                r["batch%d" % batch]["same_shape_fp32_weights_ms"] = round(tf, 4)
             del x, o
         r["paper_rtx2080_btc_fmt_context_only"] = PAPER_TABLE6_RTX2080[name]
         t5[name] = r

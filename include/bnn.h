@@ -141,6 +141,18 @@ int bnn_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C
  *   y_f32 [N][P][Q][O] fp32 or NULL, bits [N][P][Q][ceil(O/32)] or NULL (not both NULL). */
 int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
                      int N, int H, int W, int C, int O, int k, int stride, int pad, void* stream);
+/* First layer with binarized weights only (Sec. 6.1, "BWN"): the input stays real-valued, each weight is one
+ * bit that decides whether the input element is added (bit 1) or subtracted (bit 0); zero padding;
+ * bits = (y >= thr[o]).  fp32 accumulation (every product is exact), 1e-4 relative like the layer above.
+ *   x [N][H][W][C] fp32 (finite values), wbits [O][k][k][ceil(C/32)] packed along C (pad bits 0), thr [O] fp32,
+ *   y_f32 [N][P][Q][O] fp32 or NULL, bits [N][P][Q][ceil(O/32)] or NULL (not both NULL).
+ *   workspace: device scratch of at least bnn_bwn_workspace_bytes(C, O, k) bytes, 16-byte aligned (it receives
+ *   the weights expanded to bf16 in matrix-core operand order; contents are not needed after the call).
+ *   N*P*Q < 2^31.  k*ceil(k*C/8) above about 80 (64 output channels: 160) does not fit LDS: BNN_ERR_UNSUPPORTED. */
+size_t bnn_bwn_workspace_bytes(int C, int O, int k);
+int bnn_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, float* y_f32, uint32_t* bits,
+                     int N, int H, int W, int C, int O, int k, int stride, int pad,
+                     void* workspace, size_t workspace_bytes, void* stream);
 /* pooled[n][c] = sum over HW positions of the +1/-1 value of channel c (exact integer);
  * y[n][j] = sum_c (pooled[n][c] / HW) * w[j][c].
  *   bits [N][HW][ceil(C/32)], w [J][C] fp32, y [N][J] fp32, pooled_out [N][C] int32 or NULL.
@@ -164,6 +176,8 @@ int bnn_net_input_u8(bnn_net* net, int cols, int thr);                       /* 
 int bnn_net_input_bits(bnn_net* net, int cols);                             /* [batch][ld_w] packed bits, ld_w = ceil(cols/32) rounded up to 4 */
 int bnn_net_input_conv_f32(bnn_net* net, const float* w, const float* thr, /* [batch][H][W][C] fp32 -> stem conv -> bits */
                            int H, int W, int C, int O, int k, int stride, int pad);
+int bnn_net_input_bwn_f32(bnn_net* net, const uint32_t* wbits, const float* thr, /* same, weights as bits (bnn_bwn_conv_thr) */
+                          int H, int W, int C, int O, int k, int stride, int pad);
 /* Binarized fully-connected layer, W [N][ldw_w] with ldw_w = ceil(K/32) rounded up to 4.
  * thr != NULL: output bits; thr == NULL: int32 scores [batch][N] (only as the last layer). */
 int bnn_net_add_fc(bnn_net* net, const uint32_t* W, const int32_t* thr, int K, int N);

@@ -87,6 +87,7 @@ def cnn_forward(x_f32: np.ndarray, layers: list, stem_bits: np.ndarray | None = 
 
     ``layers`` is a list of dicts, one per layer:
       {"op": "conv_f32", "w", "thr", "stride", "pad"}          first layer: fp32 conv (zero pad) then x >= thr
+      {"op": "bwn", "W", "thr", "C", "stride", "pad"}          first layer: real input, weight bits (add / subtract)
       {"op": "bconv", "W", "thr", "C", "stride", "pad"}        binarized conv (-1 padding) + threshold
       {"op": "pool", "win", "stride"}                          max-pooling of +1/-1 values
       {"op": "block", "W1","thr1","W2","thr2",["Wd"],"cin","cout","stride"}   residual block as in resnet18_forward
@@ -103,6 +104,12 @@ def cnn_forward(x_f32: np.ndarray, layers: list, stem_bits: np.ndarray | None = 
             y = orc.conv_f32(x_f32, L["w"], L["stride"], L["pad"])
             x = orc.pack_f32(y, L["thr"]) if stem_bits is None else np.ascontiguousarray(stem_bits, np.uint32)
             C = L["w"].shape[0]
+            R = None
+            outs.append(x)
+        elif op == "bwn":
+            y = orc.bwn_conv_f32(x_f32, L["W"], L["C"], L["stride"], L["pad"])
+            x = orc.pack_f32(y, L["thr"]) if stem_bits is None else np.ascontiguousarray(stem_bits, np.uint32)
+            C = L["W"].shape[0]
             R = None
             outs.append(x)
         elif op == "bconv":

@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "maxpool_or", "conv_f32_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,8 +24,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_head_f32", "bnn_net_create",
-           "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_add_fc",
+           "bnn_pack_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
            "bnn_net_forward", "bnn_net_layer_bits"]
 
@@ -56,6 +56,7 @@ def load() -> ctypes.CDLL:
         lib.bnn_status_string.argtypes = [ctypes.c_int]
         lib.bnn_bmm_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bconv_kernel_name.restype = ctypes.c_char_p
+        lib.bnn_bwn_workspace_bytes.restype = ctypes.c_size_t
         for name in EXPORTS:
             getattr(lib, name)          # fail loudly on a missing export
         _lib = lib
@@ -255,6 +256,25 @@ def conv_f32_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False):
     return (bits, y) if want_f32 else bits
 
 
+def bwn_conv_thr(x, wbits, thr, C: int, stride: int, pad: int, want_f32: bool = False, workspace=None):
+    """First layer with binarized weights: x [N][H][W][C] fp32, wbits [O][k][k][cw], thr [O] -> bits (and fp32 y)."""
+    _dev(x, torch.float32, 4, "x"); _dev(wbits, _BITS, 4, "wbits"); _dev(thr, torch.float32, 1, "thr")
+    N, H, W, C2 = x.shape
+    O, k, _, cw = wbits.shape
+    if C != C2 or cw != nwords(C):
+        raise ValueError("channel mismatch")
+    P = (H + 2 * pad - k) // stride + 1
+    Q = (W + 2 * pad - k) // stride + 1
+    bits = torch.empty((N, P, Q, nwords(O)), dtype=_BITS, device=x.device)
+    y = torch.empty((N, P, Q, O), dtype=torch.float32, device=x.device) if want_f32 else None
+    if workspace is None:
+        workspace = torch.empty(max(int(load().bnn_bwn_workspace_bytes(C, O, k)), 16), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_bwn_conv_thr(_ptr(x), _ptr(wbits), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride), int(pad),
+                                       _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(x)), "bnn_bwn_conv_thr")
+    return (bits, y) if want_f32 else bits
+
+
 def head_f32(bits, w, C: int, want_pooled: bool = False):
     """bits [N][H][W][cw] -> fp32 logits [N][J] = FC(sum-pool(+1/-1) / HW); w [J][C]."""
     _dev(bits, _BITS, 4, "bits"); _dev(w, torch.float32, 2, "w")
@@ -306,6 +326,16 @@ class Net:
         self._in_dtype = torch.float32
         self._added(w, thr)
 
+    def input_bwn_f32(self, wbits, thr, H: int, W: int, C: int, stride: int, pad: int):
+        _dev(wbits, _BITS, 4, "wbits"); _dev(thr, torch.float32, 1, "thr")
+        O, k, _, cw = wbits.shape
+        if cw != nwords(C):
+            raise ValueError("channel mismatch")
+        _check(load().bnn_net_input_bwn_f32(self._h, _ptr(wbits), _ptr(thr), int(H), int(W), int(C), O, k, int(stride), int(pad)),
+               "bnn_net_input_bwn_f32")
+        self._in_dtype = torch.float32
+        self._added(wbits, thr)
+
     def add_fc(self, W, thr, K: int):
         _dev(W, _BITS, 2, "W")
         if thr is not None:
@@ -355,6 +385,8 @@ class Net:
             op = L["op"]
             if op == "conv_f32":
                 net.input_conv_f32(dev(L["w"]), dev(L["thr"]), in_hw, in_hw, L["stride"], L["pad"])
+            elif op == "bwn":
+                net.input_bwn_f32(dev(L["W"]), dev(L["thr"]), in_hw, in_hw, L["C"], L["stride"], L["pad"])
             elif op == "bconv":
                 net.add_conv(dev(L["W"]), dev(L["thr"]), L["C"], L["stride"], L["pad"])
             elif op == "pool":

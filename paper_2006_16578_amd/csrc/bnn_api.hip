@@ -106,6 +106,7 @@ struct bnn_net {
         int H = 1, W = 1, C = 0;
         size_t bits_off = 0; int words_per_row = 0; long long rows_per_image = 1;
         long long sum_bound = 0;      // BLOCK: largest |S| this block can produce
+        bool bwn = false;             // IN_CONV_F32: w0 holds weight bits (first layer with binarized weights)
     };
     std::vector<Layer> layers;
     // results of the last forward, for bnn_net_layer_bits
@@ -124,6 +125,7 @@ struct Plan {
     size_t total = 0;
     size_t resid_off[3] = {0, 0, 0};
     size_t resid_bytes = 0;
+    size_t bwn_off = 0, bwn_bytes = 0;   // expanded first-layer weights (first layer with binarized weights only)
     int rc = BNN_OK;
 };
 
@@ -192,6 +194,10 @@ Plan plan(bnn_net* net, int batch) {
     if (have_resid) {
         pl.resid_bytes = align256(max_resid);
         for (int r = 0; r < 3; ++r) { pl.resid_off[r] = off; off += pl.resid_bytes; }
+    }
+    if (net->layers[0].kind == bnn_net::IN_CONV_F32 && net->layers[0].bwn) {
+        const bnn_net::Layer& L0 = net->layers[0];
+        pl.bwn_off = off; pl.bwn_bytes = bwn_workspace_bytes(L0.c, L0.d, L0.k); off += align256(pl.bwn_bytes);
     }
     pl.total = off;
     return pl;
@@ -305,6 +311,23 @@ int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_
     if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
     return launch_conv_f32_thr(x, w, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, static_cast<hipStream_t>(stream));
 }
+size_t bnn_bwn_workspace_bytes(int C, int O, int k) {
+    if (C < 1 || O < 1 || k < 1 || (long long)k * C > (1 << 16)) return 0;
+    return bwn_workspace_bytes(C, O, k);
+}
+int bnn_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, float* y_f32, uint32_t* bits, int N, int H,
+                     int W, int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !wbits || (!y_f32 && !bits) || (bits && !thr)) return BNN_ERR_INVALID_ARG;
+    if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0) return BNN_ERR_INVALID_ARG;
+    if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
+    const long long P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    if ((long long)N * P * Q >= (1LL << 31) || (long long)k * C > (1 << 16) || (long long)W * C >= (1LL << 30))
+        return BNN_ERR_UNSUPPORTED;
+    if (!workspace) return BNN_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return BNN_ERR_ALIGNMENT;
+    return launch_bwn_conv_thr(x, wbits, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, workspace, workspace_bytes,
+                               static_cast<hipStream_t>(stream));
+}
 int bnn_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled_out, int N, int HW, int C, int J,
                  void* stream) {
     if (!bits || !w || !y || N < 1 || HW < 1 || C < 1 || J < 1) return BNN_ERR_INVALID_ARG;
@@ -342,6 +365,12 @@ int bnn_net_input_conv_f32(bnn_net* net, const float* w, const float* thr, int H
     L.a = H; L.b = W; L.c = C; L.d = O; L.k = k; L.stride = stride; L.pad = pad;
     net->layers.push_back(L);
     return BNN_OK;
+}
+int bnn_net_input_bwn_f32(bnn_net* net, const uint32_t* wbits, const float* thr, int H, int W, int C, int O, int k,
+                          int stride, int pad) {
+    const int rc = bnn_net_input_conv_f32(net, reinterpret_cast<const float*>(wbits), thr, H, W, C, O, k, stride, pad);
+    if (rc == BNN_OK) net->layers.back().bwn = true;
+    return rc;
 }
 int bnn_net_add_fc(bnn_net* net, const uint32_t* W, const int32_t* thr, int K, int N) {
     if (!net || !W || K < 1 || N < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
@@ -424,9 +453,12 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 obits = const_cast<uint32_t*>(static_cast<const uint32_t*>(input));   // used in place
                 break;
             case bnn_net::IN_CONV_F32:
-                rc = bnn_conv_f32_thr(static_cast<const float*>(input), static_cast<const float*>(L.w0),
-                                      static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,
-                                      L.stride, L.pad, stream);
+                rc = L.bwn ? bnn_bwn_conv_thr(static_cast<const float*>(input), static_cast<const uint32_t*>(L.w0),
+                                              static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,
+                                              L.stride, L.pad, ws + pl.bwn_off, pl.bwn_bytes, stream)
+                           : bnn_conv_f32_thr(static_cast<const float*>(input), static_cast<const float*>(L.w0),
+                                              static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,
+                                              L.stride, L.pad, stream);
                 R = nullptr;
                 break;
             case bnn_net::FC: {

@@ -1,0 +1,635 @@
+// First layer with binarized weights (paper Sec. 6.1, "BWN"): real-valued NHWC input, one bit per
+// weight, out[n][p][q][o] = sum over the window of (+x if the weight bit is 1, -x if it is 0), zero
+// padding, then the fused threshold -> packed bits.
+//
+// gfx950 design.  The paper adds or subtracts element by element on the scalar cores because Turing's
+// bit tensor cores cannot take a real-valued operand.  Here the layer runs on the bf16 matrix cores
+// (16x the fp32 MFMA rate) without giving up fp32 inputs: every fp32 input value is split exactly into
+// three bf16 terms x = h + m + l (8 significant bits each), the +1/-1 weights are exact in bf16, so each
+// product is exact and the sum is accumulated in fp32 by v_mfma_f32_32x32x16_bf16 -- the same result, up
+// to the order of the fp32 additions, as an fp32 multiply-accumulate.
+//
+// Implicit GEMM: a GEMM row is an output pixel, a column an output channel.  K is covered by "runs" of
+// 8 consecutive elements of one filter row (the k*C values of a filter row are contiguous in NHWC): a lane
+// supplies the 8 K-slots of its half-wave for one MFMA from one run.  K-slots that would count an element
+// twice or that hold no element get weight 0, so the input side needs no mask for them.  A small kernel
+// first expands the weight bits into bf16 in fragment order [channel tile][run][channel][8 x bf16]
+// (caller's workspace); every workgroup copies its channel tile to LDS with plain 16-byte loads and reads
+// one 16-byte unit per MFMA operand.
+//
+// Two kernels:
+//  * LDS-staged (default).  A workgroup owns a rectangle of output pixels of one image.  It loads the
+//    input patch under that rectangle once with coalesced loads, splits every value once, and keeps the
+//    three bf16 planes in LDS ([plane][patch row][pixel][Cp], Cp = C padded so that a pixel step is a
+//    multiple of 8 bytes).  The K loop then only reads LDS (two 8-byte reads per operand) and issues MFMAs;
+//    zero padding is written at staging time.  This removes the k*k/stride^2-fold re-splitting and
+//    re-masking of the same input value by neighbouring output pixels that bounds the direct kernel.
+//  * Direct (fallback when patch + weights exceed LDS).  Every lane loads its runs straight from global
+//    memory two K-steps ahead and splits them in registers.
+#include <type_traits>
+
+#include "bnn_internal.h"
+
+namespace bnn {
+namespace {
+
+typedef float v16f_bwn __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf_bwn __attribute__((ext_vector_type(8)));
+typedef float float4_ub __attribute__((ext_vector_type(4), aligned(4)));
+extern "C" __device__ int bnn_bwn_writelane_i32(int val, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
+struct Split3 {
+    uint4 h, m, l;      // 8 bf16 each: x = h + m + l exactly
+};
+
+// Exact three-way split of 8 floats into bf16 terms, packed two per register (element 2p in the low half).
+__device__ __forceinline__ Split3 split3(const float (&x)[8]) {
+    Split3 s;
+    uint32_t hw[4], mw[4], lw[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float x0 = x[2 * p], x1 = x[2 * p + 1];
+        const uint32_t u0 = __float_as_uint(x0), u1 = __float_as_uint(x1);
+        hw[p] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);                 // upper halves = truncation to bf16
+        const float r0 = x0 - __uint_as_float(u0 & 0xffff0000u);            // exact: at most 16 significant bits left
+        const float r1 = x1 - __uint_as_float(u1 & 0xffff0000u);
+        const uint32_t v0 = __float_as_uint(r0), v1 = __float_as_uint(r1);
+        mw[p] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);
+        const float l0 = r0 - __uint_as_float(v0 & 0xffff0000u);            // exact: at most 8 significant bits left
+        const float l1 = r1 - __uint_as_float(v1 & 0xffff0000u);
+        lw[p] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
+    }
+    s.h = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+    s.m = make_uint4(mw[0], mw[1], mw[2], mw[3]);
+    s.l = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    return s;
+}
+
+// Expands weight bits to bf16 +1.0 / -1.0 / 0: one thread per 16-byte unit (8 K-slots of one run of one
+// channel).  wexp [col_tiles][2 * nsteps][cols] units.  A filter row is seg = k*Cp slots (channel c of tap t at
+// slot t*Cp + c, channels >= C are padding); run j of a row starts at slot 8*j, or, with `moveback`, the last
+// run is moved back to end at seg and the slots it shares with the run before get weight 0.
+__global__ __launch_bounds__(256) void bwn_expand_kernel(const uint32_t* __restrict__ wbits, uint4* __restrict__ wexp, int C, int Cp,
+                                                         int O, int k, int cols, int moveback, int nunits) {
+    const int u = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (u >= nunits) return;
+    const int seg = k * Cp, rpr = (seg + 7) >> 3, nruns = k * rpr, nsteps = (nruns + 1) >> 1;
+    const int last0 = seg >= 8 ? seg - 8 : 0, cw = (C + 31) >> 5;
+    const int per_tile = 2 * nsteps * cols;
+    const int tile = u / per_tile, v = u - tile * per_tile;
+    const int rho = v / cols, col = v - rho * cols;
+    const int o = tile * cols + col;
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    if (rho < nruns && o < O) {
+        const int r = rho / rpr, j = rho - r * rpr;
+        const int e0 = moveback ? min(8 * j, last0) : 8 * j;
+        int t = e0 / Cp, c = e0 - t * Cp;
+        const uint32_t* wrow = wbits + ((long long)o * k + r) * k * cw;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int e = e0 + s;
+            uint32_t val = 0u;
+            if (e < seg && e >= 8 * j && c < C) {
+                const uint32_t b = (wrow[t * cw + (c >> 5)] >> (c & 31)) & 1u;
+                val = b ? 0x3F80u : 0xBF80u;
+            }
+            pk[s >> 1] |= val << (16 * (s & 1));
+            if (++c == Cp) { c = 0; ++t; }
+        }
+    }
+    wexp[u] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+}
+
+// ------------------------------------------------------------------------------------------ LDS-staged
+struct BwnTile {            // geometry of the LDS-staged kernel, computed on the host
+    int H, W, C, Cp, O, stride, pad, P, Q, k;
+    int FQ, FP;             // a 32-pixel fragment is FP rows x FQ columns of output pixels (FP * FQ = 32)
+    int TP;                 // output rows per workgroup (= WAVES * MT * FP); its columns are one fragment wide
+    int tiles_p, tiles_q;
+    int PR;                 // patch rows
+    int PC, PCC;            // patch pixels per row; bf16 elements of a patch row that hold data (PC * Cp)
+    int pitch;              // bytes between patch rows of a plane: multiple of 8, >= 2 * PCC + 16
+    int rpr, nsteps;        // runs per filter row, MFMA K-steps
+    int wbytes;             // bytes of expanded weights in LDS (patch planes follow)
+    FastDiv div_tiles, div_tq, div_row, div_cp, div_fq, div_pc;
+};
+
+template <int MT, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
+                                                                const float* __restrict__ thr, float* __restrict__ y,
+                                                                uint32_t* __restrict__ bits, BwnTile g) {
+    constexpr int COLS = NT * 32, NTHR = WAVES * 64;
+    extern __shared__ uint4 smem[];
+    uint4* wlds = smem;                                               // [2 * nsteps][COLS] units of 8 bf16
+    char* patch = reinterpret_cast<char*>(smem) + g.wbytes;           // [3 planes][PR][pitch bytes]
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5, wave = tid >> 6;
+    const int n0 = (int)blockIdx.y * COLS;
+    const int plane = g.PR * g.pitch;
+
+    // workgroup -> image, tile row, tile column
+    const int blk = (int)blockIdx.x;
+    const int n = fast_div(blk, g.div_tiles);
+    const int trem = blk - n * (g.tiles_p * g.tiles_q);
+    const int tp = fast_div(trem, g.div_tq), tq = trem - tp * g.tiles_q;
+    const int p0 = tp * g.TP, q0 = tq * g.FQ;
+    const int y0 = p0 * g.stride - g.pad, x0 = q0 * g.stride - g.pad;
+
+    {   // expanded weights of this channel tile -> LDS
+        const int nunits = 2 * g.nsteps * COLS;
+        const uint4* src = wexp + (long long)blockIdx.y * nunits;
+        for (int base = 0; base < nunits; base += 4 * NTHR) {
+            uint4 tmp[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) tmp[q] = src[min(base + q * NTHR + tid, nunits - 1)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int u = base + q * NTHR + tid;
+                if (u < nunits) wlds[u] = tmp[q];
+            }
+        }
+    }
+    {   // input patch -> three bf16 planes; out-of-image positions, padding channels and row slack become 0
+        const float* ximg = x + (long long)n * g.H * g.W * g.C;
+        auto put = [&](int off, float v) {                            // exact three-way split of one value
+            const uint32_t a = __float_as_uint(v);
+            const float r1 = v - __uint_as_float(a & 0xffff0000u);
+            const uint32_t b = __float_as_uint(r1);
+            const float r2 = r1 - __uint_as_float(b & 0xffff0000u);  // fits bf16
+            *reinterpret_cast<unsigned short*>(patch + off) = (unsigned short)(a >> 16);
+            *reinterpret_cast<unsigned short*>(patch + plane + off) = (unsigned short)(b >> 16);
+            *reinterpret_cast<unsigned short*>(patch + 2 * plane + off) = (unsigned short)(__float_as_uint(r2) >> 16);
+        };
+        if (g.C <= 4) {
+            // one patch pixel per thread and pass, four passes in flight
+            const int npx = g.PR * g.PC;
+            for (int base = 0; base < npx; base += 4 * NTHR) {
+                float v[4][4];
+                int off[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = base + u * NTHR + tid;
+                    const int r = fast_div(e, g.div_pc), px = e - r * g.PC;
+                    const int yy = y0 + r, xx = x0 + px;
+                    const bool ok = e < npx && (unsigned)yy < (unsigned)g.H && (unsigned)xx < (unsigned)g.W;
+                    const float* src = ximg + ((long long)yy * g.W + xx) * g.C;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        v[u][c] = 0.f;
+                        if (ok && c < g.C) v[u][c] = src[c];
+                    }
+                    off[u] = e < npx ? r * g.pitch + px * g.Cp * 2 : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (off[u] < 0) continue;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (c < g.Cp) put(off[u] + 2 * c, v[u][c]);
+                }
+            }
+            // slack behind the last pixel of every row
+            const int slack = (g.pitch - 2 * g.PCC) >> 1;
+            for (int e = tid; e < g.PR * slack; e += NTHR) {
+                const int r = e / slack, i2 = e - r * slack;
+                put(r * g.pitch + 2 * (g.PCC + i2), 0.f);
+            }
+        } else {
+            const int epr = g.pitch >> 1;                             // bf16 slots per patch row
+            const int total = g.PR * epr;
+            for (int base = 0; base < total; base += 4 * NTHR) {
+                float v[4];
+                int off[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = base + u * NTHR + tid;
+                    const int r = fast_div(e, g.div_row);
+                    const int rem = e - r * epr;
+                    const int px = fast_div(rem, g.div_cp), c = rem - px * g.Cp;
+                    const int yy = y0 + r, xx = x0 + px;
+                    const bool ok = e < total && rem < g.PCC && c < g.C && (unsigned)yy < (unsigned)g.H && (unsigned)xx < (unsigned)g.W;
+                    v[u] = 0.f;
+                    if (ok) v[u] = ximg[((long long)yy * g.W + xx) * g.C + c];
+                    off[u] = e < total ? r * g.pitch + rem * 2 : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (off[u] >= 0) put(off[u], v[u]);
+            }
+        }
+    }
+    __syncthreads();
+
+    // fragment i of this wave: output rows p0 + (wave*MT + i)*FP + dp, column q0 + dq
+    const int dp = fast_div(l32, g.div_fq), dq = l32 - dp * g.FQ;
+    if (p0 + wave * MT * g.FP >= g.P) return;                         // nothing of this wave is inside the image
+    int abase[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) abase[i] = (((wave * MT + i) * g.FP + dp) * g.stride) * g.pitch + dq * g.stride * g.Cp * 2;
+
+    v16f_bwn acc[MT][NT];
+
+    // this lane's run index is 2*step + half; (rr, jj) = (filter row, run within the row).  A run index past
+    // the last one (odd run count, upper half-wave) re-reads the last run against zero weights.
+    int rr = half / g.rpr, jj = half - rr * g.rpr;
+    auto advance = [&]() {
+        jj += 2;
+        while (jj >= g.rpr) { jj -= g.rpr; ++rr; }
+        if (rr >= g.k) { rr = g.k - 1; jj = g.rpr - 1; }
+    };
+    if (rr >= g.k) { rr = g.k - 1; jj = g.rpr - 1; }
+    auto load_a = [&](uint4 (&a)[MT][3]) {
+        const int off = rr * g.pitch + jj * 16;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) {
+                const char* src = patch + pl * plane + abase[i] + off;
+                const uint2 lo = *reinterpret_cast<const uint2*>(src);
+                const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
+                a[i][pl] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+    };
+    auto load_b = [&](int step, uint4 (&b)[NT]) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) b[j] = wlds[(2 * step + half) * COLS + 32 * j + l32];
+    };
+    auto multiply = [&](const uint4 (&a)[MT][3], const uint4 (&b)[NT], auto first) {
+        const v16f_bwn zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int pl = 2; pl >= 0; --pl)                               // smallest terms first
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, a[i][pl]),
+                                                                         __builtin_bit_cast(v8bf_bwn, b[j]),
+                                                                         (decltype(first)::value && pl == 2) ? zero : acc[i][j], 0, 0, 0);
+    };
+
+    // the first K-step starts the accumulators from a constant 0 (no register clearing)
+    uint4 a0[MT][3], a1[MT][3], b0[NT], b1[NT];
+    load_a(a0); load_b(0, b0);
+    if (g.nsteps > 1) { advance(); load_a(a1); load_b(1, b1); }
+    multiply(a0, b0, std::true_type{});
+    for (int step = 1; step < g.nsteps; step += 2) {
+        if (step + 1 < g.nsteps) { advance(); load_a(a0); load_b(step + 1, b0); }
+        multiply(a1, b1, std::false_type{});
+        if (step + 1 < g.nsteps) {
+            if (step + 2 < g.nsteps) { advance(); load_a(a1); load_b(step + 2, b1); }
+            multiply(a0, b0, std::false_type{});
+        }
+    }
+
+    float th[NT];
+    bool cok[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < g.O;
+        th[j] = (bits != nullptr && cok[j]) ? thr[col] : __builtin_inff();
+    }
+    const int ow = (g.O + 31) / 32;
+    const long long img_pix = (long long)n * g.P * g.Q;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int frow0 = p0 + (wave * MT + i) * g.FP;                // first output row of the fragment
+        if (frow0 >= g.P) break;
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int lo_row = 8 * (r >> 2) + (r & 3);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const float v = acc[i][j][r];
+                if (y != nullptr) {
+                    const int m = lo_row + 4 * half;                  // fragment row of this register in this lane
+                    const int mp = fast_div(m, g.div_fq), mq = m - mp * g.FQ;
+                    if (frow0 + mp < g.P && q0 + mq < g.Q && cok[j])
+                        y[(img_pix + (long long)(frow0 + mp) * g.Q + q0 + mq) * g.O + n0 + 32 * j + l32] = v;
+                }
+                if (bits != nullptr) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= th[j]);
+                    wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)ball, lo_row, (int)wout[j]);
+                    wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)(ball >> 32), lo_row + 4, (int)wout[j]);
+                }
+            }
+        }
+        // lane m < 32 holds the packed words of fragment row m = output pixel (frow0 + dp, q0 + dq)
+        if (bits != nullptr && lane < 32 && frow0 + dp < g.P && q0 + dq < g.Q) {
+            const long long pix = img_pix + (long long)(frow0 + dp) * g.Q + q0 + dq;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int wi = (n0 >> 5) + j;
+                if (wi < ow) bits[pix * ow + wi] = wout[j];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ direct
+// MT x NT accumulator tiles of 32x32 per wave, WAVES waves per workgroup (they share the weights in LDS), each wave walks `tiles_per_wave`
+// consecutive groups of MT*32 output pixels; the workgroup covers NT*32 output channels.
+template <int MT, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
+                                                       const float* __restrict__ thr, float* __restrict__ y,
+                                                       uint32_t* __restrict__ bits, int N, int H, int W, int C, int O,
+                                                       int k, int stride, int pad, int P, int Q, FastDiv div_pq, FastDiv div_q,
+                                                       int tiles_per_wave) {
+    constexpr int COLS = NT * 32, NTHR = WAVES * 64;
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5, wave = threadIdx.x >> 6;
+    const int npix = N * P * Q;
+    const int n0 = (int)blockIdx.y * COLS;
+    const int seg = k * C;                                   // floats in one filter row
+    const int rpr = (seg + 7) >> 3;                          // runs per filter row
+    const int nruns = k * rpr;
+    const int nsteps = (nruns + 1) >> 1;                     // one MFMA K-step takes two runs (one per half-wave)
+    const int last0 = seg >= 8 ? seg - 8 : 0;                // first float of the last run of a filter row
+    const int rowlen = W * C;
+    const long long total = (long long)N * H * rowlen;       // floats in x
+
+    // ---- expanded weights of this workgroup's channel tile -> LDS
+    extern __shared__ uint4 wlds[];                          // [2 * nsteps][COLS] units of 8 bf16
+    {
+        const int nunits = 2 * nsteps * COLS;
+        const uint4* src = wexp + (long long)blockIdx.y * nunits;
+        for (int base = 0; base < nunits; base += 4 * NTHR) {
+            uint4 tmp[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) tmp[q] = src[min(base + q * NTHR + (int)threadIdx.x, nunits - 1)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int u = base + q * NTHR + (int)threadIdx.x;
+                if (u < nunits) wlds[u] = tmp[q];
+            }
+        }
+    }
+    __syncthreads();
+
+    float th[NT];
+    bool cok[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < O;
+        th[j] = (bits != nullptr && cok[j]) ? thr[col] : __builtin_inff();
+    }
+    const int ow = (O + 31) / 32;
+
+    for (int tw = 0; tw < tiles_per_wave; ++tw) {
+        const long long m0l = (((long long)blockIdx.x * WAVES + wave) * tiles_per_wave + tw) * (MT * 32);
+        if (m0l >= npix) break;                              // uniform per wave, after the only barrier
+        const int m0 = (int)m0l;
+
+        long long xbase[MT];        // float index of input row 0 of this lane's image
+        int xoff[MT], ytop[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const int pix = min(m0 + 32 * i + l32, npix - 1);
+            const int n = fast_div(pix, div_pq);
+            const int rem = pix - n * (P * Q);
+            const int p = fast_div(rem, div_q), q = rem - p * Q;
+            ytop[i] = p * stride - pad;
+            xoff[i] = (q * stride - pad) * C;
+            xbase[i] = (long long)n * H * rowlen;
+        }
+
+        v16f_bwn acc[MT][NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // Loads this lane's run (filter row r, floats [e0, e0+8) of the row's segment) for every A fragment;
+        // positions outside the image become 0.
+        auto fetch = [&](int r, int e0, float (&run)[MT][8]) {
+            const int cnt = min(8, seg - e0);                // floats of the run inside the segment
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                const int yy = ytop[i] + r;
+                const bool yok = (unsigned)yy < (unsigned)H;
+                const long long start = xbase[i] + (long long)(yok ? yy : 0) * rowlen + xoff[i] + e0;
+                if (start >= 0 && start + 8 <= total) {      // the whole run lies inside the tensor
+                    const float4_ub v0 = *reinterpret_cast<const float4_ub*>(x + start);
+                    const float4_ub v1 = *reinterpret_cast<const float4_ub*>(x + start + 4);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) { run[i][t] = v0[t]; run[i][4 + t] = v1[t]; }
+                } else {                                     // first / last pixels of the tensor
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const long long idx = start + t;
+                        run[i][t] = (idx >= 0 && idx < total) ? x[idx] : 0.f;
+                    }
+                }
+                // zero padding; skipped when every lane of the wave has its whole run inside the image
+                const int xs = xoff[i] + e0;
+                const bool inside = yok && xs >= 0 && xs + 8 <= rowlen && cnt == 8;
+                if (__builtin_amdgcn_ballot_w64(inside) != ~0ull) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const bool ok = yok && t < cnt && (unsigned)(xs + t) < (unsigned)rowlen;
+                        run[i][t] = ok ? run[i][t] : 0.f;
+                    }
+                }
+            }
+        };
+
+        auto multiply = [&](int step, const float (&run)[MT][8]) {
+            uint4 b[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = wlds[(2 * step + half) * COLS + 32 * j + l32];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                const Split3 s = split3(run[i]);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const v8bf_bwn bv = __builtin_bit_cast(v8bf_bwn, b[j]);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.l), bv, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.m), bv, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.h), bv, acc[i][j], 0, 0, 0);
+                }
+            }
+        };
+
+        // this lane's run index advances by 2 per step; (rr, jj) = (filter row, run within the row).  A run
+        // index past the last one (odd run count, upper half-wave) repeats the last run against zero weights.
+        int rr = half / rpr, jj = half - rr * rpr;
+        auto advance = [&]() {
+            jj += 2;
+            while (jj >= rpr) { jj -= rpr; ++rr; }
+        };
+        auto run_e0 = [&]() { return min(8 * jj, last0); };
+        auto clamp_last = [&]() {
+            if (rr >= k) { rr = k - 1; jj = rpr - 1; }
+        };
+
+        // three run buffers: the loads of step s + 2 are issued before the MFMAs of step s
+        float run0[MT][8], run1[MT][8], run2[MT][8];
+        auto next = [&](float (&run)[MT][8]) {
+            advance(); clamp_last(); fetch(rr, run_e0(), run);
+        };
+        clamp_last();
+        fetch(rr, run_e0(), run0);
+        if (nsteps > 1) next(run1);
+        for (int step = 0; step < nsteps; step += 3) {
+            if (step + 2 < nsteps) next(run2);
+            multiply(step, run0);
+            if (step + 1 < nsteps) {
+                if (step + 3 < nsteps) next(run0);
+                multiply(step + 1, run1);
+            }
+            if (step + 2 < nsteps) {
+                if (step + 4 < nsteps) next(run1);
+                multiply(step + 2, run2);
+            }
+        }
+
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const int rbase = m0 + 32 * i;
+            if (rbase >= npix) break;
+            uint32_t wout[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lo_row = 8 * (r >> 2) + (r & 3);
+                const int row = rbase + lo_row + 4 * half;
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const float v = acc[i][j][r];
+                    if (y != nullptr && row < npix && cok[j]) y[(long long)row * O + n0 + 32 * j + l32] = v;
+                    if (bits != nullptr) {
+                        const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= th[j]);
+                        wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)ball, lo_row, (int)wout[j]);
+                        wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)(ball >> 32), lo_row + 4, (int)wout[j]);
+                    }
+                }
+            }
+            const int row = rbase + lane;
+            if (bits != nullptr && lane < 32 && row < npix) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < ow) bits[(long long)row * ow + wi] = wout[j];
+                }
+            }
+        }
+    }
+}
+
+template <int MT, int NT, int WAVES>
+int launch_bwn_direct(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
+                      int C, int O, int k, int stride, int pad, int P, int Q, void* workspace, size_t workspace_bytes,
+                      hipStream_t s) {
+    constexpr int COLS = NT * 32;
+    const long long npix = (long long)N * P * Q;
+    const int seg = k * C, nruns = k * ((seg + 7) / 8), nsteps = (nruns + 1) / 2;
+    const int col_tiles = (int)cdiv(O, COLS);
+    const size_t lds_bytes = (size_t)2 * nsteps * COLS * 16;
+    if (lds_bytes > 160 * 1024) return BNN_ERR_UNSUPPORTED;
+    if (workspace_bytes < lds_bytes * col_tiles) return BNN_ERR_WORKSPACE;
+    if (lds_bytes > 64 * 1024) {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_conv_kernel<MT, NT, WAVES>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    }
+    uint4* wexp = static_cast<uint4*>(workspace);
+    const int nunits = col_tiles * 2 * nsteps * COLS;
+    hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, C, O, k, COLS, 1, nunits);
+    // Several pixel groups per wave amortise the weight copy, as long as the grid still fills the chip.
+    const long long groups = cdiv(npix, MT * 32);
+    int tpw = 1;
+    while (tpw < 8 && cdiv(groups, (long long)WAVES * (tpw * 2)) * col_tiles >= 4 * 256) tpw *= 2;
+    dim3 grid((unsigned)cdiv(groups, (long long)WAVES * tpw), (unsigned)col_tiles);
+    hipLaunchKernelGGL((bwn_conv_kernel<MT, NT, WAVES>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, N, H, W, C, O, k, stride,
+                       pad, P, Q, make_fastdiv(P * Q), make_fastdiv(Q), tpw);
+    return check_launch();
+}
+
+// Channels per pixel in the LDS patch: the smallest Cp >= C for which a pixel step (stride * Cp bf16) is a
+// multiple of 8 bytes, so that every operand read is 8-byte aligned.
+int staged_cp(int C, int stride) {
+    const int m = stride % 4 == 0 ? 1 : (stride % 2 == 0 ? 2 : 4);
+    return (C + m - 1) / m * m;
+}
+
+constexpr size_t LDS_MAX = 160 * 1024;
+
+// Fills the geometry for an MT x NT x WAVES configuration; false if weights + patch do not fit LDS.
+bool staged_geom(int MT, int NT, int WAVES, int N, int H, int W, int C, int O, int k, int stride, int pad, int P, int Q,
+                 BwnTile* g, size_t* lds_bytes) {
+    g->H = H; g->W = W; g->C = C; g->Cp = staged_cp(C, stride); g->O = O; g->stride = stride; g->pad = pad; g->P = P; g->Q = Q; g->k = k;
+    g->FQ = Q >= 24 ? 32 : (Q >= 12 ? 16 : 8);
+    g->FP = 32 / g->FQ;
+    g->TP = WAVES * MT * g->FP;
+    g->tiles_p = (int)cdiv(P, g->TP); g->tiles_q = (int)cdiv(Q, g->FQ);
+    g->PR = (g->TP - 1) * stride + k;
+    const long long pcc = ((long long)(g->FQ - 1) * stride + k) * g->Cp;
+    const long long pitch = (2 * pcc + 16 + 7) / 8 * 8;
+    const long long seg = (long long)k * g->Cp;
+    g->rpr = (int)((seg + 7) / 8);
+    const long long nruns = (long long)k * g->rpr;
+    g->nsteps = (int)((nruns + 1) / 2);
+    const long long wbytes = 2LL * g->nsteps * NT * 32 * 16;
+    const long long total = wbytes + 3LL * g->PR * pitch;
+    if (total > (long long)LDS_MAX || (long long)N * g->tiles_p * g->tiles_q >= (1LL << 31)) return false;
+    g->PC = (g->FQ - 1) * stride + k; g->PCC = (int)pcc; g->pitch = (int)pitch; g->wbytes = (int)wbytes;
+    g->div_pc = make_fastdiv((uint32_t)g->PC);
+    g->div_tiles = make_fastdiv((uint32_t)(g->tiles_p * g->tiles_q)); g->div_tq = make_fastdiv((uint32_t)g->tiles_q);
+    g->div_row = make_fastdiv((uint32_t)(pitch / 2)); g->div_cp = make_fastdiv((uint32_t)g->Cp); g->div_fq = make_fastdiv((uint32_t)g->FQ);
+    *lds_bytes = (size_t)total;
+    return true;
+}
+
+template <int MT, int NT, int WAVES>
+int launch_bwn_staged(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int C, int O,
+                      int k, const BwnTile& g, size_t lds_bytes, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    constexpr int COLS = NT * 32;
+    const int col_tiles = (int)cdiv(O, COLS);
+    if (workspace_bytes < (size_t)g.wbytes * col_tiles) return BNN_ERR_WORKSPACE;
+    if (lds_bytes > 64 * 1024) {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_staged_kernel<MT, NT, WAVES>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
+        if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    }
+    uint4* wexp = static_cast<uint4*>(workspace);
+    const int nunits = col_tiles * 2 * g.nsteps * COLS;
+    hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, g.Cp, O, k, COLS, 0,
+                       nunits);
+    dim3 grid((unsigned)(N * g.tiles_p * g.tiles_q), (unsigned)col_tiles);
+    hipLaunchKernelGGL((bwn_staged_kernel<MT, NT, WAVES>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, g);
+    return check_launch();
+}
+
+}  // namespace
+
+// Upper bound over every kernel configuration: 128-channel tiles, channels padded by at most 3.
+size_t bwn_workspace_bytes(int C, int O, int k) {
+    const long long seg = (long long)k * (C + 3), nruns = k * ((seg + 7) / 8), nsteps = (nruns + 1) / 2;
+    return (size_t)(cdiv(O, 128) * 128 * 2 * nsteps * 16);
+}
+
+int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
+                        int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    BwnTile g;
+    size_t lds = 0;
+    // LDS-staged kernel with small workgroups while several of them fit a CU side by side (one loads its
+    // patch while another multiplies); otherwise the direct kernel, eight waves sharing one copy of the weights.
+    constexpr size_t SIDE_BY_SIDE = 64 * 1024;
+    if (O > 64 && staged_geom(1, 4, 4, N, H, W, C, O, k, stride, pad, P, Q, &g, &lds) && lds <= SIDE_BY_SIDE)
+        return launch_bwn_staged<1, 4, 4>(x, wbits, thr, y, bits, N, C, O, k, g, lds, workspace, workspace_bytes, s);
+    if (staged_geom(2, 2, 4, N, H, W, C, O, k, stride, pad, P, Q, &g, &lds) && lds <= SIDE_BY_SIDE)
+        return launch_bwn_staged<2, 2, 4>(x, wbits, thr, y, bits, N, C, O, k, g, lds, workspace, workspace_bytes, s);
+    if (staged_geom(1, 2, 4, N, H, W, C, O, k, stride, pad, P, Q, &g, &lds) && lds <= SIDE_BY_SIDE)
+        return launch_bwn_staged<1, 2, 4>(x, wbits, thr, y, bits, N, C, O, k, g, lds, workspace, workspace_bytes, s);
+    if (O <= 64) return launch_bwn_direct<2, 2, 8>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
+    return launch_bwn_direct<1, 4, 8>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
+}
+
+}  // namespace bnn

@@ -157,16 +157,21 @@ def check_cnn(bnn, orc, spec, x, path, tier):
     xd = to_dev(x)
     scores = host(net.forward(xd, path=path))
     L0 = layers[0]
-    _, y = bnn.conv_f32_thr(xd, to_dev(L0["w"]), to_dev(L0["thr"]), L0["stride"], L0["pad"], want_f32=True)
-    ref0 = orc.conv_f32(x, L0["w"], L0["stride"], L0["pad"])
+    if L0["op"] == "bwn":
+        _, y = bnn.bwn_conv_thr(xd, to_dev(L0["W"]), to_dev(L0["thr"]), L0["C"], L0["stride"], L0["pad"], want_f32=True)
+        ref0 = orc.bwn_conv_f32(x, L0["W"], L0["C"], L0["stride"], L0["pad"])
+        cout = L0["W"].shape[0]
+    else:
+        _, y = bnn.conv_f32_thr(xd, to_dev(L0["w"]), to_dev(L0["thr"]), L0["stride"], L0["pad"], want_f32=True)
+        ref0 = orc.conv_f32(x, L0["w"], L0["stride"], L0["pad"])
+        cout = L0["w"].shape[0]
     tol = 1e-4 * np.maximum(np.abs(ref0), np.sqrt((ref0.astype(np.float64) ** 2).mean()))
     assert (np.abs(host(y) - ref0) <= tol).all()
     ref_bits = orc.pack_f32(ref0, L0["thr"])
     bits0 = words(net.layer_bits(0)).reshape(ref_bits.shape)
     diff = bits0 ^ ref_bits
     if diff.any():
-        C = L0["w"].shape[0]
-        d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), C).reshape(ref0.shape) > 0
+        d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), cout).reshape(ref0.shape) > 0
         assert (np.abs(ref0 - L0["thr"])[d] <= tol[d]).all()
         print("first-layer bits inside the fp32 tolerance that differ:", int(d.sum()), flush=True)
     outs = nets.cnn_forward(x, layers, stem_bits=bits0, tier=tier, keep=True)
@@ -176,10 +181,50 @@ def check_cnn(bnn, orc, spec, x, path, tier):
     assert scores.dtype == np.int32 and np.array_equal(scores, outs[-1])
 
 
-@pytest.mark.parametrize("name,batch,path,tier", [("cifar_vgg", 5, 1, 0), ("cifar_vgg", 5, 2, 0), ("cifar_vgg", 64, 0, 1),
-                                                  ("cifar_resnet14", 5, 1, 0), ("cifar_resnet14", 5, 2, 0),
-                                                  ("cifar_resnet14", 64, 0, 1),
-                                                  ("alexnet", 3, 2, 1), ("alexnet", 16, 0, 1),
-                                                  ("vgg16", 2, 0, 1)])
-def test_table5_networks(bnn, orc, name, batch, path, tier):
-    check_cnn(bnn, orc, wl.cnn_layers(name), wl.cnn_input(name, batch), path, tier)
+@pytest.mark.parametrize("name,batch,path,tier,first", [
+    ("cifar_vgg", 5, 1, 0, "bwn"), ("cifar_vgg", 5, 2, 0, "f32"), ("cifar_vgg", 64, 0, 1, "bwn"),
+    ("cifar_resnet14", 5, 1, 0, "f32"), ("cifar_resnet14", 5, 2, 0, "bwn"), ("cifar_resnet14", 64, 0, 1, "bwn"),
+    ("alexnet", 3, 2, 1, "f32"), ("alexnet", 16, 0, 1, "bwn"), ("vgg16", 2, 0, 1, "bwn"), ("vgg16", 1, 0, 1, "f32")])
+def test_table5_networks(bnn, orc, name, batch, path, tier, first):
+    check_cnn(bnn, orc, wl.cnn_layers(name, first=first), wl.cnn_input(name, batch), path, tier)
+
+
+@pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
+                                   (2, 32, 32, 3, 64, 7, 4, 3), (1, 8, 8, 2, 33, 1, 1, 0), (2, 32, 32, 3, 128, 3, 1, 1),
+                                   (1, 40, 37, 3, 128, 11, 4, 2), (2, 12, 12, 35, 96, 3, 2, 1), (1, 6, 6, 1, 200, 2, 1, 0),
+                                   (9, 31, 33, 3, 64, 3, 1, 1)])
+def test_bwn_first_layer_shapes(bnn, orc, shape):
+    N, H, W, C, O, k, st, pad = shape
+    rng = np.random.default_rng(sum(shape) + 1)
+    x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
+    wb = wl.random_bits(rng, (O, k, k), C)
+    thr = rng.normal(0, 1.0, size=O).astype(np.float32)
+    bits, y = bnn.bwn_conv_thr(to_dev(x), to_dev(wb), to_dev(thr), C, st, pad, want_f32=True)
+    ref = orc.bwn_conv_f32(x, wb, C, st, pad)
+    tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
+    assert host(y).shape == ref.shape
+    assert (np.abs(host(y) - ref) <= tol).all()
+    # far tighter in fact: every product is exact, only the fp32 additions round
+    assert np.abs(host(y) - ref).max() <= 2e-6 * max(1.0, np.abs(ref).max()) * np.sqrt(k * k * C)
+    assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
+    # bits only (no fp32 output) gives the same words
+    assert np.array_equal(words(bnn.bwn_conv_thr(to_dev(x), to_dev(wb), to_dev(thr), C, st, pad)), words(bits))
+
+
+def test_bwn_exact_cases(bnn, orc):
+    # (a) integer inputs: the three-way bf16 split is exact and sums below 2^24 never round, so the fp32
+    # result equals the oracle's bit for bit; (b) isolated values with all 24 significand bits set (at most
+    # one non-zero term per output): checks that the split drops no bit
+    rng = np.random.default_rng(5)
+    wb = wl.random_bits(rng, (40, 5, 5), 3)
+    zero = to_dev(np.zeros(40, np.float32))
+    x = rng.integers(-30000, 30001, size=(2, 14, 13, 3)).astype(np.float32)
+    _, y = bnn.bwn_conv_thr(to_dev(x), to_dev(wb), zero, 3, 2, 2, want_f32=True)
+    assert np.array_equal(host(y), orc.bwn_conv_f32(x, wb, 3, 2, 2))
+    x = np.zeros((1, 30, 30, 3), np.float32)
+    for (h, w, c, v) in ((2, 3, 0, 16777215.0 / 4096), (12, 20, 1, -11184811.0 / 65536), (25, 6, 2, 13421773.0 * 8),
+                         (20, 27, 0, 8388609.0 / 2 ** 30)):
+        x[0, h, w, c] = v
+    _, y = bnn.bwn_conv_thr(to_dev(x), to_dev(wb), zero, 3, 1, 2, want_f32=True)
+    ref = orc.bwn_conv_f32(x, wb, 3, 1, 2)
+    assert np.abs(ref).max() > 1e7 and np.array_equal(host(y), ref)

@@ -162,10 +162,16 @@ def _conv_f32_layer(rng_w, cin, cout, k, stride, pad, scale=0.05):
             "thr": np.zeros(cout, dtype=np.float32), "stride": stride, "pad": pad}
 
 
-def cnn_layers(name: str, config: int = 7) -> dict:
+def _bwn_layer(rng_w, cin, cout, k, stride, pad):
+    return {"op": "bwn", "W": random_bits(rng_w, (cout, k, k), cin), "thr": np.zeros(cout, dtype=np.float32),
+            "C": cin, "stride": stride, "pad": pad}
+
+
+def cnn_layers(name: str, config: int = 7, first: str = "bwn") -> dict:
     """Layer lists with the shapes of the paper's Table 5 (Cifar-10 VGG and ResNet-14, ImageNet AlexNet
     and VGG-16); random +1/-1 weights, conv thresholds uniform integers in [-64, 64], FC thresholds in
-    [-32, 32], fp32 first layer ~ N(0, 0.05) with threshold 0.  "k x nFC" is read as k - 1 hidden layers of n
+    [-32, 32].  First layer (threshold 0): ``first="bwn"`` -- real-valued input, binarized weights, as the paper
+    runs it (Sec. 6.1); ``first="f32"`` -- real-valued weights ~ N(0, 0.05).  "k x nFC" is read as k - 1 hidden layers of n
     neurons followed by the output layer, as the benchmark configuration reads the MLP.
     Returns {"layers", "in_hw", "classes"}."""
     idx = [0]
@@ -193,21 +199,26 @@ def cnn_layers(name: str, config: int = 7) -> dict:
             b["Wd"] = random_bits(rng(), (cout, 1, 1), cin)
         return b
 
+    def first_layer(cin, cout, k, stride, pad, scale=0.05):
+        if first == "bwn":
+            return _bwn_layer(rng(), cin, cout, k, stride, pad)
+        return _conv_f32_layer(rng(), cin, cout, k, stride, pad, scale)
+
     if name == "cifar_vgg":          # (2x128C3)-MP2-(2x256C3)-MP2-(2x512C3)-MP2-(3x1024FC), 32x32x3 -> 10
-        L = [_conv_f32_layer(rng(), 3, 128, 3, 1, 1), bconv(128, 128), pool(), bconv(128, 256), bconv(256, 256), pool(),
+        L = [first_layer(3, 128, 3, 1, 1), bconv(128, 128), pool(), bconv(128, 256), bconv(256, 256), pool(),
              bconv(256, 512), bconv(512, 512), pool(), fc(4 * 4 * 512, 1024), fc(1024, 1024), fc(1024, 10, last=True)]
         return {"layers": L, "in_hw": 32, "classes": 10}
     if name == "cifar_resnet14":     # 128C3/2-4x128C3-4x256C3-4x512C3-(2x512FC), 32x32x3 -> 10
-        L = [_conv_f32_layer(rng(), 3, 128, 3, 2, 1), block(128, 128, 1), block(128, 128, 1), block(128, 256, 2),
+        L = [first_layer(3, 128, 3, 2, 1), block(128, 128, 1), block(128, 128, 1), block(128, 256, 2),
              block(256, 256, 1), block(256, 512, 2), block(512, 512, 1), fc(4 * 4 * 512, 512), fc(512, 10, last=True)]
         return {"layers": L, "in_hw": 32, "classes": 10}
     if name == "alexnet":            # (128C11/4)-P2-(256C5)-P2-(3x256C3)-P2-(3x4096FC), 224x224x3 -> 1000
-        L = [_conv_f32_layer(rng(), 3, 128, 11, 4, 2, scale=0.02), pool(), bconv(128, 256, 5, 1, 2), pool(),
+        L = [first_layer(3, 128, 11, 4, 2, scale=0.02), pool(), bconv(128, 256, 5, 1, 2), pool(),
              bconv(256, 256), bconv(256, 256), bconv(256, 256), pool(),
              fc(6 * 6 * 256, 4096), fc(4096, 4096), fc(4096, 1000, last=True)]
         return {"layers": L, "in_hw": 224, "classes": 1000}
     if name == "vgg16":              # (2x64C3)-P2-(2x128C3)-P2-(3x256C3)-P2-2x(3x512C3-P2)-(3x4096FC), 224x224x3 -> 1000
-        L = [_conv_f32_layer(rng(), 3, 64, 3, 1, 1), bconv(64, 64), pool(), bconv(64, 128), bconv(128, 128), pool(),
+        L = [first_layer(3, 64, 3, 1, 1), bconv(64, 64), pool(), bconv(64, 128), bconv(128, 128), pool(),
              bconv(128, 256), bconv(256, 256), bconv(256, 256), pool(),
              bconv(256, 512), bconv(512, 512), bconv(512, 512), pool(),
              bconv(512, 512), bconv(512, 512), bconv(512, 512), pool(),
