@@ -70,10 +70,10 @@ __device__ __forceinline__ Split3 split3(const float (&x)[8]) {
 // slot t*Cp + c, channels >= C are padding); run j of a row starts at slot 8*j, or, with `moveback`, the last
 // run is moved back to end at seg and the slots it shares with the run before get weight 0.
 __global__ __launch_bounds__(256) void bwn_expand_kernel(const uint32_t* __restrict__ wbits, uint4* __restrict__ wexp, int C, int Cp,
-                                                         int O, int k, int cols, int moveback, int nunits) {
+                                                         int O, int k, int cols, int moveback, int nsteps, int nunits) {
     const int u = (int)(blockIdx.x * 256 + threadIdx.x);
     if (u >= nunits) return;
-    const int seg = k * Cp, rpr = (seg + 7) >> 3, nruns = k * rpr, nsteps = (nruns + 1) >> 1;
+    const int seg = k * Cp, rpr = (seg + 7) >> 3, nruns = k * rpr;      // nsteps >= ceil(nruns / 2); the rest is zero
     const int last0 = seg >= 8 ? seg - 8 : 0, cw = (C + 31) >> 5;
     const int per_tile = 2 * nsteps * cols;
     const int tile = u / per_tile, v = u - tile * per_tile;
@@ -114,8 +114,12 @@ struct BwnTile {            // geometry of the LDS-staged kernel, computed on th
     FastDiv div_tiles, div_tq, div_row, div_cp, div_fq, div_pc;
 };
 
-template <int MT, int NT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
+// CIN: input channels known at compile time (3: colour images), 0: any.  WANT_Y: also store the fp32 sums.
+// At least two waves per SIMD are requested so that the register budget is 256: the accumulators then stay in
+// ordinary VGPRs and the epilogue compares them in place (with 512 registers allowed the compiler parks them in
+// AGPRs and copies every one back before the compare).
+template <int MT, int NT, int WAVES, int CIN, bool WANT_Y>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwn_staged_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
                                                                 const float* __restrict__ thr, float* __restrict__ y,
                                                                 uint32_t* __restrict__ bits, BwnTile g) {
     constexpr int COLS = NT * 32, NTHR = WAVES * 64;
@@ -160,11 +164,11 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __r
             *reinterpret_cast<unsigned short*>(patch + plane + off) = (unsigned short)(b >> 16);
             *reinterpret_cast<unsigned short*>(patch + 2 * plane + off) = (unsigned short)(__float_as_uint(r2) >> 16);
         };
-        if (g.C <= 4) {
+        if (CIN == 3) {
             // one patch pixel per thread and pass, four passes in flight
             const int npx = g.PR * g.PC;
             for (int base = 0; base < npx; base += 4 * NTHR) {
-                float v[4][4];
+                float v[4][3];
                 int off[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -172,20 +176,18 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __r
                     const int r = fast_div(e, g.div_pc), px = e - r * g.PC;
                     const int yy = y0 + r, xx = x0 + px;
                     const bool ok = e < npx && (unsigned)yy < (unsigned)g.H && (unsigned)xx < (unsigned)g.W;
-                    const float* src = ximg + ((long long)yy * g.W + xx) * g.C;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        v[u][c] = 0.f;
-                        if (ok && c < g.C) v[u][c] = src[c];
+                    v[u][0] = v[u][1] = v[u][2] = 0.f;
+                    if (ok) {
+                        const float* src = ximg + ((long long)yy * g.W + xx) * 3;
+                        v[u][0] = src[0]; v[u][1] = src[1]; v[u][2] = src[2];
                     }
                     off[u] = e < npx ? r * g.pitch + px * g.Cp * 2 : -1;
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (off[u] < 0) continue;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (c < g.Cp) put(off[u] + 2 * c, v[u][c]);
+                    put(off[u], v[u][0]); put(off[u] + 2, v[u][1]); put(off[u] + 4, v[u][2]);
+                    if (g.Cp == 4) put(off[u] + 6, 0.f);
                 }
             }
             // slack behind the last pixel of every row
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __r
     for (int j = 0; j < NT; ++j) {
         const int col = n0 + 32 * j + l32;
         cok[j] = col < g.O;
-        th[j] = (bits != nullptr && cok[j]) ? thr[col] : __builtin_inff();
+        th[j] = ((!WANT_Y || bits != nullptr) && cok[j]) ? thr[col] : __builtin_inff();
     }
     const int ow = (g.O + 31) / 32;
     const long long img_pix = (long long)n * g.P * g.Q;
@@ -304,13 +306,13 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __r
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 const float v = acc[i][j][r];
-                if (y != nullptr) {
+                if (WANT_Y) {
                     const int m = lo_row + 4 * half;                  // fragment row of this register in this lane
                     const int mp = fast_div(m, g.div_fq), mq = m - mp * g.FQ;
                     if (frow0 + mp < g.P && q0 + mq < g.Q && cok[j])
                         y[(img_pix + (long long)(frow0 + mp) * g.Q + q0 + mq) * g.O + n0 + 32 * j + l32] = v;
                 }
-                if (bits != nullptr) {
+                if (!WANT_Y || bits != nullptr) {       // without the fp32 output the bits are always wanted
                     const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= th[j]);
                     wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)ball, lo_row, (int)wout[j]);
                     wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)(ball >> 32), lo_row + 4, (int)wout[j]);
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_staged_kernel(const float* __r
             }
         }
         // lane m < 32 holds the packed words of fragment row m = output pixel (frow0 + dp, q0 + dq)
-        if (bits != nullptr && lane < 32 && frow0 + dp < g.P && q0 + dq < g.Q) {
+        if ((!WANT_Y || bits != nullptr) && lane < 32 && frow0 + dp < g.P && q0 + dq < g.Q) {
             const long long pix = img_pix + (long long)(frow0 + dp) * g.Q + q0 + dq;
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
@@ -345,7 +347,9 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     const int seg = k * C;                                   // floats in one filter row
     const int rpr = (seg + 7) >> 3;                          // runs per filter row
     const int nruns = k * rpr;
-    const int nsteps = (nruns + 1) >> 1;                     // one MFMA K-step takes two runs (one per half-wave)
+    // one MFMA K-step takes two runs (one per half-wave); the step count is rounded up to a multiple of 3 (the
+    // depth of the prefetch rotation), the added steps multiply by zero weights
+    const int nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
     const int last0 = seg >= 8 ? seg - 8 : 0;                // first float of the last run of a filter row
     const int rowlen = W * C;
     const long long total = (long long)N * H * rowlen;       // floats in x
@@ -404,47 +408,57 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        // Loads this lane's run (filter row r, floats [e0, e0+8) of the row's segment) for every A fragment;
-        // positions outside the image become 0.
-        auto fetch = [&](int r, int e0, float (&run)[MT][8]) {
+        struct Run {                // one prefetched K-step: the values, their in-image range, where they start
+            float v[MT][8];
+            int rng[MT];
+            long long start[MT];
+        };
+
+        // Loads this lane's run (filter row r, floats [e0, e0+8) of the row's segment) for every A fragment and
+        // records which of the 8 positions lie inside the image as the range [lo, hi) (packed lo | hi << 8).
+        // The zero padding itself is applied when the run is consumed, so that nothing waits on the loads here,
+        // and there is no branch: a run that would leave the tensor (only at its very first and last pixels) is
+        // loaded from offset 0 instead, flagged (bit 16), and re-read element by element when it is consumed.
+        auto fetch = [&](int r, int e0, Run& q) {
             const int cnt = min(8, seg - e0);                // floats of the run inside the segment
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
                 const int yy = ytop[i] + r;
                 const bool yok = (unsigned)yy < (unsigned)H;
                 const long long start = xbase[i] + (long long)(yok ? yy : 0) * rowlen + xoff[i] + e0;
-                if (start >= 0 && start + 8 <= total) {      // the whole run lies inside the tensor
-                    const float4_ub v0 = *reinterpret_cast<const float4_ub*>(x + start);
-                    const float4_ub v1 = *reinterpret_cast<const float4_ub*>(x + start + 4);
+                const bool inb = start >= 0 && start + 8 <= total;
+                const float* src = x + (inb ? start : 0);
+                const float4_ub v0 = *reinterpret_cast<const float4_ub*>(src);
+                const float4_ub v1 = *reinterpret_cast<const float4_ub*>(src + 4);
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) { run[i][t] = v0[t]; run[i][4 + t] = v1[t]; }
-                } else {                                     // first / last pixels of the tensor
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const long long idx = start + t;
-                        run[i][t] = (idx >= 0 && idx < total) ? x[idx] : 0.f;
-                    }
-                }
-                // zero padding; skipped when every lane of the wave has its whole run inside the image
+                for (int t = 0; t < 4; ++t) { q.v[i][t] = v0[t]; q.v[i][4 + t] = v1[t]; }
                 const int xs = xoff[i] + e0;
-                const bool inside = yok && xs >= 0 && xs + 8 <= rowlen && cnt == 8;
-                if (__builtin_amdgcn_ballot_w64(inside) != ~0ull) {
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const bool ok = yok && t < cnt && (unsigned)(xs + t) < (unsigned)rowlen;
-                        run[i][t] = ok ? run[i][t] : 0.f;
-                    }
-                }
+                const int lo = max(0, -xs), hi = yok ? max(min(cnt, rowlen - xs), 0) : 0;
+                q.rng[i] = lo | (hi << 8) | (inb ? 0 : 1 << 16);
+                q.start[i] = start;
             }
         };
 
-        auto multiply = [&](int step, const float (&run)[MT][8]) {
+        auto multiply = [&](int step, Run& q) {
             uint4 b[NT];
 #pragma unroll
             for (int j = 0; j < NT; ++j) b[j] = wlds[(2 * step + half) * COLS + 32 * j + l32];
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
-                const Split3 s = split3(run[i]);
+                // zero padding; skipped when every lane of the wave has its whole run inside the image
+                if (__builtin_amdgcn_ballot_w64(q.rng[i] == (8 << 8)) != ~0ull) {
+                    if (__builtin_amdgcn_ballot_w64((q.rng[i] >> 16) != 0) != 0ull) {
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const long long idx = q.start[i] + t;
+                            if ((q.rng[i] >> 16) != 0) q.v[i][t] = (idx >= 0 && idx < total) ? x[idx < 0 ? 0 : (idx < total ? idx : 0)] : 0.f;
+                        }
+                    }
+                    const int lo = q.rng[i] & 255, hi = (q.rng[i] >> 8) & 255;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) q.v[i][t] = (t >= lo && t < hi) ? q.v[i][t] : 0.f;
+                }
+                const Split3 s = split3(q.v[i]);
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     const v8bf_bwn bv = __builtin_bit_cast(v8bf_bwn, b[j]);
@@ -467,25 +481,23 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
             if (rr >= k) { rr = k - 1; jj = rpr - 1; }
         };
 
-        // three run buffers: the loads of step s + 2 are issued before the MFMAs of step s
-        float run0[MT][8], run1[MT][8], run2[MT][8];
-        auto next = [&](float (&run)[MT][8]) {
-            advance(); clamp_last(); fetch(rr, run_e0(), run);
+        // three run buffers: the loads of step s + 2 are issued before the MFMAs of step s.  Fetches are
+        // unconditional (past the end they repeat the last run) so that the number of loads in flight at every
+        // wait is the same on every path.
+        Run run0, run1, run2;
+        auto next = [&](Run& q) {
+            advance(); clamp_last(); fetch(rr, run_e0(), q);
         };
         clamp_last();
         fetch(rr, run_e0(), run0);
-        if (nsteps > 1) next(run1);
+        next(run1);
         for (int step = 0; step < nsteps; step += 3) {
-            if (step + 2 < nsteps) next(run2);
+            next(run2);
             multiply(step, run0);
-            if (step + 1 < nsteps) {
-                if (step + 3 < nsteps) next(run0);
-                multiply(step + 1, run1);
-            }
-            if (step + 2 < nsteps) {
-                if (step + 4 < nsteps) next(run1);
-                multiply(step + 2, run2);
-            }
+            next(run0);
+            multiply(step + 1, run1);
+            next(run1);
+            multiply(step + 2, run2);
         }
 
 #pragma unroll
@@ -528,7 +540,7 @@ int launch_bwn_direct(const float* x, const uint32_t* wbits, const float* thr, f
                       hipStream_t s) {
     constexpr int COLS = NT * 32;
     const long long npix = (long long)N * P * Q;
-    const int seg = k * C, nruns = k * ((seg + 7) / 8), nsteps = (nruns + 1) / 2;
+    const int seg = k * C, nruns = k * ((seg + 7) / 8), nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
     const int col_tiles = (int)cdiv(O, COLS);
     const size_t lds_bytes = (size_t)2 * nsteps * COLS * 16;
     if (lds_bytes > 160 * 1024) return BNN_ERR_UNSUPPORTED;
@@ -540,7 +552,7 @@ int launch_bwn_direct(const float* x, const uint32_t* wbits, const float* thr, f
     }
     uint4* wexp = static_cast<uint4*>(workspace);
     const int nunits = col_tiles * 2 * nsteps * COLS;
-    hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, C, O, k, COLS, 1, nunits);
+    hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, C, O, k, COLS, 1, nsteps, nunits);
     // Several pixel groups per wave amortise the weight copy, as long as the grid still fills the chip.
     const long long groups = cdiv(npix, MT * 32);
     int tpw = 1;
@@ -586,31 +598,42 @@ bool staged_geom(int MT, int NT, int WAVES, int N, int H, int W, int C, int O, i
     return true;
 }
 
-template <int MT, int NT, int WAVES>
-int launch_bwn_staged(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int C, int O,
+template <int MT, int NT, int WAVES, int CIN, bool WANT_Y>
+int launch_bwn_staged_v(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int C, int O,
                       int k, const BwnTile& g, size_t lds_bytes, void* workspace, size_t workspace_bytes, hipStream_t s) {
     constexpr int COLS = NT * 32;
     const int col_tiles = (int)cdiv(O, COLS);
     if (workspace_bytes < (size_t)g.wbytes * col_tiles) return BNN_ERR_WORKSPACE;
     if (lds_bytes > 64 * 1024) {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_staged_kernel<MT, NT, WAVES>),
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_staged_kernel<MT, NT, WAVES, CIN, WANT_Y>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
         if (attr != hipSuccess) return BNN_ERR_DEVICE;
     }
     uint4* wexp = static_cast<uint4*>(workspace);
     const int nunits = col_tiles * 2 * g.nsteps * COLS;
     hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, g.Cp, O, k, COLS, 0,
-                       nunits);
+                       g.nsteps, nunits);
     dim3 grid((unsigned)(N * g.tiles_p * g.tiles_q), (unsigned)col_tiles);
-    hipLaunchKernelGGL((bwn_staged_kernel<MT, NT, WAVES>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, g);
+    hipLaunchKernelGGL((bwn_staged_kernel<MT, NT, WAVES, CIN, WANT_Y>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, g);
     return check_launch();
+}
+
+template <int MT, int NT, int WAVES>
+int launch_bwn_staged(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int C, int O,
+                      int k, const BwnTile& g, size_t lds_bytes, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    // the fp32 sums are a test / debugging output: only the generic-channel variant carries them
+    if (y != nullptr)
+        return launch_bwn_staged_v<MT, NT, WAVES, 0, true>(x, wbits, thr, y, bits, N, C, O, k, g, lds_bytes, workspace, workspace_bytes, s);
+    if (C == 3)
+        return launch_bwn_staged_v<MT, NT, WAVES, 3, false>(x, wbits, thr, y, bits, N, C, O, k, g, lds_bytes, workspace, workspace_bytes, s);
+    return launch_bwn_staged_v<MT, NT, WAVES, 0, false>(x, wbits, thr, y, bits, N, C, O, k, g, lds_bytes, workspace, workspace_bytes, s);
 }
 
 }  // namespace
 
 // Upper bound over every kernel configuration: 128-channel tiles, channels padded by at most 3.
 size_t bwn_workspace_bytes(int C, int O, int k) {
-    const long long seg = (long long)k * (C + 3), nruns = k * ((seg + 7) / 8), nsteps = (nruns + 1) / 2;
+    const long long seg = (long long)k * (C + 3), nruns = k * ((seg + 7) / 8), nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
     return (size_t)(cdiv(O, 128) * 128 * 2 * nsteps * 16);
 }
 
