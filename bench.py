@@ -250,6 +250,29 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
                       "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4)})
         del x, f, bits
     out["bconv_sweep_batch16_64x64_3x3"] = sweep
+    # ---- "general" forms (Sec. 7.2 / 7.3): real-valued operands binarized on the way in, fp32 result
+    gen = []
+    for n in (2048, 4096, 8192):
+        A = torch.randn((n, n), dtype=torch.float32, device=dev)
+        B = torch.randn((n, n), dtype=torch.float32, device=dev)
+        C = torch.empty((n, n), dtype=torch.float32, device=dev)
+        ws = torch.empty(2 * n * n // 8 + 1024, dtype=torch.uint8, device=dev)
+        t = _time_gpu(torch, lambda: bnn.bmm_general_f32(A, B, out=C, workspace=ws), 10)
+        tp = _time_gpu(torch, lambda: bnn.sign_pack_f32(A), 10)
+        gen.append({"shape": "bmm_sq%d" % n, "ms": round(t, 5), "tops": round(2.0 * n ** 3 / t / 1e9, 1),
+                    "binarize_one_operand_ms": round(tp, 5),
+                    "hbm_gbs": round((3 * n * n * 4 + 4 * n * n / 8) / t / 1e6, 1)})
+        del A, B, C, ws
+    for ch in (128, 512):
+        x = torch.randn((16, 64, 64, ch), dtype=torch.float32, device=dev)
+        f = torch.randn((ch, 3, 3, ch), dtype=torch.float32, device=dev)
+        o = torch.empty((16, 64, 64, ch), dtype=torch.float32, device=dev)
+        ws = torch.empty((x.numel() + f.numel()) // 8 + 1024, dtype=torch.uint8, device=dev)
+        t = _time_gpu(torch, lambda: bnn.bconv_general_f32(x, f, 1, 1, out=o, workspace=ws), 10)
+        gen.append({"shape": "bconv_batch16_64x64_3x3_c%d" % ch, "ms": round(t, 5),
+                    "tops": round(2.0 * 16 * 64 * 64 * ch * 9 * ch / t / 1e9, 1)})
+        del x, f, o, ws
+    out["general_f32_in_f32_out"] = gen
     # ---- binarized MLP (config 3)
     params = wl.mlp_params()
     net = bnn.Net()

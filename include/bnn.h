@@ -125,6 +125,23 @@ int bnn_pack_u8(const uint8_t* x, int thr, uint32_t* bits, int64_t rows, int col
 int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
 /* out[r][c] = +1 / -1 as int32 from bits [rows][ldb_w]; out [rows][ldo].  Seeds the int32
  * residual chain from a bit tensor. */
+/* Binarization by sign (Eq. 1): bit = (x >= 0).  x [rows][ldx] fp32 -> bits [rows][ldb_w] (pad bits and pad words 0). */
+int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream);
+
+/* The "general" forms of Sec. 7.2 / 7.3: real-valued operands in, real-valued result out.  Both operands are
+ * binarized by sign (Eq. 1) into the caller's workspace, multiplied as +1/-1 values (Eq. 2 / Eq. 3), and the
+ * integer sums are stored as fp32 (exact: every sum is below 2^24).
+ *   BMM:   A [M][lda], B [N][ldb] (the K x N operand stored column by column), C [M][ldc] fp32.
+ *   BConv: in [N][H][W][C], filt [O][k][k][C], out [N][P][Q][O] fp32; padding as in bnn_bconv.
+ *   workspace: device scratch of at least bnn_*_general_workspace_bytes(...) bytes, 256-byte aligned; it holds the
+ *   packed operands and is not needed after the call.  C / out 16-byte aligned. */
+size_t bnn_bmm_general_workspace_bytes(int M, int N, int K);
+int bnn_bmm_general_f32(const float* A, const float* B, float* C, int M, int N, int K, int lda, int ldb, int ldc,
+                        void* workspace, size_t workspace_bytes, void* stream);
+size_t bnn_bconv_general_workspace_bytes(int N, int H, int W, int C, int O, int k);
+int bnn_bconv_general_f32(const float* in, const float* filt, float* out, int N, int H, int W, int C, int O, int k,
+                          int stride, int pad, int pad_mode, void* workspace, size_t workspace_bytes, void* stream);
+
 int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream);
 
 /* Max-pooling of packed +1/-1 activations: behind the threshold the maximum over a window is the

@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,7 +24,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_pack_f32", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
+           "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
            "bnn_net_forward", "bnn_net_layer_bits"]
@@ -57,6 +58,8 @@ def load() -> ctypes.CDLL:
         lib.bnn_bmm_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bconv_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bwn_workspace_bytes.restype = ctypes.c_size_t
+        lib.bnn_bmm_general_workspace_bytes.restype = ctypes.c_size_t
+        lib.bnn_bconv_general_workspace_bytes.restype = ctypes.c_size_t
         for name in EXPORTS:
             getattr(lib, name)          # fail loudly on a missing export
         _lib = lib
@@ -213,6 +216,54 @@ def pack_f32(x, thr, ldb_w: int | None = None):
     with torch.cuda.device(x.device):
         _check(load().bnn_pack_f32(_ptr(x), _ptr(thr), _ptr(bits), ctypes.c_int64(rows), cols, ldb_w, _stream(x)), "bnn_pack_f32")
     return bits
+
+
+def sign_pack_f32(x, ldb_w: int | None = None):
+    """Binarization by sign: x [rows][cols] fp32 -> bits [rows][ldb_w], bit = (x >= 0)."""
+    _dev(x, torch.float32, 2, "x")
+    rows, cols = x.shape
+    ldb_w = nwords(cols) if ldb_w is None else ldb_w
+    bits = torch.empty((rows, ldb_w), dtype=_BITS, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_sign_pack_f32(_ptr(x), _ptr(bits), ctypes.c_int64(rows), cols, cols, ldb_w, _stream(x)), "bnn_sign_pack_f32")
+    return bits
+
+
+def bmm_general_f32(A, B, out=None, workspace=None):
+    """General BMM: fp32 A [M][K], B [N][K] -> fp32 [M][N] of the sign-binarized product."""
+    _dev(A, torch.float32, 2, "A"); _dev(B, torch.float32, 2, "B")
+    M, K = A.shape
+    N = B.shape[0]
+    if B.shape[1] != K:
+        raise ValueError("K mismatch")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if workspace is None:
+        workspace = torch.empty(max(int(load().bnn_bmm_general_workspace_bytes(M, N, K)), 256), dtype=torch.uint8, device=A.device)
+    with torch.cuda.device(A.device):
+        _check(load().bnn_bmm_general_f32(_ptr(A), _ptr(B), _ptr(out), M, N, K, K, K, N, _ptr(workspace),
+                                          ctypes.c_size_t(workspace.numel()), _stream(A)), "bnn_bmm_general_f32")
+    return out
+
+
+def bconv_general_f32(x, filt, stride: int, pad: int, pad_mode: int = PAD_MINUS_ONE, out=None, workspace=None):
+    """General BConv: fp32 x [N][H][W][C], filt [O][k][k][C] -> fp32 [N][P][Q][O] of the sign-binarized convolution."""
+    _dev(x, torch.float32, 4, "x"); _dev(filt, torch.float32, 4, "filt")
+    N, H, W, C = x.shape
+    O, k, _, C2 = filt.shape
+    if C != C2:
+        raise ValueError("channel mismatch")
+    P = (H + 2 * pad - k) // stride + 1 if stride > 0 else 1
+    Q = (W + 2 * pad - k) // stride + 1 if stride > 0 else 1
+    if out is None:
+        out = torch.empty((N, max(P, 1), max(Q, 1), O), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(int(load().bnn_bconv_general_workspace_bytes(N, H, W, C, O, k)), 256), dtype=torch.uint8,
+                                device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_bconv_general_f32(_ptr(x), _ptr(filt), _ptr(out), N, H, W, C, O, k, int(stride), int(pad), int(pad_mode),
+                                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(x)), "bnn_bconv_general_f32")
+    return out
 
 
 def unpack_i32(bits, cols: int):

@@ -22,7 +22,7 @@ int dispatch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, 
 }
 
 int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* thr, uint32_t* Cbits,
-               int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream) {
+               int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream, bool out_f32 = false) {
     if (!A || !B || M < 1 || N < 1 || K < 1) return BNN_ERR_INVALID_ARG;
     if (!C && !Cbits) return BNN_ERR_INVALID_ARG;
     if (Cbits && !thr) return BNN_ERR_INVALID_ARG;
@@ -39,7 +39,7 @@ int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* 
     g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0; g.kinv = 65536;
     g.div_pq = make_fastdiv(1u); g.div_q = make_fastdiv(1u);
     Epi e = {};
-    e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w;
+    e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w; e.out_f32 = out_f32 ? 1 : 0;
     return dispatch(A, B, g, e, path, static_cast<hipStream_t>(stream));
 }
 
@@ -61,7 +61,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
                  const int32_t* thr, uint32_t* bits, int N, int H, int W, int C, int O, int k, int stride,
                  int pad, int pad_mode, int path, void* stream, const uint32_t* resid_bits = nullptr,
                  const uint32_t* x2 = nullptr, const uint32_t* filt2 = nullptr, int H2 = 0, int W2 = 0, int C2 = 0,
-                 int stride2 = 1, bool sums16 = false) {
+                 int stride2 = 1, bool sums16 = false, bool out_f32 = false) {
     if (!in || !filt) return BNN_ERR_INVALID_ARG;
     if (!out && !bits) return BNN_ERR_INVALID_ARG;
     if (bits && !thr) return BNN_ERR_INVALID_ARG;
@@ -83,7 +83,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
         g.A2 = x2; g.B2 = filt2; g.H2 = H2; g.W2 = W2; g.cw2 = words(C2); g.stride2 = stride2; g.bits2 = C2;
     }
     Epi e = {};
-    e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O);
+    e.out = out; e.resid = resid; e.ldc = O; e.thr = thr; e.bits = bits; e.ldbits_w = words(O); e.out_f32 = out_f32 ? 1 : 0;
     e.resid_bits = resid ? nullptr : resid_bits; e.ld_resid_bits_w = words(O);
     if (sums16) {       // internal callers: out / resid point at 16-bit storage of the same values
         e.out16 = reinterpret_cast<int16_t*>(out); e.out = nullptr;
@@ -293,6 +293,59 @@ int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows,
     if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
     return launch_pack_f32(x, thr, bits, rows, cols, ldb_w, static_cast<hipStream_t>(stream));
 }
+int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream) {
+    if (!x || !bits || rows < 1 || cols < 1 || ldx < cols || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
+    if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
+    return launch_sign_pack_f32(x, bits, rows, cols, ldx, ldb_w, static_cast<hipStream_t>(stream));
+}
+
+size_t bnn_bmm_general_workspace_bytes(int M, int N, int K) {
+    if (M < 1 || N < 1 || K < 1 || K > BNN_MAX_K) return 0;
+    const size_t ldw = (size_t)round4(words(K));
+    return align256((size_t)M * ldw * 4) + align256((size_t)N * ldw * 4);
+}
+int bnn_bmm_general_f32(const float* A, const float* B, float* C, int M, int N, int K, int lda, int ldb, int ldc,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 1 || lda < K || ldb < K || ldc < N) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < bnn_bmm_general_workspace_bytes(M, N, K)) return BNN_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || !aligned16(C)) return BNN_ERR_ALIGNMENT;
+    const int ldw = round4(words(K));
+    uint32_t* Ab = static_cast<uint32_t*>(workspace);
+    uint32_t* Bb = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + align256((size_t)M * ldw * 4));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = launch_sign_pack_f32(A, Ab, M, K, lda, ldw, s);
+    if (rc != BNN_OK) return rc;
+    rc = launch_sign_pack_f32(B, Bb, N, K, ldb, ldw, s);
+    if (rc != BNN_OK) return rc;
+    return bmm_common(Ab, Bb, reinterpret_cast<int32_t*>(C), nullptr, nullptr, M, N, K, ldw, ldw, ldc, 0, BNN_PATH_AUTO, stream, true);
+}
+
+size_t bnn_bconv_general_workspace_bytes(int N, int H, int W, int C, int O, int k) {
+    if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1) return 0;
+    const size_t cw = (size_t)words(C);
+    return align256((size_t)N * H * W * cw * 4) + align256((size_t)O * k * k * cw * 4);
+}
+int bnn_bconv_general_f32(const float* in, const float* filt, float* out, int N, int H, int W, int C, int O, int k, int stride,
+                          int pad, int pad_mode, void* workspace, size_t workspace_bytes, void* stream) {
+    int P, Q;
+    if (!in || !filt || !out) return BNN_ERR_INVALID_ARG;
+    const int rc0 = conv_shape(N, H, W, C, O, k, stride, pad, pad_mode, &P, &Q);
+    if (rc0 != BNN_OK) return rc0;
+    if (!workspace || workspace_bytes < bnn_bconv_general_workspace_bytes(N, H, W, C, O, k)) return BNN_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || !aligned16(out)) return BNN_ERR_ALIGNMENT;
+    const int cw = words(C);
+    uint32_t* xb = static_cast<uint32_t*>(workspace);
+    uint32_t* fb = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + align256((size_t)N * H * W * cw * 4));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = launch_sign_pack_f32(in, xb, (long long)N * H * W, C, C, cw, s);
+    if (rc != BNN_OK) return rc;
+    rc = launch_sign_pack_f32(filt, fb, (long long)O * k * k, C, C, cw, s);
+    if (rc != BNN_OK) return rc;
+    return bconv_common(xb, fb, reinterpret_cast<int32_t*>(out), nullptr, nullptr, nullptr, N, H, W, C, O, k, stride, pad, pad_mode,
+                        BNN_PATH_AUTO, stream, nullptr, nullptr, nullptr, 0, 0, 0, 1, false, true);
+}
+
 int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream) {
     if (!bits || !out || rows < 1 || cols < 1 || ldb_w < words(cols) || ldo < cols) return BNN_ERR_INVALID_ARG;
     return launch_unpack_i32(bits, out, rows, cols, ldb_w, ldo, static_cast<hipStream_t>(stream));

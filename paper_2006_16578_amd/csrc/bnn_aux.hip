@@ -361,6 +361,13 @@ int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long 
     return check_launch();
 }
 
+// Binarization by sign (Eq. 1: x >= 0 -> +1) of a row-major fp32 matrix with row stride ldx.
+int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s) {
+    hipLaunchKernelGGL((pack_kernel<float, float, true>), dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, s,
+                       x, nullptr, 0.f, bits, rows, cols, ldx, ldb_w);
+    return check_launch();
+}
+
 int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s) {
     dim3 grid((unsigned)min((long long)cdiv(cols, 256), 64LL), (unsigned)min(rows, 65535LL));
     hipLaunchKernelGGL(unpack_kernel, grid, dim3(256), 0, s, bits, out, rows, cols, ldb_w, ldo);

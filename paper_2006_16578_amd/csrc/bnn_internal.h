@@ -71,6 +71,7 @@ struct Epi {
     const int16_t* resid16;
     int16_t* out16;
     int ldc;               // elements between rows of out / resid
+    int out_f32;           // 1: `out` receives the sums converted to fp32 (exact: |v| < 2^24) instead of int32
     const int32_t* thr;    // thr[col]: bit = (v >= thr[col])
     uint32_t* bits;        // bits[row*ldbits_w + col/32]
     int ldbits_w;          // words between rows of bits; words beyond ceil(cols/32) are zeroed
@@ -89,6 +90,7 @@ const char* describe_valu(const Geom& g);
 int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, long long rows, int cols,
                           int ldx, int ldb_w, hipStream_t s);
 int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
+int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s);
 int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s);
 int launch_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, hipStream_t s);

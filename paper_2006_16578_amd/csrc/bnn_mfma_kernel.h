@@ -167,7 +167,7 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
             for (int j = 0; j < NT; ++j) {
                 const int col = n0 + 32 * j + l32;
                 const int v = (int)acc[i][j][r] - corr + (HAS_RESID ? rv[r][j] : 0);
-                if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = v;
+                if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = e.out_f32 ? __float_as_int((float)v) : v;
                 if (e.out16 != nullptr && rok && cok[j]) e.out16[row * (long long)e.ldc + col] = (int16_t)v;
                 if (e.bits != nullptr) {
                     const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);

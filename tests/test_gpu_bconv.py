@@ -115,3 +115,16 @@ def test_error_codes(bnn):
     with pytest.raises(bnn.BnnError) as e:
         bnn.bconv(x, f7, 32, 1, 1)                # window larger than the padded image
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("shape", [(2, 6, 5, 40, 3, 3, 1, 1), (3, 20, 20, 128, 64, 3, 1, 1), (2, 17, 13, 96, 70, 3, 2, 1),
+                                   (1, 9, 9, 33, 5, 1, 1, 0)])
+@pytest.mark.parametrize("pad_mode", [0, 1])
+def test_general_bconv_f32(bnn, orc, shape, pad_mode):
+    # Sec. 7.3 "general" BConv: real-valued input and filter, real-valued output
+    N, H, W, C, O, k, st, pad = shape
+    rng = np.random.default_rng(sum(shape) + pad_mode)
+    x = rng.normal(size=(N, H, W, C)).astype(np.float32)
+    f = rng.normal(size=(O, k, k, C)).astype(np.float32)
+    got = host(bnn.bconv_general_f32(to_dev(x), to_dev(f), st, pad, pad_mode))
+    assert got.dtype == np.float32 and np.array_equal(got, orc.general_bconv_f32(x, f, st, pad, pad_mode))

@@ -153,3 +153,18 @@ def test_error_codes(bnn):
     assert lib.bnn_bmm(None, None, None, 1, 1, 1, 4, 4, 1, None) == -1
     p = __import__("ctypes").c_void_p(big.data_ptr())
     assert lib.bnn_bmm(p, p, p, 1, 1, (1 << 20) + 1, 1 << 16, 1 << 16, 1, None) == -3
+
+
+@pytest.mark.parametrize("shape", [(9, 5, 70), (300, 200, 1000), (1024, 1024, 1024), (64, 129, 4097)])
+def test_general_bmm_f32(bnn, orc, shape):
+    # Sec. 7.2 "general" BMM: real-valued operands, binarized by sign on the way in, real-valued result
+    M, N, K = shape
+    rng = np.random.default_rng(sum(shape))
+    A = rng.normal(size=(M, K)).astype(np.float32)
+    B = rng.normal(size=(N, K)).astype(np.float32)
+    A[0, 0] = 0.0
+    B[N - 1, K - 1] = -0.0
+    got = host(bnn.bmm_general_f32(to_dev(A), to_dev(B)))
+    assert got.dtype == np.float32 and np.array_equal(got, orc.general_bmm_f32(A, B))
+    zero = np.zeros(K, np.float32)
+    assert np.array_equal(words(bnn.sign_pack_f32(to_dev(A))), orc.pack_f32(A, zero))
