@@ -280,14 +280,25 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
     for l in range(4):
         net.add_fc(to_dev(params["W"][l]), to_dev(params["thr"][l]) if l < 3 else None, params["K"][l])
     mlp = {}
-    for batch in (1024, 8):
+    for batch in (32768, 1024, 8):
         imgs = to_dev(wl.mlp_images(batch))
         o = torch.empty((batch, 10), dtype=torch.int32, device=dev)
         t = _time_gpu(torch, lambda: net.forward(imgs, out=o), 50)
-        mlp["batch%d" % batch] = {"ms": round(t, 5), "images_per_s": round(batch / t * 1e3, 1)}
+        # one cooperative launch for the whole network (Sec. 6.2), with and without its device-wide barriers
+        # (without: results undefined, timing only -- the way the paper's Table 10 prices synchronisation)
+        tp = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o), 50)
+        tn = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o, no_sync=True), 50)
+        net.forward(imgs, out=o)
+        mlp["batch%d" % batch] = {"ms": round(min(t, tp), 5), "images_per_s": round(batch / min(t, tp) * 1e3, 1),
+                                  "per_layer_launches_ms": round(t, 5), "persistent_kernel_ms": round(tp, 5),
+                                  "persistent_without_barriers_ms": round(tn, 5),
+                                  "barrier_share_of_persistent": round(max(tp - tn, 0.0) / tp, 3)}
         if batch == 8:
             tg = _time_graph(torch, lambda: net.forward(imgs, out=o), 50)
             mlp["batch8"]["hip_graph_replay_ms"] = round(tg, 5)
+        del imgs, o
+    mlp["paper_rtx2080_btc_fmt_context_only"] = {"latency8_ms": 0.055, "images_per_s_batch1024": 5.48e6,
+                                                 "images_per_s_batch32k": 7.62e6, "sync_share": 0.0826}
     out["mlp_784_1024x3_10"] = mlp
     # ---- ResNet-18-shaped forward (config 5), batch 256
     p = wl.resnet18_params()

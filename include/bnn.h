@@ -219,6 +219,17 @@ int bnn_net_workspace_bytes(const bnn_net* net, int batch, size_t* bytes);
  * workspace: device memory of at least bnn_net_workspace_bytes(), 256-byte aligned. */
 int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch,
                     void* workspace, size_t workspace_bytes, int path, void* stream);
+/* The same forward as ONE kernel launch (Sec. 6.2: every layer a device function of one kernel, a device-wide
+ * barrier between layers).  Supported: an input layer (u8 or bits) followed by fully-connected layers only, at
+ * most 8 of them; anything else returns BNN_ERR_UNSUPPORTED (use bnn_net_forward).  Same arguments, workspace
+ * and results as bnn_net_forward.  The grid never exceeds what the device holds at once; a barrier
+ * that is not reached by all workgroups within about 0.1 s makes every workgroup leave the kernel, the output
+ * is then undefined.  Calls that overlap on one device must use different workspaces.
+ * flags: 0, or BNN_PERSIST_NO_SYNC = skip the barriers -- the results are then UNDEFINED; it exists only to
+ * measure what the barriers cost. */
+#define BNN_PERSIST_NO_SYNC 1
+int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch,
+                               void* workspace, size_t workspace_bytes, int flags, void* stream);
 /* After a forward: device pointer (inside the workspace) and shape of the packed bits produced by
  * layer `layer` (0 = input layer), for layer-by-layer checking.  words_per_row receives the row
  * length in words, rows the number of rows (batch, or batch*P*Q). */

@@ -28,7 +28,7 @@ EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
-           "bnn_net_forward", "bnn_net_layer_bits"]
+           "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_layer_bits"]
 
 
 class BnnError(RuntimeError):
@@ -467,6 +467,22 @@ class Net:
         with torch.cuda.device(x.device):
             _check(load().bnn_net_forward(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws), ctypes.c_size_t(self._ws.numel()),
                                           int(path), _stream(x)), "bnn_net_forward")
+        return out
+
+    def forward_persistent(self, x, out=None, no_sync: bool = False):
+        """Same forward in one cooperative kernel launch (FC chains only).  no_sync skips the device-wide
+        barriers: results undefined, for timing the barriers only."""
+        _dev(x, self._in_dtype, None, "input")
+        batch = x.shape[0]
+        need = self.workspace_bytes(batch)
+        if self._ws is None or self._ws.numel() < need or self._ws.device != x.device:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        if out is None:
+            out = torch.empty((batch, self._out_cols), dtype=self._out_kind, device=x.device)
+        with torch.cuda.device(x.device):
+            _check(load().bnn_net_forward_persistent(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws),
+                                                     ctypes.c_size_t(self._ws.numel()), 1 if no_sync else 0, _stream(x)),
+                   "bnn_net_forward_persistent")
         return out
 
     def layer_bits(self, layer: int):

@@ -21,6 +21,15 @@ int dispatch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, 
     }
 }
 
+Geom bmm_geom(int M, int N, int K, int lda_w, int ldb_w) {
+    Geom g = {};
+    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = round4(words(K)); g.bits_tap = K;
+    g.lda_w = lda_w; g.ldb_w = ldb_w;
+    g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0; g.kinv = 65536;
+    g.div_pq = make_fastdiv(1u); g.div_q = make_fastdiv(1u);
+    return g;
+}
+
 int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* thr, uint32_t* Cbits,
                int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream, bool out_f32 = false) {
     if (!A || !B || M < 1 || N < 1 || K < 1) return BNN_ERR_INVALID_ARG;
@@ -33,11 +42,7 @@ int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* 
     if (C && (ldc < N || !aligned16(C))) return ldc < N ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
     if (Cbits && (ldcb_w < words(N) || !aligned16(Cbits))) return ldcb_w < words(N) ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
     if (thr && !aligned16(thr)) return BNN_ERR_ALIGNMENT;
-    Geom g = {};
-    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = kw4; g.bits_tap = K;
-    g.lda_w = lda_w; g.ldb_w = ldb_w;
-    g.H = g.W = g.P = g.Q = g.k = g.stride = 1; g.pad = 0; g.excl = 0; g.kinv = 65536;
-    g.div_pq = make_fastdiv(1u); g.div_q = make_fastdiv(1u);
+    const Geom g = bmm_geom(M, N, K, lda_w, ldb_w);
     Epi e = {};
     e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w; e.out_f32 = out_f32 ? 1 : 0;
     return dispatch(A, B, g, e, path, static_cast<hipStream_t>(stream));
@@ -126,6 +131,7 @@ struct Plan {
     size_t resid_off[3] = {0, 0, 0};
     size_t resid_bytes = 0;
     size_t bwn_off = 0, bwn_bytes = 0;   // expanded first-layer weights (first layer with binarized weights only)
+    size_t sync_off = 0;                 // barrier counter and abort flag of the persistent kernel
     int rc = BNN_OK;
 };
 
@@ -199,6 +205,7 @@ Plan plan(bnn_net* net, int batch) {
         const bnn_net::Layer& L0 = net->layers[0];
         pl.bwn_off = off; pl.bwn_bytes = bwn_workspace_bytes(L0.c, L0.d, L0.k); off += align256(pl.bwn_bytes);
     }
+    pl.sync_off = off; off += 256;
     pl.total = off;
     return pl;
 }
@@ -578,6 +585,60 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
         cur = obits; curH = L.H; curW = L.W; curC = L.C; cur_ld = L.words_per_row;
     }
     return BNN_OK;
+}
+
+int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch, void* workspace,
+                               size_t workspace_bytes, int flags, void* stream) {
+    if (!net || !input || !output || batch < 1 || net->layers.size() < 2) return BNN_ERR_INVALID_ARG;
+    if (flags & ~BNN_PERSIST_NO_SYNC) return BNN_ERR_INVALID_ARG;
+    for (size_t i = 0; i < net->layers.size(); ++i) {
+        const bnn_net::Kind kd = net->layers[i].kind;
+        const bool ok = (i == 0) ? (kd == bnn_net::IN_U8 || kd == bnn_net::IN_BITS) : (kd == bnn_net::FC);
+        if (!ok) return BNN_ERR_UNSUPPORTED;           // fully-connected chains only
+    }
+    if (net->layers.size() - 1 > (size_t)PERSIST_MAX_LAYERS) return BNN_ERR_UNSUPPORTED;
+    Plan pl = plan(net, batch);
+    if (pl.rc != BNN_OK) return pl.rc;
+    if (!workspace || workspace_bytes < pl.total) return BNN_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BNN_ERR_ALIGNMENT;
+    char* ws = static_cast<char*>(workspace);
+    net->last_ws = ws; net->last_batch = batch;
+
+    PersistNet pn = {};
+    const bnn_net::Layer& L0 = net->layers[0];
+    const uint32_t* cur;
+    if (L0.kind == bnn_net::IN_U8) {
+        pn.in_u8 = static_cast<const uint8_t*>(input);
+        pn.in_bits = reinterpret_cast<uint32_t*>(ws + L0.bits_off);
+        pn.in_rows = batch; pn.in_cols = L0.a; pn.in_thr = L0.thr_u8; pn.in_ldw = L0.words_per_row;
+        cur = pn.in_bits;
+    } else {
+        if (!aligned16(input)) return BNN_ERR_ALIGNMENT;
+        cur = static_cast<const uint32_t*>(input);
+    }
+    int cur_ld = L0.words_per_row;
+    for (size_t i = 1; i < net->layers.size(); ++i) {
+        const bnn_net::Layer& L = net->layers[i];
+        PersistLayer& P = pn.layer[pn.nlayers++];
+        const int K = L.a, Nn = L.b;
+        if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+        P.A = cur; P.B = static_cast<const uint32_t*>(L.w0);
+        P.g = bmm_geom(batch, Nn, K, cur_ld, round4(words(K)));
+        P.e = Epi{};
+        int col_span = Nn;
+        if (L.t0) {
+            P.e.thr = static_cast<const int32_t*>(L.t0);
+            P.e.bits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
+            P.e.ldbits_w = L.words_per_row;
+            col_span = max(Nn, L.words_per_row * 32);   // pad words of the output rows are written (as zeros) too
+            cur = P.e.bits; cur_ld = L.words_per_row;
+        } else {
+            P.e.out = static_cast<int32_t*>(output); P.e.ldc = Nn;
+        }
+        P.gx = (int)cdiv(batch, 64); P.gy = (int)cdiv(col_span, 64);
+    }
+    return launch_persist_fc(pn, reinterpret_cast<unsigned*>(ws + pl.sync_off), (flags & BNN_PERSIST_NO_SYNC) ? 0 : 1,
+                             static_cast<hipStream_t>(stream));
 }
 
 int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int64_t* rows, int* words_per_row) {

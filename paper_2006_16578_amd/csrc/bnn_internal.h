@@ -77,6 +77,25 @@ struct Epi {
     int ldbits_w;          // words between rows of bits; words beyond ceil(cols/32) are zeroed
 };
 
+// A chain of binarized FC layers for the whole-network persistent kernel (passed by value as a kernel argument).
+constexpr int PERSIST_MAX_LAYERS = 8;
+struct PersistLayer {
+    const uint32_t* A;
+    const uint32_t* B;
+    Geom g;
+    Epi e;
+    int gx, gy;            // 64 x 64 output tiles
+};
+struct PersistNet {
+    int nlayers;
+    const uint8_t* in_u8;  // optional input layer: [in_rows][in_cols] 8-bit values -> in_bits [in_rows][in_ldw], bit = (x >= in_thr)
+    uint32_t* in_bits;
+    long long in_rows;
+    int in_cols, in_thr, in_ldw;
+    PersistLayer layer[PERSIST_MAX_LAYERS];
+};
+int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, hipStream_t s);
+
 int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_staged(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);

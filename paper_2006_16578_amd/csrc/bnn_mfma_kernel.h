@@ -292,13 +292,11 @@ __device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, 
 // V: words each lane loads per fragment and chunk (a chunk is 2*V words = V MFMA K-steps);
 // CONV: rows are output pixels gathered through the filter window; EXCL: out-of-frame taps
 // contribute nothing; GUARD: the last chunk of a tap may run past tw.
+// One workgroup tile (bx, by) of the product: everything from the operand loads to the epilogue.
 template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
-__global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __restrict__ A,
-                                                             const uint32_t* __restrict__ B, Geom g, Epi e,
-                                                             int gx, int gy) {
+__device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const uint32_t* __restrict__ B, const Geom& g,
+                                          const Epi& e, const int bx, const int by) {
     constexpr int MT = TL::MT, NT = TL::NT;
-    int bx, by;
-    if (!tile_coords(gx, gy, bx, by)) return;          // uniform for the workgroup
     const int lane = threadIdx.x & 63;
     const int l32 = lane & 31;
     const int half = lane >> 5;
@@ -428,6 +426,15 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __r
     int corr2 = 0;
     if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
     epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap);
+}
+
+template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
+__global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __restrict__ A,
+                                                             const uint32_t* __restrict__ B, Geom g, Epi e,
+                                                             int gx, int gy) {
+    int bx, by;
+    if (!tile_coords(gx, gy, bx, by)) return;          // uniform for the workgroup
+    mfma_tile<TL, V, CONV, EXCL, GUARD>(A, B, g, e, bx, by);
 }
 
 template <class TL, int V, bool CONV, bool GUARD>

@@ -228,3 +228,44 @@ def test_bwn_exact_cases(bnn, orc):
     _, y = bnn.bwn_conv_thr(to_dev(x), to_dev(wb), zero, 3, 1, 2, want_f32=True)
     ref = orc.bwn_conv_f32(x, wb, 3, 1, 2)
     assert np.abs(ref).max() > 1e7 and np.array_equal(host(y), ref)
+
+
+# ------------------------------------------------------------------ whole-network persistent kernel (FC chains)
+@pytest.mark.parametrize("batch", [8, 37, 1024, 3000])
+def test_mlp_persistent(bnn, orc, batch):
+    params = wl.mlp_params()
+    imgs = wl.mlp_images(batch)
+    net = bnn.Net()
+    net.input_u8(784, params["in_thr"])
+    for l in range(4):
+        net.add_fc(to_dev(params["W"][l]), to_dev(params["thr"][l]) if l < 3 else None, params["K"][l])
+    ref, hidden = nets.mlp_forward(imgs, params, keep=True)
+    x = to_dev(imgs)
+    for rep in range(3):                                   # the barrier counter is re-armed on every call
+        got = host(net.forward_persistent(x))
+        assert np.array_equal(got, ref), "call %d" % rep
+    for l in range(3):
+        assert np.array_equal(words(net.layer_bits(l + 1)), hidden[l])
+    assert np.array_equal(host(net.forward(x)), ref)       # and the per-layer path still agrees
+
+
+def test_persistent_bits_input_and_limits(bnn, orc):
+    rng = np.random.default_rng(3)
+    dims = (200, 96, 70, 5)
+    W = [wl.random_bits(rng, dims[i + 1], dims[i], wl.round_up(wl.nwords(dims[i]), 4)) for i in range(3)]
+    thr = [wl.random_thresholds(rng, dims[i + 1], -8, 8) for i in range(2)]
+    x = wl.random_bits(rng, 50, dims[0], wl.round_up(wl.nwords(dims[0]), 4))
+    net = bnn.Net()
+    net.input_bits(dims[0])
+    for i in range(3):
+        net.add_fc(to_dev(W[i]), to_dev(thr[i]) if i < 2 else None, dims[i])
+    h = x
+    for i in range(2):
+        h = orc.threshold_pack(orc.bmm(h, W[i], dims[i]), thr[i], ldb_w=wl.round_up(wl.nwords(dims[i + 1]), 4))
+    ref = orc.bmm(h, W[2], dims[2])
+    assert np.array_equal(host(net.forward_persistent(to_dev(x))), ref)
+    # a convolutional network is refused, not mis-run
+    spec = wl.cnn_layers("cifar_vgg")
+    cnn = bnn.Net.from_layers(spec["layers"], spec["in_hw"])
+    with pytest.raises(bnn.BnnError):
+        cnn.forward_persistent(to_dev(wl.cnn_input("cifar_vgg", 2)))
