@@ -273,6 +273,28 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
                     "tops": round(2.0 * 16 * 64 * 64 * ch * 9 * ch / t / 1e9, 1)})
         del x, f, o, ws
     out["general_f32_in_f32_out"] = gen
+    # ---- layout study (Sec. 5.1 / 4.1 redone for this chip): weights pre-tiled in MFMA fragment order against plain
+    # rows on the shapes that read operands straight from L2, and the fragment-load latency against the row stride
+    lay = {"fc_shapes": [], "fragment_load_ticks_vs_row_stride_bytes": {}}
+    for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096)):
+        case = wl.bmm_case(2, M, N, K, index0=900 + M % 7)
+        A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+        Bt = bnn.tile_b(B, K)
+        o = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
+        t_rows = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o), 30)
+        t_tile = _time_gpu(torch, lambda: bnn.bmm_thr_tiled(A, Bt, tau, N, K, out=o), 30)
+        t_rows_direct = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o, path=bnn.PATH_MFMA), 30)
+        lay["fc_shapes"].append({"M": M, "N": N, "K": K, "rows_kernel": bnn.bmm_kernel_name(M, N, K),
+                                 "rows_ms": round(t_rows, 5), "pretiled_direct_ms": round(t_tile, 5),
+                                 "rows_tops": round(2.0 * M * N * K / t_rows / 1e9, 1),
+                                 "pretiled_tops": round(2.0 * M * N * K / t_tile / 1e9, 1)})
+        del A, B, Bt, o
+    for stride in (32, 48, 64, 96, 128, 256, 512, 1024, 2048, 2064, 4096):
+        lay["fragment_load_ticks_vs_row_stride_bytes"][str(stride)] = {
+            "dependent": round(bnn.probe_load_stride(stride, iters=8192, dependent=True), 1),
+            "eight_in_flight": round(bnn.probe_load_stride(stride, iters=8192, dependent=False), 1),
+            "dependent_16KiB_footprint": round(bnn.probe_load_stride(stride, iters=8192, dependent=True, footprint_bytes=16384), 1)}
+    out["layout_study"] = lay
     # ---- binarized MLP (config 3)
     params = wl.mlp_params()
     net = bnn.Net()

@@ -125,6 +125,26 @@ int bnn_pack_u8(const uint8_t* x, int thr, uint32_t* bits, int64_t rows, int col
 int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
 /* out[r][c] = +1 / -1 as int32 from bits [rows][ldb_w]; out [rows][ldo].  Seeds the int32
  * residual chain from a bit tensor. */
+/* Pre-tiled weight operand, in the spirit of the paper's FSB format (Sec. 5.1: store the operand in the order the
+ * matrix unit's tile loads consume it), with this chip's tile: rows are grouped by 32, and a group stores, for
+ * every 16-byte step along K, the 16 bytes of its 32 rows back to back, so that the 32 lanes of an MFMA fragment
+ * load read 512 contiguous bytes.  16-byte unit u of row r moves to unit ((r/32) * (ldb_w/4) + u) * 32 + r % 32.
+ *   bnn_tile_b: B [N][ldb_w] -> B_tiled, ceil(N/32)*32 * ldb_w words (rows past N are zeros); ldb_w % 4 == 0.
+ *   bnn_bmm_tiled / bnn_bmm_thr_tiled: as bnn_bmm / bnn_bmm_thr with B given in that format (matrix-core path,
+ *   operands read straight from L2 without LDS staging). */
+int bnn_tile_b(const uint32_t* B, uint32_t* B_tiled, int N, int K, int ldb_w, void* stream);
+int bnn_bmm_tiled(const uint32_t* A, const uint32_t* B_tiled, int32_t* C, int M, int N, int K,
+                  int lda_w, int ldb_w, int ldc, void* stream);
+int bnn_bmm_thr_tiled(const uint32_t* A, const uint32_t* B_tiled, const int32_t* thr, uint32_t* Cbits, int M, int N, int K,
+                      int lda_w, int ldb_w, int ldcb_w, void* stream);
+/* Diagnostic, after the load-latency microbenchmark of Sec. 4.1: ONE wave loads `iters` MFMA operand fragments
+ * (lane l: 16 bytes of row l % 32 at byte 16 * (l / 32)) from a zero-filled buffer of `rows` rows that are
+ * `stride_bytes` apart (multiple of 16, >= 32; the buffer holds rows * stride_bytes bytes), walking along the rows.
+ * dependent != 0 chains every address on the previous load (latency), 0 issues them back to back.
+ * cycles[0] receives the elapsed ticks of the shader cycle counter, cycles[1] is scratch. */
+int bnn_probe_load_stride(const uint32_t* zeros, int64_t* cycles, int stride_bytes, int rows, int iters, int dependent,
+                          void* stream);
+
 /* Binarization by sign (Eq. 1): bit = (x >= 0).  x [rows][ldx] fp32 -> bits [rows][ldb_w] (pad bits and pad words 0). */
 int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream);
 

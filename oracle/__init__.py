@@ -102,6 +102,20 @@ def bmm_rows(A, B, K: int, row0: int, rows: int) -> np.ndarray:
     return C
 
 
+def tile_b(B) -> np.ndarray:
+    """The pre-tiled weight layout as its definition: rows grouped by 32, 16-byte unit u of row r moves to unit
+    ((r // 32) * units_per_row + u) * 32 + r % 32; rows past N are zeros.  A pure permutation, no arithmetic."""
+    B = _words(B, 2)
+    N, ldw = B.shape
+    assert ldw % 4 == 0
+    upr = ldw // 4
+    groups = (N + 31) // 32
+    padded = np.zeros((groups * 32, upr, 4), dtype=np.uint32)
+    padded[:N] = B.reshape(N, upr, 4)
+    # [group][row-in-group][unit][4] -> [group][unit][row-in-group][4]
+    return np.ascontiguousarray(padded.reshape(groups, 32, upr, 4).transpose(0, 2, 1, 3)).reshape(groups * 32, ldw)
+
+
 # ----------------------------------------------------------------------------- O3
 def conv_out_size(H: int, k: int, stride: int, pad: int) -> int:
     return (H + 2 * pad - k) // stride + 1

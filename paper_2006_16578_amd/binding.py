@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
+           "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
@@ -216,6 +216,54 @@ def pack_f32(x, thr, ldb_w: int | None = None):
     with torch.cuda.device(x.device):
         _check(load().bnn_pack_f32(_ptr(x), _ptr(thr), _ptr(bits), ctypes.c_int64(rows), cols, ldb_w, _stream(x)), "bnn_pack_f32")
     return bits
+
+
+def tile_b(B, K: int):
+    """Weights [N][ldb_w] -> the pre-tiled layout bnn_bmm_tiled reads (32-row groups, 16-byte units interleaved)."""
+    _dev(B, _BITS, 2, "B")
+    N, ldb = B.shape
+    out = torch.empty(((N + 31) // 32 * 32, ldb), dtype=_BITS, device=B.device)
+    with torch.cuda.device(B.device):
+        _check(load().bnn_tile_b(_ptr(B), _ptr(out), N, int(K), ldb, _stream(B)), "bnn_tile_b")
+    return out
+
+
+def bmm_tiled(A, Bt, N: int, K: int, out=None):
+    _dev(A, _BITS, 2, "A"); _dev(Bt, _BITS, 2, "Bt")
+    M = A.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    with torch.cuda.device(A.device):
+        _check(load().bnn_bmm_tiled(_ptr(A), _ptr(Bt), _ptr(out), M, int(N), int(K), A.shape[1], Bt.shape[1], out.shape[1],
+                                    _stream(A)), "bnn_bmm_tiled")
+    return out
+
+
+def bmm_thr_tiled(A, Bt, thr, N: int, K: int, ldcb_w: int | None = None, out=None):
+    _dev(A, _BITS, 2, "A"); _dev(Bt, _BITS, 2, "Bt"); _dev(thr, torch.int32, 1, "thr")
+    M = A.shape[0]
+    ldcb_w = round_up(nwords(N), 4) if ldcb_w is None else ldcb_w
+    if out is None:
+        out = torch.empty((M, ldcb_w), dtype=_BITS, device=A.device)
+    with torch.cuda.device(A.device):
+        _check(load().bnn_bmm_thr_tiled(_ptr(A), _ptr(Bt), _ptr(thr), _ptr(out), M, int(N), int(K), A.shape[1], Bt.shape[1],
+                                        out.shape[1], _stream(A)), "bnn_bmm_thr_tiled")
+    return out
+
+
+def probe_load_stride(stride_bytes: int, rows: int | None = None, iters: int = 4096, dependent: bool = True, device="cuda",
+                      footprint_bytes: int = 1 << 20):
+    """Shader-cycle-counter ticks per MFMA operand-fragment load of one wave, rows `stride_bytes` apart (diagnostic).
+    By default the buffer is `footprint_bytes` in all, so that every stride is measured at the same cache level."""
+    if rows is None:
+        rows = max(32, footprint_bytes // stride_bytes // 32 * 32)
+    buf = torch.zeros(rows * stride_bytes // 4, dtype=_BITS, device=device)
+    cyc = torch.zeros(2, dtype=torch.int64, device=device)
+    with torch.cuda.device(buf.device):
+        for _ in range(2):                                  # the second run has the buffer in cache
+            _check(load().bnn_probe_load_stride(_ptr(buf), _ptr(cyc), int(stride_bytes), int(rows), int(iters),
+                                                1 if dependent else 0, _stream(buf)), "bnn_probe_load_stride")
+    return float(cyc[0].item()) / iters
 
 
 def sign_pack_f32(x, ldb_w: int | None = None):

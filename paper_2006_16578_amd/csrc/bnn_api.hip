@@ -31,7 +31,8 @@ Geom bmm_geom(int M, int N, int K, int lda_w, int ldb_w) {
 }
 
 int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* thr, uint32_t* Cbits,
-               int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream, bool out_f32 = false) {
+               int M, int N, int K, int lda_w, int ldb_w, int ldc, int ldcb_w, int path, void* stream, bool out_f32 = false,
+               bool b_tiled = false) {
     if (!A || !B || M < 1 || N < 1 || K < 1) return BNN_ERR_INVALID_ARG;
     if (!C && !Cbits) return BNN_ERR_INVALID_ARG;
     if (Cbits && !thr) return BNN_ERR_INVALID_ARG;
@@ -42,7 +43,9 @@ int bmm_common(const uint32_t* A, const uint32_t* B, int32_t* C, const int32_t* 
     if (C && (ldc < N || !aligned16(C))) return ldc < N ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
     if (Cbits && (ldcb_w < words(N) || !aligned16(Cbits))) return ldcb_w < words(N) ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
     if (thr && !aligned16(thr)) return BNN_ERR_ALIGNMENT;
-    const Geom g = bmm_geom(M, N, K, lda_w, ldb_w);
+    Geom g = bmm_geom(M, N, K, lda_w, ldb_w);
+    g.b_tiled = b_tiled ? 1 : 0;
+    if (b_tiled && path == BNN_PATH_VALU) return BNN_ERR_UNSUPPORTED;
     Epi e = {};
     e.out = C; e.resid = nullptr; e.ldc = ldc; e.thr = thr; e.bits = Cbits; e.ldbits_w = ldcb_w; e.out_f32 = out_f32 ? 1 : 0;
     return dispatch(A, B, g, e, path, static_cast<hipStream_t>(stream));
@@ -300,6 +303,28 @@ int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows,
     if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;
     return launch_pack_f32(x, thr, bits, rows, cols, ldb_w, static_cast<hipStream_t>(stream));
 }
+int bnn_tile_b(const uint32_t* B, uint32_t* B_tiled, int N, int K, int ldb_w, void* stream) {
+    if (!B || !B_tiled || N < 1 || K < 1 || ldb_w < round4(words(K))) return BNN_ERR_INVALID_ARG;
+    if ((ldb_w & 3) || !aligned16(B) || !aligned16(B_tiled)) return BNN_ERR_ALIGNMENT;
+    return launch_tile_b(B, B_tiled, N, ldb_w, static_cast<hipStream_t>(stream));
+}
+int bnn_bmm_tiled(const uint32_t* A, const uint32_t* B_tiled, int32_t* C, int M, int N, int K, int lda_w, int ldb_w, int ldc,
+                  void* stream) {
+    if (!C) return BNN_ERR_INVALID_ARG;
+    return bmm_common(A, B_tiled, C, nullptr, nullptr, M, N, K, lda_w, ldb_w, ldc, 0, BNN_PATH_MFMA, stream, false, true);
+}
+int bnn_bmm_thr_tiled(const uint32_t* A, const uint32_t* B_tiled, const int32_t* thr, uint32_t* Cbits, int M, int N, int K,
+                      int lda_w, int ldb_w, int ldcb_w, void* stream) {
+    if (!Cbits || !thr) return BNN_ERR_INVALID_ARG;
+    return bmm_common(A, B_tiled, nullptr, thr, Cbits, M, N, K, lda_w, ldb_w, 0, ldcb_w, BNN_PATH_MFMA, stream, false, true);
+}
+int bnn_probe_load_stride(const uint32_t* zeros, int64_t* cycles, int stride_bytes, int rows, int iters, int dependent,
+                          void* stream) {
+    if (!zeros || !cycles || stride_bytes < 32 || (stride_bytes & 15) || rows < 32 || iters < 1) return BNN_ERR_INVALID_ARG;
+    return launch_probe_stride(zeros, reinterpret_cast<long long*>(cycles), stride_bytes, rows, iters, dependent ? 1 : 0,
+                               static_cast<hipStream_t>(stream));
+}
+
 int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream) {
     if (!x || !bits || rows < 1 || cols < 1 || ldx < cols || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
     if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;

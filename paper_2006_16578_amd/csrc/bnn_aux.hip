@@ -43,6 +43,63 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     }
 }
 
+// Re-tiles a packed operand for the matrix-core fragment loads (the idea of the paper's FSB format, Sec. 5.1,
+// with this chip's tile): rows are grouped by 32; a group stores, for every 16-byte step along K, the 16 bytes
+// of its 32 rows back to back.  Unit (16 bytes) u of row r goes to ((r / 32) * units_per_row + u) * 32 + r % 32.
+// Rows past N in the last group are written as zeros.  One thread per destination unit.
+__global__ __launch_bounds__(256) void tile_b_kernel(const uint4* __restrict__ B, uint4* __restrict__ Bt, int N, int upr,
+                                                     long long nunits) {
+    const long long d = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (d >= nunits) return;
+    const int r32 = (int)(d & 31);
+    const long long gu = d >> 5;
+    const long long grp = gu / upr;
+    const int u = (int)(gu - grp * upr);
+    const long long row = grp * 32 + r32;
+    Bt[d] = row < N ? B[row * upr + u] : make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Load-latency probe in the manner of the paper's Sec. 4.1 (latency of a tile load against the row stride):
+// one wave repeatedly loads the operand fragment of one MFMA -- lane l reads 16 bytes of row l % 32 at byte
+// offset 16 * (l / 32) -- from rows `stride` bytes apart, walking along K.  dependent = 1 chains each address
+// on the previous load's data (pure latency), 0 issues them back to back (throughput of one wave).
+// cycles[0] = ticks of the shader cycle counter for `iters` loads, cycles[1] = a checksum that keeps the loads alive.
+__global__ __launch_bounds__(64) void probe_stride_kernel(const uint32_t* __restrict__ buf, long long* __restrict__ cycles,
+                                                          int stride_bytes, int rows, int iters, int dependent) {
+    const int lane = threadIdx.x;
+    const int r = lane & 31, half = lane >> 5;
+    const int steps = stride_bytes / 32;                     // fragment positions along a row (32 bytes each)
+    const char* base = reinterpret_cast<const char*>(buf) + (long long)r * stride_bytes + half * 16;
+    unsigned sum = 0;
+    int step = 0, row0 = 0;
+    auto advance = [&]() {
+        if (++step >= steps) { step = 0; row0 += 32; if (row0 + 32 > rows) row0 = 0; }
+    };
+    const long long t0 = __builtin_readcyclecounter();
+    if (dependent) {
+        for (int it = 0; it < iters; ++it) {
+            const uint4 v = *reinterpret_cast<const uint4*>(base + (long long)row0 * stride_bytes + step * 32);
+            sum += v.y ^ v.z ^ v.w;
+            step += (int)v.x;                                // the buffer holds zeros: a data dependence, same addresses
+            advance();
+        }
+    } else {
+        for (int it = 0; it < iters; it += 8) {              // eight loads in flight
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = *reinterpret_cast<const uint4*>(base + (long long)row0 * stride_bytes + step * 32);
+                advance();
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+    }
+    const long long t1 = __builtin_readcyclecounter();
+    if (lane == 0) cycles[0] = t1 - t0;
+    if (sum == 0x12345u && lane == 1) cycles[1] = sum;
+}
+
 // Max-pooling of +1/-1 activations after the threshold = bitwise OR of the packed words of the
 // window (Sec. 6.1).  One thread per output word.
 __global__ __launch_bounds__(256) void maxpool_or_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
@@ -365,6 +422,20 @@ int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long 
 int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s) {
     hipLaunchKernelGGL((pack_kernel<float, float, true>), dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, s,
                        x, nullptr, 0.f, bits, rows, cols, ldx, ldb_w);
+    return check_launch();
+}
+
+int launch_tile_b(const uint32_t* B, uint32_t* Bt, int N, int ldb_w, hipStream_t s) {
+    const int upr = ldb_w / 4;
+    const long long nunits = cdiv(N, 32) * 32 * (long long)upr;
+    hipLaunchKernelGGL(tile_b_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, reinterpret_cast<const uint4*>(B),
+                       reinterpret_cast<uint4*>(Bt), N, upr, nunits);
+    return check_launch();
+}
+
+int launch_probe_stride(const uint32_t* buf, long long* cycles, int stride_bytes, int rows, int iters, int dependent,
+                        hipStream_t s) {
+    hipLaunchKernelGGL(probe_stride_kernel, dim3(1), dim3(64), 0, s, buf, cycles, stride_bytes, rows, iters, dependent);
     return check_launch();
 }
 

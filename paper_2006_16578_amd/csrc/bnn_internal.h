@@ -51,6 +51,7 @@ struct Geom {
     FastDiv div_pq, div_q;   // divisions by P*Q and by Q (row -> image, pixel row, pixel column); rows < 2^31
     int kinv;        // ceil(65536 / k): tap / k == (tap * kinv) >> 16 for every tap < k*k + 64 (checked for k <= 42; k <= 32 accepted)
     int excl;        // 1: out-of-frame taps contribute nothing; 0: they count as -1
+    int b_tiled;     // BMM only: B is stored in tiles of 32 rows x 16 bytes (bnn_tile_b), ldb_w words per row as before
     // Optional second source, accumulated into the same sums: a 1x1 convolution (no padding) of
     // a second packed tensor A2 [N][H2][W2][cw2] sampled at (p*stride2, q*stride2) with filters
     // B2 [cols][cw2] -- the binarized downsample shortcut of a residual block, fused so that its
@@ -110,6 +111,8 @@ int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, 
                           int ldx, int ldb_w, hipStream_t s);
 int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s);
+int launch_tile_b(const uint32_t* B, uint32_t* Bt, int N, int ldb_w, hipStream_t s);
+int launch_probe_stride(const uint32_t* buf, long long* cycles, int stride_bytes, int rows, int iters, int dependent, hipStream_t s);
 int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s);
 int launch_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, hipStream_t s);

@@ -22,7 +22,7 @@ bool staged_ok(const Geom& g, int tile) {
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
     const int tile = mfma::pick_tile(g, &e);
     if (!g.conv) {
-        if (staged_ok(g, tile)) {
+        if (!g.b_tiled && staged_ok(g, tile)) {
             switch (tile) {
                 case 0: return mfma::launch_staged_tile<mfma::TileBig, 16, false>(A, B, g, e, s);
                 case 1: return mfma::launch_staged_tile<mfma::TileTall, 16, false>(A, B, g, e, s);
@@ -42,14 +42,14 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 
 const char* describe_mfma(const Geom& g) {
     const int tile = mfma::pick_tile(g);
-    const bool st = staged_ok(g, tile);
+    const bool st = !g.b_tiled && staged_ok(g, tile);
     switch (tile) {
         case 0: return g.conv ? (st ? "mfma_fp4_conv_lds_wg256x128" : "mfma_fp4_conv_wg256x128")
-                              : "mfma_fp4_bmm_lds_wg256x128";
+                              : (st ? "mfma_fp4_bmm_lds_wg256x128" : "mfma_fp4_bmm_wg256x128");
         case 1: return g.conv ? (st ? "mfma_fp4_conv_lds_wg512x64" : "mfma_fp4_conv_wg512x64")
-                              : "mfma_fp4_bmm_lds_wg512x64";
+                              : (st ? "mfma_fp4_bmm_lds_wg512x64" : "mfma_fp4_bmm_wg512x64");
         case 2: return g.conv ? (st ? "mfma_fp4_conv_lds_wg128x128" : "mfma_fp4_conv_wg128x128")
-                              : "mfma_fp4_bmm_lds_wg128x128";
+                              : (st ? "mfma_fp4_bmm_lds_wg128x128" : "mfma_fp4_bmm_wg128x128");
         default: return g.conv ? "mfma_fp4_conv_wg64x64" : "mfma_fp4_bmm_wg64x64";
     }
 }

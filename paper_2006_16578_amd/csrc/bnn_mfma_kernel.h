@@ -330,8 +330,11 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int col = min(n0 + 32 * j + l32, g.cols - 1);
-        brow[j] = B + (long long)col * g.ldb_w;
+        // tiled B: rows are grouped by 32; a group stores, for each 16-byte step along K, its 32 rows' 16 bytes
+        // back to back, so the 32 lanes of a fragment load read 512 contiguous bytes
+        brow[j] = g.b_tiled ? B + (long long)(col >> 5) * g.ldb_w * 32 + (col & 31) * 4 : B + (long long)col * g.ldb_w;
     }
+    const int bmul = g.b_tiled ? 32 : 1;                // words between consecutive 4-word groups of a row, / 4
 
     v16f acc[MT][NT];
 #pragma unroll
@@ -373,7 +376,7 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
         const int boff = tt * g.tw + (wok ? wo : 0);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            load_words<V>(brow[j] + boff, rb[buf][j]);
+            load_words<V>(brow[j] + boff * bmul, rb[buf][j]);
             if (GUARD) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) rb[buf][j][v] = wok ? rb[buf][j][v] : 0u;

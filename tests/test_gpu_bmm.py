@@ -168,3 +168,20 @@ def test_general_bmm_f32(bnn, orc, shape):
     assert got.dtype == np.float32 and np.array_equal(got, orc.general_bmm_f32(A, B))
     zero = np.zeros(K, np.float32)
     assert np.array_equal(words(bnn.sign_pack_f32(to_dev(A))), orc.pack_f32(A, zero))
+
+
+@pytest.mark.parametrize("shape", [(8, 4096, 4096), (128, 1000, 800), (300, 70, 1234), (1024, 1024, 1024), (2100, 2200, 512)])
+def test_bmm_pretiled_weights(bnn, orc, shape):
+    M, N, K = shape
+    case = wl.bmm_case(96, M, N, K, index0=M % 89)
+    Bt = bnn.tile_b(to_dev(case["B"]), K)
+    assert np.array_equal(words(Bt), orc.tile_b(case["B"]))
+    ref = orc.bmm(case["A"], case["B"], K, tier=1)
+    assert np.array_equal(host(bnn.bmm_tiled(to_dev(case["A"]), Bt, N, K)), ref)
+    bits = words(bnn.bmm_thr_tiled(to_dev(case["A"]), Bt, to_dev(case["tau"]), N, K))
+    assert np.array_equal(bits, orc.threshold_pack(ref, case["tau"], ldb_w=wl.round_up(wl.nwords(N), 4)))
+
+
+def test_probe_load_stride_runs(bnn):
+    t = bnn.probe_load_stride(128, rows=256, iters=512)
+    assert 1.0 < t < 1e5

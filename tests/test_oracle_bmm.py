@@ -202,3 +202,21 @@ def test_bad_arguments(orc):
     A = np.zeros((2, 1), np.uint32)
     with pytest.raises(RuntimeError):
         orc.bmm(A, A, 40)          # K does not fit the leading dimension
+
+
+def test_tile_b_layout_definition(orc):
+    # element-by-element against the index formula, written with explicit loops
+    rng = np.random.default_rng(11)
+    for (N, K) in ((70, 256), (32, 128), (5, 640)):
+        ldw = wl.round_up(wl.nwords(K), 4)
+        B = wl.random_bits(rng, N, K, ldw)
+        T = orc.tile_b(B).reshape(-1)
+        upr = ldw // 4
+        assert T.size == (N + 31) // 32 * 32 * ldw
+        seen = np.zeros(T.size, bool)
+        for r in range(N):
+            for u in range(upr):
+                d = ((r // 32) * upr + u) * 32 + r % 32
+                assert (T[4 * d:4 * d + 4] == B[r, 4 * u:4 * u + 4]).all()
+                seen[4 * d:4 * d + 4] = True
+        assert (T[~seen] == 0).all()
