@@ -276,7 +276,8 @@ def run_extras(bnn, wl, np, torch, to_dev, dev):
     # ---- layout study (Sec. 5.1 / 4.1 redone for this chip): weights pre-tiled in MFMA fragment order against plain
     # rows on the shapes that read operands straight from L2, and the fragment-load latency against the row stride
     lay = {"fc_shapes": [], "fragment_load_ticks_vs_row_stride_bytes": {}}
-    for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096)):
+    for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096), (4096, 4096, 4096),
+                      (8192, 8192, 8192)):
         case = wl.bmm_case(2, M, N, K, index0=900 + M % 7)
         A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
         Bt = bnn.tile_b(B, K)
