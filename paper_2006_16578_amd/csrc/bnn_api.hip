@@ -242,6 +242,7 @@ const char* bnn_bconv_kernel_name(int N, int H, int W, int C, int O, int k, int 
     if (conv_shape(N, H, W, C, O, k, stride, pad, BNN_PAD_MINUS_ONE, &P, &Q) != BNN_OK) return "invalid";
     Geom g = {};
     g.rows = (long long)N * P * Q; g.cols = O; g.conv = 1; g.taps = k * k; g.tw = words(C); g.bits_tap = C;
+    g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad; g.lda_w = g.tw; g.ldb_w = k * k * g.tw;
     return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g);
 }
 

@@ -69,6 +69,16 @@ __device__ __forceinline__ uint32_t write_lane(uint32_t val, int lane, uint32_t 
     return (uint32_t)bnn_llvm_writelane_i32((int)val, lane, (int)old);
 }
 
+// Makes the compiler keep the MFMA accumulators in the accumulation registers (AGPRs).  When a kernel's
+// register budget is 256 or less (two or more waves per SIMD) the compiler otherwise puts them in ordinary
+// VGPRs, and the accumulator reads and writes of every MFMA then compete with the vector ALU for the VGPR
+// ports: the same expansion + MFMA loop runs at 5.4 PFLOP/s with VGPR accumulators and at 6.4 with AGPR ones.
+// An (empty) inline-asm result in an AGPR is what tells the compiler that the function uses AGPRs at all.
+__device__ __forceinline__ void accumulators_in_agprs() {
+    int hint;
+    asm volatile("; accumulators in AGPRs" : "=a"(hint));
+}
+
 // Workgroup shape: WM x WN waves, each owning MT x NT accumulator tiles of 32 x 32; MINB is the
 // number of workgroups per CU the register allocation is sized for.
 template <int MT_, int NT_, int WM_, int WN_, int MINB_>

@@ -36,6 +36,8 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
     constexpr int STAGE = 4 * (RA + RB);                 // units per slab
     constexpr int LA = ROWS / 64, LB = (COLS + 63) / 64; // granules each thread moves per slab
     extern __shared__ uint4 lds[];                       // 2 * STAGE units, sized at launch
+    // BMM on the large tiles: the registers left beside 128 accumulators suffice without spilling
+    if constexpr (!CONV && TL::MINB <= 2) accumulators_in_agprs();
 
     int bx, by;
     if (!tile_coords(gx, gy, bx, by)) return;            // uniform for the workgroup
