@@ -178,6 +178,17 @@ int bnn_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C
  *   y_f32 [N][P][Q][O] fp32 or NULL, bits [N][P][Q][ceil(O/32)] or NULL (not both NULL). */
 int bnn_conv_f32_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
                      int N, int H, int W, int C, int O, int k, int stride, int pad, void* stream);
+/* The same layer on the bf16 matrix cores: every input value and every weight is split exactly into three bf16
+ * terms and all nine term products are accumulated in fp32, so each product x*w is exact and only the fp32
+ * additions round (at least as accurate as an fp32 multiply-add chain; same 1e-4 contract).  Needs
+ *   workspace: device scratch of at least bnn_conv_f32_split_workspace_bytes(C, O, k) bytes, 16-byte aligned
+ *   (it receives the split weights in matrix-core operand order; not needed after the call);
+ * N*P*Q < 2^31; finite inputs.  BNN_ERR_UNSUPPORTED when the split filter bank of 64 output channels does not
+ * fit LDS (k*ceil(k*C/8) above about 50): use bnn_conv_f32_thr then. */
+size_t bnn_conv_f32_split_workspace_bytes(int C, int O, int k);
+int bnn_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
+                           int N, int H, int W, int C, int O, int k, int stride, int pad,
+                           void* workspace, size_t workspace_bytes, void* stream);
 /* First layer with binarized weights only (Sec. 6.1, "BWN"): the input stays real-valued, each weight is one
  * bit that decides whether the input element is added (bit 1) or subtracted (bit 0); zero padding;
  * bits = (y >= thr[o]).  fp32 accumulation (every product is exact), 1e-4 relative like the layer above.

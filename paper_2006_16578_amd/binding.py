@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "conv_f32_split_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -25,7 +25,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
            "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
-           "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
            "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_layer_bits"]
@@ -58,6 +58,7 @@ def load() -> ctypes.CDLL:
         lib.bnn_bmm_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bconv_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bwn_workspace_bytes.restype = ctypes.c_size_t
+        lib.bnn_conv_f32_split_workspace_bytes.restype = ctypes.c_size_t
         lib.bnn_bmm_general_workspace_bytes.restype = ctypes.c_size_t
         lib.bnn_bconv_general_workspace_bytes.restype = ctypes.c_size_t
         for name in EXPORTS:
@@ -352,6 +353,26 @@ def conv_f32_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False):
     with torch.cuda.device(x.device):
         _check(load().bnn_conv_f32_thr(_ptr(x), _ptr(w), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride), int(pad),
                                        _stream(x)), "bnn_conv_f32_thr")
+    return (bits, y) if want_f32 else bits
+
+
+def conv_f32_split_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False, workspace=None):
+    """fp32 first layer on the bf16 matrix cores (inputs and weights split exactly into three bf16 terms each)."""
+    _dev(x, torch.float32, 4, "x"); _dev(w, torch.float32, 4, "w"); _dev(thr, torch.float32, 1, "thr")
+    N, H, W, C = x.shape
+    O, k, _, C2 = w.shape
+    if C != C2:
+        raise ValueError("channel mismatch")
+    P = (H + 2 * pad - k) // stride + 1
+    Q = (W + 2 * pad - k) // stride + 1
+    bits = torch.empty((N, P, Q, nwords(O)), dtype=_BITS, device=x.device)
+    y = torch.empty((N, P, Q, O), dtype=torch.float32, device=x.device) if want_f32 else None
+    if workspace is None:
+        workspace = torch.empty(max(int(load().bnn_conv_f32_split_workspace_bytes(C, O, k)), 16), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().bnn_conv_f32_split_thr(_ptr(x), _ptr(w), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride),
+                                             int(pad), _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(x)),
+               "bnn_conv_f32_split_thr")
     return (bits, y) if want_f32 else bits
 
 

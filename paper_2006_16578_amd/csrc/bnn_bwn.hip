@@ -100,6 +100,42 @@ __global__ __launch_bounds__(256) void bwn_expand_kernel(const uint32_t* __restr
     wexp[u] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
+// Same layout for real-valued weights w [O][k][k][C]: each weight is split exactly into three bf16 terms
+// (as the input values are) and the three terms go to three planes, wexp [col_tiles][3][2 * nsteps][cols] units.
+__global__ __launch_bounds__(256) void conv_f32_expand_kernel(const float* __restrict__ w, uint4* __restrict__ wexp, int C, int O,
+                                                              int k, int cols, int nsteps, int nunits) {
+    const int u = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (u >= nunits) return;
+    const int seg = k * C, rpr = (seg + 7) >> 3, nruns = k * rpr;
+    const int last0 = seg >= 8 ? seg - 8 : 0;
+    const int per_plane = 2 * nsteps * cols;
+    const int tile = u / (3 * per_plane), v3 = u - tile * (3 * per_plane);
+    const int plane = v3 / per_plane, v = v3 - plane * per_plane;
+    const int rho = v / cols, col = v - rho * cols;
+    const int o = tile * cols + col;
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    if (rho < nruns && o < O) {
+        const int r = rho / rpr, j = rho - r * rpr;
+        const int e0 = min(8 * j, last0);
+        const float* wrow = w + ((long long)o * k + r) * seg;        // the k*C weights of filter row r are contiguous
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int e = e0 + s;
+            uint32_t val = 0u;
+            if (e < seg && e >= 8 * j) {
+                const float x0 = wrow[e];
+                const uint32_t a = __float_as_uint(x0);
+                const float r1 = x0 - __uint_as_float(a & 0xffff0000u);
+                const uint32_t b = __float_as_uint(r1);
+                const float r2 = r1 - __uint_as_float(b & 0xffff0000u);
+                val = (plane == 0 ? a : plane == 1 ? b : __float_as_uint(r2)) >> 16;
+            }
+            pk[s >> 1] |= val << (16 * (s & 1));
+        }
+    }
+    wexp[u] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+}
+
 // ------------------------------------------------------------------------------------------ LDS-staged
 struct BwnTile {            // geometry of the LDS-staged kernel, computed on the host
     int H, W, C, Cp, O, stride, pad, P, Q, k;
@@ -332,14 +368,15 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwn_staged_kernel(const
 }
 
 // ------------------------------------------------------------------------------------------ direct
-// MT x NT accumulator tiles of 32x32 per wave, WAVES waves per workgroup (they share the weights in LDS), each wave walks `tiles_per_wave`
-// consecutive groups of MT*32 output pixels; the workgroup covers NT*32 output channels.
-template <int MT, int NT, int WAVES>
+// MT x NT accumulator tiles of 32x32 per wave, WAVES waves per workgroup (they share the weights in LDS); the
+// workgroup covers NT*32 output channels and is persistent: its waves stride over the groups of MT*32 output pixels.
+// NPL: weight planes -- 1: +1/-1 weights (one bf16 value each); 3: real-valued weights split into three bf16 terms,
+// every one of the nine input-term x weight-term products is then formed, so each product is exact here too.
+template <int MT, int NT, int WAVES, int NPL>
 __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
                                                        const float* __restrict__ thr, float* __restrict__ y,
                                                        uint32_t* __restrict__ bits, int N, int H, int W, int C, int O,
-                                                       int k, int stride, int pad, int P, int Q, FastDiv div_pq, FastDiv div_q,
-                                                       int tiles_per_wave) {
+                                                       int k, int stride, int pad, int P, int Q, FastDiv div_pq, FastDiv div_q) {
     constexpr int COLS = NT * 32, NTHR = WAVES * 64;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5, wave = threadIdx.x >> 6;
     const int npix = N * P * Q;
@@ -355,9 +392,9 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     const long long total = (long long)N * H * rowlen;       // floats in x
 
     // ---- expanded weights of this workgroup's channel tile -> LDS
-    extern __shared__ uint4 wlds[];                          // [2 * nsteps][COLS] units of 8 bf16
+    extern __shared__ uint4 wlds[];                          // [NPL][2 * nsteps][COLS] units of 8 bf16
     {
-        const int nunits = 2 * nsteps * COLS;
+        const int nunits = NPL * 2 * nsteps * COLS;
         const uint4* src = wexp + (long long)blockIdx.y * nunits;
         for (int base = 0; base < nunits; base += 4 * NTHR) {
             uint4 tmp[4];
@@ -382,10 +419,10 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     }
     const int ow = (O + 31) / 32;
 
-    for (int tw = 0; tw < tiles_per_wave; ++tw) {
-        const long long m0l = (((long long)blockIdx.x * WAVES + wave) * tiles_per_wave + tw) * (MT * 32);
-        if (m0l >= npix) break;                              // uniform per wave, after the only barrier
-        const int m0 = (int)m0l;
+    // the workgroups stay for the whole kernel (one per CU: the weights are copied once); the waves stride over
+    // the groups of MT*32 output pixels
+    for (long long grp = (long long)blockIdx.x * WAVES + wave; grp * (MT * 32) < npix; grp += (long long)gridDim.x * WAVES) {
+        const int m0 = (int)(grp * (MT * 32));
 
         long long xbase[MT];        // float index of input row 0 of this lane's image
         int xoff[MT], ytop[MT];
@@ -440,9 +477,11 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
         };
 
         auto multiply = [&](int step, Run& q) {
-            uint4 b[NT];
+            uint4 b[NPL][NT];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) b[j] = wlds[(2 * step + half) * COLS + 32 * j + l32];
+            for (int pw = 0; pw < NPL; ++pw)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) b[pw][j] = wlds[(pw * 2 * nsteps + 2 * step + half) * COLS + 32 * j + l32];
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
                 // zero padding; skipped when every lane of the wave has its whole run inside the image
@@ -459,13 +498,19 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
                     for (int t = 0; t < 8; ++t) q.v[i][t] = (t >= lo && t < hi) ? q.v[i][t] : 0.f;
                 }
                 const Split3 s = split3(q.v[i]);
+                const uint4 xs[3] = {s.h, s.m, s.l};
+                // smallest terms first: (input term, weight term) pairs in order of decreasing index sum
 #pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const v8bf_bwn bv = __builtin_bit_cast(v8bf_bwn, b[j]);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.l), bv, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.m), bv, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, s.h), bv, acc[i][j], 0, 0, 0);
-                }
+                for (int sum = 2 + (NPL - 1); sum >= 0; --sum)
+#pragma unroll
+                    for (int px = 2; px >= 0; --px) {
+                        const int pw = sum - px;
+                        if (pw < 0 || pw >= NPL) continue;
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, xs[px]),
+                                                                                 __builtin_bit_cast(v8bf_bwn, b[pw][j]), acc[i][j], 0, 0, 0);
+                    }
             }
         };
 
@@ -534,32 +579,43 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     }
 }
 
-template <int MT, int NT, int WAVES>
-int launch_bwn_direct(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
+template <int MT, int NT, int WAVES, int NPL>
+int launch_bwn_direct(const float* x, const void* weights, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
                       int C, int O, int k, int stride, int pad, int P, int Q, void* workspace, size_t workspace_bytes,
                       hipStream_t s) {
     constexpr int COLS = NT * 32;
     const long long npix = (long long)N * P * Q;
     const int seg = k * C, nruns = k * ((seg + 7) / 8), nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
     const int col_tiles = (int)cdiv(O, COLS);
-    const size_t lds_bytes = (size_t)2 * nsteps * COLS * 16;
+    const size_t lds_bytes = (size_t)NPL * 2 * nsteps * COLS * 16;
     if (lds_bytes > 160 * 1024) return BNN_ERR_UNSUPPORTED;
     if (workspace_bytes < lds_bytes * col_tiles) return BNN_ERR_WORKSPACE;
     if (lds_bytes > 64 * 1024) {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_conv_kernel<MT, NT, WAVES>),
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_conv_kernel<MT, NT, WAVES, NPL>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr != hipSuccess) return BNN_ERR_DEVICE;
     }
     uint4* wexp = static_cast<uint4*>(workspace);
-    const int nunits = col_tiles * 2 * nsteps * COLS;
-    hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, wbits, wexp, C, C, O, k, COLS, 1, nsteps, nunits);
-    // Several pixel groups per wave amortise the weight copy, as long as the grid still fills the chip.
+    const int nunits = col_tiles * NPL * 2 * nsteps * COLS;
+    if (NPL == 1)
+        hipLaunchKernelGGL(bwn_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, static_cast<const uint32_t*>(weights),
+                           wexp, C, C, O, k, COLS, 1, nsteps, nunits);
+    else
+        hipLaunchKernelGGL(conv_f32_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s,
+                           static_cast<const float*>(weights), wexp, C, O, k, COLS, nsteps, nunits);
+    // one workgroup per CU (registers allow no more), resident for the whole call
     const long long groups = cdiv(npix, MT * 32);
-    int tpw = 1;
-    while (tpw < 8 && cdiv(groups, (long long)WAVES * (tpw * 2)) * col_tiles >= 4 * 256) tpw *= 2;
-    dim3 grid((unsigned)cdiv(groups, (long long)WAVES * tpw), (unsigned)col_tiles);
-    hipLaunchKernelGGL((bwn_conv_kernel<MT, NT, WAVES>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, N, H, W, C, O, k, stride,
-                       pad, P, Q, make_fastdiv(P * Q), make_fastdiv(Q), tpw);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus < 1)
+            return BNN_ERR_DEVICE;
+    }
+    const long long wgs = min(cdiv(groups, WAVES), (long long)max(1, cus / col_tiles));
+    dim3 grid((unsigned)wgs, (unsigned)col_tiles);
+    hipLaunchKernelGGL((bwn_conv_kernel<MT, NT, WAVES, NPL>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, N, H, W, C, O, k, stride,
+                       pad, P, Q, make_fastdiv(P * Q), make_fastdiv(Q));
     return check_launch();
 }
 
@@ -651,8 +707,20 @@ int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr,
         return launch_bwn_staged<2, 2, 4>(x, wbits, thr, y, bits, N, C, O, k, g, lds, workspace, workspace_bytes, s);
     if (staged_geom(1, 2, 4, N, H, W, C, O, k, stride, pad, P, Q, &g, &lds) && lds <= SIDE_BY_SIDE)
         return launch_bwn_staged<1, 2, 4>(x, wbits, thr, y, bits, N, C, O, k, g, lds, workspace, workspace_bytes, s);
-    if (O <= 64) return launch_bwn_direct<2, 2, 8>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
-    return launch_bwn_direct<1, 4, 8>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
+    if (O <= 64) return launch_bwn_direct<2, 2, 8, 1>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
+    return launch_bwn_direct<1, 4, 8, 1>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
+}
+
+// Real-valued weights on the same kernel: three weight planes, nine exact products per element pair.
+size_t conv_f32_split_workspace_bytes(int C, int O, int k) {
+    const long long seg = (long long)k * C, nruns = k * ((seg + 7) / 8), nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
+    return (size_t)(cdiv(O, 64) * 64 * 3 * 2 * nsteps * 16);
+}
+
+int launch_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
+                              int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    return launch_bwn_direct<2, 2, 8, 3>(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
 }
 
 }  // namespace bnn

@@ -269,3 +269,44 @@ def test_persistent_bits_input_and_limits(bnn, orc):
     cnn = bnn.Net.from_layers(spec["layers"], spec["in_hw"])
     with pytest.raises(bnn.BnnError):
         cnn.forward_persistent(to_dev(wl.cnn_input("cifar_vgg", 2)))
+
+
+@pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
+                                   (2, 32, 32, 3, 64, 7, 4, 3), (1, 8, 8, 2, 33, 1, 1, 0), (5, 64, 64, 3, 64, 7, 4, 3),
+                                   (2, 33, 31, 3, 130, 3, 1, 1)])
+def test_conv_f32_split_shapes(bnn, orc, shape):
+    # the fp32 first layer on the bf16 matrix cores (three-way exact split of inputs and weights, nine products)
+    N, H, W, C, O, k, st, pad = shape
+    rng = np.random.default_rng(sum(shape) + 3)
+    x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
+    w = rng.normal(0, 0.05, size=(O, k, k, C)).astype(np.float32)
+    thr = rng.normal(0, 0.05, size=O).astype(np.float32)
+    bits, y = bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad, want_f32=True)
+    ref = orc.conv_f32(x, w, st, pad)
+    tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
+    assert host(y).shape == ref.shape
+    assert (np.abs(host(y) - ref) <= tol).all()
+    # far tighter in fact: the products are exact, only the fp32 additions round
+    assert np.abs(host(y) - ref).max() <= 2e-6 * np.abs(w).max() * np.sqrt(k * k * C) * 4
+    assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
+    assert np.array_equal(words(bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad)), words(bits))
+
+
+def test_conv_f32_split_exact_products(bnn, orc):
+    # integer inputs and weights whose products need all 24 + 24 significand bits pairwise: with every term product
+    # formed, sums that stay below 2^24 are exact, so the result equals the oracle's bit for bit
+    rng = np.random.default_rng(6)
+    x = rng.integers(-2000, 2001, size=(2, 12, 13, 3)).astype(np.float32)
+    w = rng.integers(-50, 51, size=(40, 5, 5, 3)).astype(np.float32)
+    zero = to_dev(np.zeros(40, np.float32))
+    _, y = bnn.conv_f32_split_thr(to_dev(x), to_dev(w), zero, 2, 2, want_f32=True)
+    ref = orc.conv_f32(x, w, 2, 2)
+    assert np.abs(ref).max() < 2 ** 24 and np.array_equal(host(y), ref)
+    # one isolated full-precision product: (2^24 - 1) / 2^12 times (2^24 - 3) / 2^20 rounded once, as fp32 does
+    x = np.zeros((1, 9, 9, 3), np.float32)
+    w = np.zeros((3, 3, 3, 3), np.float32)
+    x[0, 4, 4, 1] = 16777215.0 / 4096
+    w[2, 1, 1, 1] = 16777213.0 / 1048576
+    _, y = bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(np.zeros(3, np.float32)), 1, 1, want_f32=True)
+    assert host(y)[0, 4, 4, 2] == np.float32(np.float64(x[0, 4, 4, 1]) * np.float64(w[2, 1, 1, 1]))
+    assert np.array_equal(host(y), orc.conv_f32(x, w, 1, 1))
