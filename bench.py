@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--path", choices=["auto", "valu", "mfma"], default="auto", help="arithmetic path (profiling runs)")
     ap.add_argument("--shapes", default="", help="comma-separated subset of the sweep, e.g. sq8192 (profiling runs)")
     ap.add_argument("--variant", choices=["both", "bits", "int32"], default="both", help="epilogues to run (profiling runs)")
+    ap.add_argument("--only", default="", help="run only these extra sections (comma-separated: bconv, bconv_sweep, general, "
+                                               "layout, mlp, resnet18, table5) and print them; the BMM sweep is skipped (profiling runs)")
+    ap.add_argument("--resnet-batches", default="256,8", help="batch sizes of the ResNet-18 section (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="only run a plain device copy of this many MiB three times (calibrates the HBM byte counters)")
     args = ap.parse_args()
@@ -83,6 +86,11 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "device copy", "bytes_read": n, "bytes_written": n, "launches": 3}))
+        return 0
+
+    rb = tuple(int(t) for t in args.resnet_batches.split(",") if t)
+    if args.only:
+        print(json.dumps({"only": args.only, **run_extras(bnn, wl, np, torch, to_dev, dev, set(args.only.split(",")), rb)}))
         return 0
 
     # ------------------------------------------------------------------ BMM sweep, resident in HBM
@@ -169,7 +177,7 @@ def main() -> int:
 
     extras = {}
     if not args.skip_extras:
-        extras = run_extras(bnn, wl, np, torch, to_dev, dev)
+        extras = run_extras(bnn, wl, np, torch, to_dev, dev, None, rb)
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline(wl, np)
@@ -217,172 +225,183 @@ def _time_graph(torch, fn, iters):
     return _time_gpu(torch, g.replay, iters)
 
 
-def run_extras(bnn, wl, np, torch, to_dev, dev):
+def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 8)):
     out = {}
+
+    def want(section):
+        return only is None or section in only
+
     # ---- single BConv layers (config 4)
-    convs = []
-    for name, case in (("conv_56x56_c128_o128_s1", wl.cfg4a()), ("conv_56x56_c64_o128_s2", wl.cfg4b())):
-        x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
-        N, H, W, C, O, k, st, pad = (case[q] for q in ("N", "H", "W", "C", "O", "k", "stride", "pad"))
-        P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
-        bits = torch.empty((N, P, Q, wl.nwords(O)), dtype=torch.int32, device=dev)
-        y = torch.empty((N, P, Q, O), dtype=torch.int32, device=dev)
-        ops = 2.0 * N * P * Q * O * k * k * C
-        t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, C, st, pad, bnn.PAD_MINUS_ONE, out=bits), 20)
-        t_i = _time_gpu(torch, lambda: bnn.bconv(x, f, C, st, pad, bnn.PAD_MINUS_ONE, out=y), 20)
-        convs.append({"shape": name, "kernel": bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad),
-                      "bits_out_ms": round(t_b, 5), "bits_out_tops": round(ops / t_b / 1e9, 2),
-                      "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
-                      "int32_out_ms": round(t_i, 5), "int32_out_tops": round(ops / t_i / 1e9, 2),
-                      "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1)})
-        del x, f, bits, y
-    out["bconv_shapes"] = convs
+    if want("bconv"):
+        convs = []
+        for name, case in (("conv_56x56_c128_o128_s1", wl.cfg4a()), ("conv_56x56_c64_o128_s2", wl.cfg4b())):
+            x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
+            N, H, W, C, O, k, st, pad = (case[q] for q in ("N", "H", "W", "C", "O", "k", "stride", "pad"))
+            P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+            bits = torch.empty((N, P, Q, wl.nwords(O)), dtype=torch.int32, device=dev)
+            y = torch.empty((N, P, Q, O), dtype=torch.int32, device=dev)
+            ops = 2.0 * N * P * Q * O * k * k * C
+            t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, C, st, pad, bnn.PAD_MINUS_ONE, out=bits), 20)
+            t_i = _time_gpu(torch, lambda: bnn.bconv(x, f, C, st, pad, bnn.PAD_MINUS_ONE, out=y), 20)
+            convs.append({"shape": name, "kernel": bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad),
+                          "bits_out_ms": round(t_b, 5), "bits_out_tops": round(ops / t_b / 1e9, 2),
+                          "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                          "int32_out_ms": round(t_i, 5), "int32_out_tops": round(ops / t_i / 1e9, 2),
+                          "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1)})
+            del x, f, bits, y
+        out["bconv_shapes"] = convs
     # ---- the paper's BConv sweep (Sec. 7.3): batch 16, 64x64 input, 3x3, stride 1, C = O
-    sweep = []
-    for ch in (128, 256, 512, 640, 1024, 2048):
-        case = wl.bconv_case(6, 16, 64, 64, ch, ch, 3, 1, 1, index0=ch % 97)
-        x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
-        bits = torch.empty((16, 64, 64, wl.nwords(ch)), dtype=torch.int32, device=dev)
-        ops = 2.0 * 16 * 64 * 64 * ch * 9 * ch
-        t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, ch, 1, 1, bnn.PAD_MINUS_ONE, out=bits), 10)
-        sweep.append({"C=O": ch, "kernel": bnn.bconv_kernel_name(16, 64, 64, ch, ch, 3, 1, 1), "bits_out_ms": round(t_b, 5),
-                      "bits_out_tops": round(ops / t_b / 1e9, 1),
-                      "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4)})
-        del x, f, bits
-    out["bconv_sweep_batch16_64x64_3x3"] = sweep
+    if want("bconv_sweep"):
+        sweep = []
+        for ch in (128, 256, 512, 640, 1024, 2048):
+            case = wl.bconv_case(6, 16, 64, 64, ch, ch, 3, 1, 1, index0=ch % 97)
+            x, f, tau = to_dev(case["x"]), to_dev(case["filt"]), to_dev(case["tau"])
+            bits = torch.empty((16, 64, 64, wl.nwords(ch)), dtype=torch.int32, device=dev)
+            ops = 2.0 * 16 * 64 * 64 * ch * 9 * ch
+            t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, ch, 1, 1, bnn.PAD_MINUS_ONE, out=bits), 10)
+            sweep.append({"C=O": ch, "kernel": bnn.bconv_kernel_name(16, 64, 64, ch, ch, 3, 1, 1), "bits_out_ms": round(t_b, 5),
+                          "bits_out_tops": round(ops / t_b / 1e9, 1),
+                          "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4)})
+            del x, f, bits
+        out["bconv_sweep_batch16_64x64_3x3"] = sweep
     # ---- "general" forms (Sec. 7.2 / 7.3): real-valued operands binarized on the way in, fp32 result
-    gen = []
-    for n in (2048, 4096, 8192):
-        A = torch.randn((n, n), dtype=torch.float32, device=dev)
-        B = torch.randn((n, n), dtype=torch.float32, device=dev)
-        C = torch.empty((n, n), dtype=torch.float32, device=dev)
-        ws = torch.empty(2 * n * n // 8 + 1024, dtype=torch.uint8, device=dev)
-        t = _time_gpu(torch, lambda: bnn.bmm_general_f32(A, B, out=C, workspace=ws), 10)
-        tp = _time_gpu(torch, lambda: bnn.sign_pack_f32(A), 10)
-        gen.append({"shape": "bmm_sq%d" % n, "ms": round(t, 5), "tops": round(2.0 * n ** 3 / t / 1e9, 1),
-                    "binarize_one_operand_ms": round(tp, 5),
-                    "hbm_gbs": round((3 * n * n * 4 + 4 * n * n / 8) / t / 1e6, 1)})
-        del A, B, C, ws
-    for ch in (128, 512):
-        x = torch.randn((16, 64, 64, ch), dtype=torch.float32, device=dev)
-        f = torch.randn((ch, 3, 3, ch), dtype=torch.float32, device=dev)
-        o = torch.empty((16, 64, 64, ch), dtype=torch.float32, device=dev)
-        ws = torch.empty((x.numel() + f.numel()) // 8 + 1024, dtype=torch.uint8, device=dev)
-        t = _time_gpu(torch, lambda: bnn.bconv_general_f32(x, f, 1, 1, out=o, workspace=ws), 10)
-        gen.append({"shape": "bconv_batch16_64x64_3x3_c%d" % ch, "ms": round(t, 5),
-                    "tops": round(2.0 * 16 * 64 * 64 * ch * 9 * ch / t / 1e9, 1)})
-        del x, f, o, ws
-    out["general_f32_in_f32_out"] = gen
+    if want("general"):
+        gen = []
+        for n in (2048, 4096, 8192):
+            A = torch.randn((n, n), dtype=torch.float32, device=dev)
+            B = torch.randn((n, n), dtype=torch.float32, device=dev)
+            C = torch.empty((n, n), dtype=torch.float32, device=dev)
+            ws = torch.empty(2 * n * n // 8 + 1024, dtype=torch.uint8, device=dev)
+            t = _time_gpu(torch, lambda: bnn.bmm_general_f32(A, B, out=C, workspace=ws), 10)
+            tp = _time_gpu(torch, lambda: bnn.sign_pack_f32(A), 10)
+            gen.append({"shape": "bmm_sq%d" % n, "ms": round(t, 5), "tops": round(2.0 * n ** 3 / t / 1e9, 1),
+                        "binarize_one_operand_ms": round(tp, 5),
+                        "hbm_gbs": round((3 * n * n * 4 + 4 * n * n / 8) / t / 1e6, 1)})
+            del A, B, C, ws
+        for ch in (128, 512):
+            x = torch.randn((16, 64, 64, ch), dtype=torch.float32, device=dev)
+            f = torch.randn((ch, 3, 3, ch), dtype=torch.float32, device=dev)
+            o = torch.empty((16, 64, 64, ch), dtype=torch.float32, device=dev)
+            ws = torch.empty((x.numel() + f.numel()) // 8 + 1024, dtype=torch.uint8, device=dev)
+            t = _time_gpu(torch, lambda: bnn.bconv_general_f32(x, f, 1, 1, out=o, workspace=ws), 10)
+            gen.append({"shape": "bconv_batch16_64x64_3x3_c%d" % ch, "ms": round(t, 5),
+                        "tops": round(2.0 * 16 * 64 * 64 * ch * 9 * ch / t / 1e9, 1)})
+            del x, f, o, ws
+        out["general_f32_in_f32_out"] = gen
     # ---- layout study (Sec. 5.1 / 4.1 redone for this chip): weights pre-tiled in MFMA fragment order against plain
-    # rows on the shapes that read operands straight from L2, and the fragment-load latency against the row stride
-    lay = {"fc_shapes": [], "fragment_load_ticks_vs_row_stride_bytes": {}}
-    for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096), (4096, 4096, 4096),
-                      (8192, 8192, 8192)):
-        case = wl.bmm_case(2, M, N, K, index0=900 + M % 7)
-        A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
-        Bt = bnn.tile_b(B, K)
-        o = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
-        t_rows = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o), 30)
-        t_tile = _time_gpu(torch, lambda: bnn.bmm_thr_tiled(A, Bt, tau, N, K, out=o), 30)
-        t_rows_direct = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o, path=bnn.PATH_MFMA), 30)
-        lay["fc_shapes"].append({"M": M, "N": N, "K": K, "rows_kernel": bnn.bmm_kernel_name(M, N, K),
-                                 "rows_ms": round(t_rows, 5), "pretiled_direct_ms": round(t_tile, 5),
-                                 "rows_tops": round(2.0 * M * N * K / t_rows / 1e9, 1),
-                                 "pretiled_tops": round(2.0 * M * N * K / t_tile / 1e9, 1)})
-        del A, B, Bt, o
-    for stride in (32, 48, 64, 96, 128, 256, 512, 1024, 2048, 2064, 4096):
-        lay["fragment_load_ticks_vs_row_stride_bytes"][str(stride)] = {
-            "dependent": round(bnn.probe_load_stride(stride, iters=8192, dependent=True), 1),
-            "eight_in_flight": round(bnn.probe_load_stride(stride, iters=8192, dependent=False), 1),
-            "dependent_16KiB_footprint": round(bnn.probe_load_stride(stride, iters=8192, dependent=True, footprint_bytes=16384), 1)}
-    out["layout_study"] = lay
+    if want("layout"):
+        # rows on the shapes that read operands straight from L2, and the fragment-load latency against the row stride
+        lay = {"fc_shapes": [], "fragment_load_ticks_vs_row_stride_bytes": {}}
+        for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096), (4096, 4096, 4096),
+                          (8192, 8192, 8192)):
+            case = wl.bmm_case(2, M, N, K, index0=900 + M % 7)
+            A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+            Bt = bnn.tile_b(B, K)
+            o = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
+            t_rows = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o), 30)
+            t_tile = _time_gpu(torch, lambda: bnn.bmm_thr_tiled(A, Bt, tau, N, K, out=o), 30)
+            t_rows_direct = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o, path=bnn.PATH_MFMA), 30)
+            lay["fc_shapes"].append({"M": M, "N": N, "K": K, "rows_kernel": bnn.bmm_kernel_name(M, N, K),
+                                     "rows_ms": round(t_rows, 5), "pretiled_direct_ms": round(t_tile, 5),
+                                     "rows_tops": round(2.0 * M * N * K / t_rows / 1e9, 1),
+                                     "pretiled_tops": round(2.0 * M * N * K / t_tile / 1e9, 1)})
+            del A, B, Bt, o
+        for stride in (32, 48, 64, 96, 128, 256, 512, 1024, 2048, 2064, 4096):
+            lay["fragment_load_ticks_vs_row_stride_bytes"][str(stride)] = {
+                "dependent": round(bnn.probe_load_stride(stride, iters=8192, dependent=True), 1),
+                "eight_in_flight": round(bnn.probe_load_stride(stride, iters=8192, dependent=False), 1),
+                "dependent_16KiB_footprint": round(bnn.probe_load_stride(stride, iters=8192, dependent=True, footprint_bytes=16384), 1)}
+        out["layout_study"] = lay
     # ---- binarized MLP (config 3)
-    params = wl.mlp_params()
-    net = bnn.Net()
-    net.input_u8(784, 127)
-    for l in range(4):
-        net.add_fc(to_dev(params["W"][l]), to_dev(params["thr"][l]) if l < 3 else None, params["K"][l])
-    mlp = {}
-    for batch in (32768, 1024, 8):
-        imgs = to_dev(wl.mlp_images(batch))
-        o = torch.empty((batch, 10), dtype=torch.int32, device=dev)
-        t = _time_gpu(torch, lambda: net.forward(imgs, out=o), 50)
-        # one cooperative launch for the whole network (Sec. 6.2), with and without its device-wide barriers
-        # (without: results undefined, timing only -- the way the paper's Table 10 prices synchronisation)
-        tp = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o), 50)
-        tn = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o, no_sync=True), 50)
-        net.forward(imgs, out=o)
-        mlp["batch%d" % batch] = {"ms": round(min(t, tp), 5), "images_per_s": round(batch / min(t, tp) * 1e3, 1),
-                                  "per_layer_launches_ms": round(t, 5), "persistent_kernel_ms": round(tp, 5),
-                                  "persistent_without_barriers_ms": round(tn, 5),
-                                  "barrier_share_of_persistent": round(max(tp - tn, 0.0) / tp, 3)}
-        if batch == 8:
-            tg = _time_graph(torch, lambda: net.forward(imgs, out=o), 50)
-            mlp["batch8"]["hip_graph_replay_ms"] = round(tg, 5)
-        del imgs, o
-    mlp["paper_rtx2080_btc_fmt_context_only"] = {"latency8_ms": 0.055, "images_per_s_batch1024": 5.48e6,
-                                                 "images_per_s_batch32k": 7.62e6, "sync_share": 0.0826}
-    out["mlp_784_1024x3_10"] = mlp
+    if want("mlp"):
+        params = wl.mlp_params()
+        net = bnn.Net()
+        net.input_u8(784, 127)
+        for l in range(4):
+            net.add_fc(to_dev(params["W"][l]), to_dev(params["thr"][l]) if l < 3 else None, params["K"][l])
+        mlp = {}
+        for batch in (32768, 1024, 8):
+            imgs = to_dev(wl.mlp_images(batch))
+            o = torch.empty((batch, 10), dtype=torch.int32, device=dev)
+            t = _time_gpu(torch, lambda: net.forward(imgs, out=o), 50)
+            # one cooperative launch for the whole network (Sec. 6.2), with and without its device-wide barriers
+            # (without: results undefined, timing only -- the way the paper's Table 10 prices synchronisation)
+            tp = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o), 50)
+            tn = _time_gpu(torch, lambda: net.forward_persistent(imgs, out=o, no_sync=True), 50)
+            net.forward(imgs, out=o)
+            mlp["batch%d" % batch] = {"ms": round(min(t, tp), 5), "images_per_s": round(batch / min(t, tp) * 1e3, 1),
+                                      "per_layer_launches_ms": round(t, 5), "persistent_kernel_ms": round(tp, 5),
+                                      "persistent_without_barriers_ms": round(tn, 5),
+                                      "barrier_share_of_persistent": round(max(tp - tn, 0.0) / tp, 3)}
+            if batch == 8:
+                tg = _time_graph(torch, lambda: net.forward(imgs, out=o), 50)
+                mlp["batch8"]["hip_graph_replay_ms"] = round(tg, 5)
+            del imgs, o
+        mlp["paper_rtx2080_btc_fmt_context_only"] = {"latency8_ms": 0.055, "images_per_s_batch1024": 5.48e6,
+                                                     "images_per_s_batch32k": 7.62e6, "sync_share": 0.0826}
+        out["mlp_784_1024x3_10"] = mlp
     # ---- ResNet-18-shaped forward (config 5), batch 256
-    p = wl.resnet18_params()
-    rnet = bnn.Net()
-    rnet.input_conv_f32(to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 224, 224, 4, 3)
-    for blk in p["blocks"]:
-        rnet.add_block(to_dev(blk["W1"]), to_dev(blk["thr1"]), to_dev(blk["W2"]), to_dev(blk["thr2"]),
-                       to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"])
-    rnet.add_head_f32(to_dev(p["fc_w"]))
-    res = {}
-    for batch in (256, 8):
-        x = to_dev(wl.resnet18_input(batch))
-        o = torch.empty((batch, 1000), dtype=torch.float32, device=dev)
-        t = _time_gpu(torch, lambda: rnet.forward(x, out=o), 10 if batch == 256 else 30)
-        res["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
-        if batch == 8:
-            tg = _time_graph(torch, lambda: rnet.forward(x, out=o), 30)
-            res["batch8"]["hip_graph_replay_ms"] = round(tg, 4)
-        if batch == 256:
-            xs, w, th = x, to_dev(p["stem_w"]), to_dev(p["stem_thr"])
-            ts = _time_gpu(torch, lambda: bnn.conv_f32_split_thr(xs, w, th, 4, 3), 5)
-            tsf = _time_gpu(torch, lambda: bnn.conv_f32_thr(xs, w, th, 4, 3), 5)
-            res["batch256"]["stem_fp32_ms"] = round(ts, 4)                    # as the forward runs it: bf16 x 3 split, nine exact products
-            res["batch256"]["stem_on_fp32_mfma_ms"] = round(tsf, 4)           # the same layer on the fp32 matrix cores
-            res["batch256"]["binarized_layers_tops"] = round(2 * 1.70e9 * batch / max(t - ts, 1e-6) / 1e9, 1)
-        del x
-    res["paper_rtx2080_images_per_s_context_only"] = PAPER_RESNET18_IMG_S
-    out["resnet18_224"] = res
-    del rnet
+    if want("resnet18"):
+        p = wl.resnet18_params()
+        rnet = bnn.Net()
+        rnet.input_conv_f32(to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 224, 224, 4, 3)
+        for blk in p["blocks"]:
+            rnet.add_block(to_dev(blk["W1"]), to_dev(blk["thr1"]), to_dev(blk["W2"]), to_dev(blk["thr2"]),
+                           to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"])
+        rnet.add_head_f32(to_dev(p["fc_w"]))
+        res = {}
+        for batch in resnet_batches:
+            x = to_dev(wl.resnet18_input(batch))
+            o = torch.empty((batch, 1000), dtype=torch.float32, device=dev)
+            t = _time_gpu(torch, lambda: rnet.forward(x, out=o), 10 if batch == 256 else 30)
+            res["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+            if batch == 8:
+                tg = _time_graph(torch, lambda: rnet.forward(x, out=o), 30)
+                res["batch8"]["hip_graph_replay_ms"] = round(tg, 4)
+            if batch == 256:
+                xs, w, th = x, to_dev(p["stem_w"]), to_dev(p["stem_thr"])
+                ts = _time_gpu(torch, lambda: bnn.conv_f32_split_thr(xs, w, th, 4, 3), 5)
+                tsf = _time_gpu(torch, lambda: bnn.conv_f32_thr(xs, w, th, 4, 3), 5)
+                res["batch256"]["stem_fp32_ms"] = round(ts, 4)                    # as the forward runs it: bf16 x 3 split, nine exact products
+                res["batch256"]["stem_on_fp32_mfma_ms"] = round(tsf, 4)           # the same layer on the fp32 matrix cores
+                res["batch256"]["binarized_layers_tops"] = round(2 * 1.70e9 * batch / max(t - ts, 1e-6) / 1e9, 1)
+            del x
+        res["paper_rtx2080_images_per_s_context_only"] = PAPER_RESNET18_IMG_S
+        out["resnet18_224"] = res
+        del rnet
     # ---- the other network shapes of the paper's Table 5: 8-image latency and throughput at the paper's batch sizes
-    t5 = {}
-    for name, big in (("cifar_vgg", 1024), ("cifar_resnet14", 1024), ("alexnet", 512), ("vgg16", 512)):
-        spec = wl.cnn_layers(name)
-        net5 = bnn.Net.from_layers(spec["layers"], spec["in_hw"], device=dev)
-        r = {}
-        for batch in (big, 8):
-            x = to_dev(wl.cnn_input(name, batch))
-            o = torch.empty((batch, spec["classes"]), dtype=torch.int32, device=dev)
-            t = _time_gpu(torch, lambda: net5.forward(x, out=o), 5 if batch == big else 20)
-            r["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
-            if batch == big:
-                # the first layer alone: binarized weights on the bf16 matrix cores (what the network uses, Sec. 6.1),
-                # and the same shape with real-valued weights on the fp32 matrix cores
-                L0 = spec["layers"][0]
-                wb, t0 = to_dev(L0["W"]), to_dev(L0["thr"])
-                O0, k0 = L0["W"].shape[0], L0["W"].shape[1]
-                wf = torch.randn((O0, k0, k0, L0["C"]), dtype=torch.float32, device=dev) * 0.05
-                tb = _time_gpu(torch, lambda: bnn.bwn_conv_thr(x, wb, t0, L0["C"], L0["stride"], L0["pad"]), 5)
-                tf = _time_gpu(torch, lambda: bnn.conv_f32_thr(x, wf, t0, L0["stride"], L0["pad"]), 3)
-                hw0 = (spec["in_hw"] + 2 * L0["pad"] - k0) // L0["stride"] + 1
-                flop = 2.0 * batch * hw0 * hw0 * O0 * k0 * k0 * L0["C"]
-                r["batch%d" % batch]["first_layer_bwn_ms"] = round(tb, 4)
-                r["batch%d" % batch]["first_layer_bwn_tflops"] = round(flop / tb / 1e9, 1)
-                r["batch%d" % batch]["first_layer_bwn_hbm_gbs"] = round(
-                    (x.numel() * 4 + batch * hw0 * hw0 * O0 / 8) / tb / 1e6, 1)
-                r["batch%d" % batch]["same_shape_fp32_weights_ms"] = round(tf, 4)
-            del x, o
-        r["paper_rtx2080_btc_fmt_context_only"] = PAPER_TABLE6_RTX2080[name]
-        t5[name] = r
-        del net5
-    out["table5_networks"] = t5
+    if want("table5"):
+        t5 = {}
+        for name, big in (("cifar_vgg", 1024), ("cifar_resnet14", 1024), ("alexnet", 512), ("vgg16", 512)):
+            spec = wl.cnn_layers(name)
+            net5 = bnn.Net.from_layers(spec["layers"], spec["in_hw"], device=dev)
+            r = {}
+            for batch in (big, 8):
+                x = to_dev(wl.cnn_input(name, batch))
+                o = torch.empty((batch, spec["classes"]), dtype=torch.int32, device=dev)
+                t = _time_gpu(torch, lambda: net5.forward(x, out=o), 5 if batch == big else 20)
+                r["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+                if batch == big:
+                    # the first layer alone: binarized weights on the bf16 matrix cores (what the network uses, Sec. 6.1),
+                    # and the same shape with real-valued weights on the fp32 matrix cores
+                    L0 = spec["layers"][0]
+                    wb, t0 = to_dev(L0["W"]), to_dev(L0["thr"])
+                    O0, k0 = L0["W"].shape[0], L0["W"].shape[1]
+                    wf = torch.randn((O0, k0, k0, L0["C"]), dtype=torch.float32, device=dev) * 0.05
+                    tb = _time_gpu(torch, lambda: bnn.bwn_conv_thr(x, wb, t0, L0["C"], L0["stride"], L0["pad"]), 5)
+                    tf = _time_gpu(torch, lambda: bnn.conv_f32_thr(x, wf, t0, L0["stride"], L0["pad"]), 3)
+                    hw0 = (spec["in_hw"] + 2 * L0["pad"] - k0) // L0["stride"] + 1
+                    flop = 2.0 * batch * hw0 * hw0 * O0 * k0 * k0 * L0["C"]
+                    r["batch%d" % batch]["first_layer_bwn_ms"] = round(tb, 4)
+                    r["batch%d" % batch]["first_layer_bwn_tflops"] = round(flop / tb / 1e9, 1)
+                    r["batch%d" % batch]["first_layer_bwn_hbm_gbs"] = round(
+                        (x.numel() * 4 + batch * hw0 * hw0 * O0 / 8) / tb / 1e6, 1)
+                    r["batch%d" % batch]["same_shape_fp32_weights_ms"] = round(tf, 4)
+                del x, o
+            r["paper_rtx2080_btc_fmt_context_only"] = PAPER_TABLE6_RTX2080[name]
+            t5[name] = r
+            del net5
+        out["table5_networks"] = t5
     return out
 
 

@@ -323,38 +323,60 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(const float* __restrict__
     }
 }
 
-// Head: exact integer sum-pool of +1/-1 over HW positions, then fp32 FC.  A workgroup handles
-// HEAD_IMGS images and HEAD_OUTS output rows.  Pooling: a thread owns one packed word (32
-// channels) of one image and counts set bits per channel over the HW positions, 4 channels at a
-// time in the bytes of one register (HW <= 255); the sum of +1/-1 is 2 * count - HW.  FC: a wave
-// per output row, lanes stride over channels, butterfly reduction.
-constexpr int HEAD_IMGS = 4;
-constexpr int HEAD_OUTS = 32;
+// Head: exact integer sum-pool of +1/-1 over HW positions, then fp32 FC.  A workgroup handles HEAD_IMGS images
+// and HEAD_OUTS output rows.  Pooling: a thread owns one packed word (32 channels) of one image and counts set
+// bits per channel over the HW positions, 4 channels at a time in the bytes of one register (HW <= 255); the sum
+// of +1/-1 is 2 * count - HW.  FC: the pooled values and the weight rows of the workgroup are staged in LDS,
+// channel-major ([c][image] and [c][output], rows padded by one float against bank conflicts), and thread
+// (image, output) walks the channels: no cross-lane reduction.
+constexpr int HEAD_IMGS = 16;
+constexpr int HEAD_OUTS = 16;
 constexpr int HEAD_MAXC = 1024;
+constexpr int HEAD_LD = 17;                              // floats per channel row in LDS (16 + 1 pad)
 
 __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ bits, const float* __restrict__ w,
                                                    float* __restrict__ y, int32_t* __restrict__ pooled_out,
                                                    int N, int HW, int C, int J) {
-    __shared__ float pooled[HEAD_IMGS][HEAD_MAXC];
+    extern __shared__ float head_lds[];
+    float* pooled = head_lds;                            // [C][HEAD_LD]: pooled[c][image]
+    float* wt = head_lds + (size_t)C * HEAD_LD;          // [C][HEAD_LD]: wt[c][output]
     const int n0 = blockIdx.x * HEAD_IMGS;
     const int j0 = blockIdx.y * HEAD_OUTS;
     const int cw = (C + 31) / 32;
     const float inv = (float)HW;
+    // weight rows of this workgroup, transposed into LDS (coalesced reads along c), eight loads in flight per thread
+    {
+        const int total = HEAD_OUTS * C;
+        for (int base = 0; base < total; base += 8 * 256) {
+            float tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                const int jj = idx / C, c = idx - jj * C;
+                tmp[u] = (idx < total && j0 + jj < J) ? w[(long long)(j0 + jj) * C + c] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                const int jj = idx / C, c = idx - jj * C;
+                if (idx < total) wt[c * HEAD_LD + jj] = tmp[u];
+            }
+        }
+    }
     for (int idx = threadIdx.x; idx < HEAD_IMGS * cw; idx += blockDim.x) {
         const int im = idx / cw, wi = idx - im * cw;
         const int n = n0 + im;
-        uint32_t cnt[8];                       // cnt[q] byte b = number of set bits of channel 4*q... see below
+        uint32_t cnt[8];                       // byte t of cnt[q] = number of set bits of channel q + 8*t of this word
 #pragma unroll
         for (int q = 0; q < 8; ++q) cnt[q] = 0u;
         if (n < N) {
             const uint32_t* b = bits + (long long)n * HW * cw + wi;
-            for (int i0 = 0; i0 < HW; i0 += 8) {            // 8 independent loads in flight
-                uint32_t v[8];
+            for (int i0 = 0; i0 < HW; i0 += 16) {           // 16 independent loads in flight
+                uint32_t v[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = (i0 + u < HW) ? b[(long long)(i0 + u) * cw] : 0u;
-                // bit (q + 8*t) of a word is added to byte t of cnt[q]
+                for (int u = 0; u < 16; ++u) v[u] = (i0 + u < HW) ? b[(long long)(i0 + u) * cw] : 0u;
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < 16; ++u)
 #pragma unroll
                     for (int q = 0; q < 8; ++q) cnt[q] += (v[u] >> q) & 0x01010101u;
             }
@@ -367,34 +389,23 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
                 if (c < C) {
                     const int s = (n < N) ? 2 * (int)((cnt[q] >> (8 * t)) & 0xFFu) - HW : 0;
                     if (pooled_out != nullptr && blockIdx.y == 0 && n < N) pooled_out[(long long)n * C + c] = s;
-                    pooled[im][c] = (float)s / inv;
+                    pooled[c * HEAD_LD + im] = (float)s / inv;
                 }
             }
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int j = j0 + wave; j < min(j0 + HEAD_OUTS, J); j += 4) {
-        float part[HEAD_IMGS];
-#pragma unroll
-        for (int im = 0; im < HEAD_IMGS; ++im) part[im] = 0.f;
-        float wv[HEAD_MAXC / 64];                       // the whole weight row in flight at once
-#pragma unroll
-        for (int u = 0; u < HEAD_MAXC / 64; ++u) wv[u] = (lane + 64 * u < C) ? w[(long long)j * C + lane + 64 * u] : 0.f;
-#pragma unroll
-        for (int u = 0; u < HEAD_MAXC / 64; ++u) {
-            if (64 * u < C) {
-                const int c = min(lane + 64 * u, C - 1);
-#pragma unroll
-                for (int im = 0; im < HEAD_IMGS; ++im) part[im] = fmaf(pooled[im][c], wv[u], part[im]);
-            }
-        }
-#pragma unroll
-        for (int im = 0; im < HEAD_IMGS; ++im) {
-            float v = part[im];
-            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-            if (lane == 0 && n0 + im < N) y[(long long)(n0 + im) * J + j] = v;
-        }
+    // thread -> (image, output); four independent partial sums shorten the dependent chain
+    const int im = threadIdx.x & (HEAD_IMGS - 1), jj = threadIdx.x / HEAD_IMGS;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+    int c = 0;
+    for (; c + 4 <= C; c += 4) {
+        p0 = fmaf(pooled[(c + 0) * HEAD_LD + im], wt[(c + 0) * HEAD_LD + jj], p0);
+        p1 = fmaf(pooled[(c + 1) * HEAD_LD + im], wt[(c + 1) * HEAD_LD + jj], p1);
+        p2 = fmaf(pooled[(c + 2) * HEAD_LD + im], wt[(c + 2) * HEAD_LD + jj], p2);
+        p3 = fmaf(pooled[(c + 3) * HEAD_LD + im], wt[(c + 3) * HEAD_LD + jj], p3);
     }
+    for (; c < C; ++c) p0 = fmaf(pooled[c * HEAD_LD + im], wt[c * HEAD_LD + jj], p0);
+    if (n0 + im < N && j0 + jj < J) y[(long long)(n0 + im) * J + j0 + jj] = (p0 + p1) + (p2 + p3);
 }
 
 }  // namespace
@@ -473,8 +484,14 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
 int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,
                     hipStream_t s) {
     if (C > HEAD_MAXC || HW > 255) return BNN_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)cdiv(N, HEAD_IMGS), (unsigned)cdiv(J, HEAD_OUTS)), dim3(256), 0, s, bits, w, y,
-                       pooled, N, HW, C, J);
+    const size_t lds_bytes = (size_t)2 * C * HEAD_LD * sizeof(float);
+    if (lds_bytes > 64 * 1024) {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&head_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)cdiv(N, HEAD_IMGS), (unsigned)cdiv(J, HEAD_OUTS)), dim3(256), lds_bytes, s, bits,
+                       w, y, pooled, N, HW, C, J);
     return check_launch();
 }
 
