@@ -464,14 +464,17 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
 // CUs (two workgroups each for the big tiles) enough workgroups -- unless the epilogue moves full
-// precision sums (residual in, sum out) and K is short: then the call is bound by that traffic
-// (about 2.5 P MAC/s against 4.5 TB/s: K < ~500 bits per byte moved per output), and the small tile,
-// with four times the resident workgroups, overlaps it with the matrix work of other workgroups.
+// precision sums and K is short.  By bandwidth alone the traffic binds below about 500 bits of K per byte
+// moved per output (2.5 P MAC/s against 4.5 TB/s), but the epilogue's loads and stores cost more than their
+// bytes, because a wave waits for them after its last MFMA: measured on the residual layers of the ResNet
+// shapes (same-run comparison of thresholds) it pays to switch up to about 2500 bits per byte read and 1200
+// per byte written.  The small tile, with four times the resident workgroups, overlaps those waits with
+// the matrix work of others.
 inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
     if (e != nullptr) {
-        const int bytes = 4 * (e->resid != nullptr) + 4 * (e->out != nullptr) + 2 * (e->resid16 != nullptr) +
-                          2 * (e->out16 != nullptr);
-        if (bytes > 0 && (long long)g.taps * g.bits_tap < 500LL * bytes &&
+        const int bytes_in = 4 * (e->resid != nullptr) + 2 * (e->resid16 != nullptr);
+        const int bytes_out = 4 * (e->out != nullptr) + 2 * (e->out16 != nullptr);
+        if (bytes_in + bytes_out > 0 && (long long)g.taps * g.bits_tap < 2500LL * bytes_in + 1200LL * bytes_out &&
             cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
             return 3;
     }
