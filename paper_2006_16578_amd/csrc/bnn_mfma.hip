@@ -13,8 +13,7 @@ bool staged_ok(const Geom& g, int tile) {
     if (tile == 3) return false;
     if (!g.conv) return true;
     if (tile == 1 && g.tw == 2) return false;    // 512 loader rows of 8-byte pixels: too many registers
-    // short K (few slabs): the direct kernel has less fixed cost per workgroup
-    return !g.excl && g.bits_tap == g.tw * 32 && (g.tw % 4 == 0 || g.tw == 2) && g.taps * g.tw >= 64;
+    return mfma::conv_stages_through_lds(g);
 }
 
 }  // namespace

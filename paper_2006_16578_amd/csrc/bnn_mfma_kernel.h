@@ -462,6 +462,13 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
     return check_launch();
 }
 
+// Convolutions that the LDS-staged kernel takes (on any tile but the smallest): -1 padding, whole-word pixels of
+// 8 bytes or a multiple of 16 bytes, and K of at least 2048 bits (with fewer slabs the direct kernel has less fixed
+// cost per workgroup).
+inline bool conv_stages_through_lds(const Geom& g) {
+    return g.conv && !g.excl && g.bits_tap == g.tw * 32 && (g.tw % 4 == 0 || g.tw == 2) && g.taps * g.tw >= 64;
+}
+
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
 // CUs (two workgroups each for the big tiles) enough workgroups -- unless the epilogue moves full
 // precision sums and K is short.  By bandwidth alone the traffic binds below about 500 bits of K per byte
@@ -479,7 +486,10 @@ inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
             return 3;
     }
     if (g.cols <= 64) return (cdiv(g.rows, TileTall::ROWS) >= 256) ? 1 : 3;
-    if (cdiv(g.rows, TileBig::ROWS) * cdiv(g.cols, TileBig::COLS) >= 384) return 0;
+    // the LDS-staged convolution kernel does better on the 128x128 tile until the 256x128 one has about four
+    // workgroups per CU slot (measured on the 14x14x256 ResNet layer and the 64x64 sweep); the others from 1.5
+    const long long big_min = conv_stages_through_lds(g) ? 2048 : 384;
+    if (cdiv(g.rows, TileBig::ROWS) * cdiv(g.cols, TileBig::COLS) >= big_min) return 0;
     if (cdiv(g.rows, TileMid::ROWS) * cdiv(g.cols, TileMid::COLS) >= 256) return 2;
     return 3;
 }
