@@ -31,7 +31,7 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
-TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_lds_wg256x128": 7.162e8}
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_lds_wg256x128": 7.154e+08}
 
 
 # Table 6 of the paper, BTC-FMT row (RTX 2080; trained weights, real data): context only
@@ -106,7 +106,8 @@ def main() -> int:
         Cb = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
         C = torch.empty((M, N), dtype=torch.int32, device=dev)
         shapes.append({"name": name, "M": M, "N": N, "K": K, "A": A, "B": B, "tau": tau, "Cb": Cb, "C": C,
-                       "kernel": bnn.bmm_kernel_name(M, N, K, path), "t_thr": [], "t_i32": []})
+                       "kernel": bnn.bmm_kernel_name(M, N, K, path),
+                       "kernel_i32": bnn.bmm_kernel_name(M, N, K, path, int32_out=True)})
     macs_step = sum((do_bits + do_i32) * float(s["M"]) * s["N"] * s["K"] for s in shapes)
 
     def one_step(record: bool):
@@ -149,6 +150,7 @@ def main() -> int:
                           "bits_out_ms": round(thr_ms, 5), "bits_out_tops": round(ops / thr_ms / 1e9, 2),
                           "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
                           "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
+                          "int32_out_kernel": s["kernel_i32"],
                           "int32_out_ms": round(i32_ms, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
                           "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1)})
 
@@ -156,10 +158,15 @@ def main() -> int:
     # takes the most time in a step
     by_kernel = {}
     for s, ps in zip(shapes, per_shape):
-        d = by_kernel.setdefault(s["kernel"], {"ms": 0.0, "flop": 0.0, "launches": 0})
-        d["ms"] += do_bits * ps["bits_out_ms"] + do_i32 * ps["int32_out_ms"]
-        d["flop"] += (do_bits + do_i32) * 2.0 * s["M"] * s["N"] * s["K"]
-        d["launches"] += do_bits + do_i32
+        kw = (s["M"] + s["N"]) * wl.nwords(s["K"]) * 4
+        for on, kern, ms, out_bytes in ((do_bits, s["kernel"], ps["bits_out_ms"], s["M"] * wl.nwords(s["N"]) * 4),
+                                        (do_i32, s["kernel_i32"], ps["int32_out_ms"], 4 * s["M"] * s["N"])):
+            if on:
+                d = by_kernel.setdefault(kern, {"ms": 0.0, "flop": 0.0, "launches": 0, "bytes": 0})
+                d["ms"] += ms
+                d["flop"] += 2.0 * s["M"] * s["N"] * s["K"]
+                d["launches"] += 1
+                d["bytes"] += kw + out_bytes
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     dk = by_kernel[dom]
     achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
@@ -167,10 +174,7 @@ def main() -> int:
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4),
                 "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
                             else None),
-                "algorithmic_bytes_per_launch": round(sum(
-                    (do_bits * ((s["M"] + s["N"]) * wl.nwords(s["K"]) * 4 + s["M"] * wl.nwords(s["N"]) * 4)
-                     + do_i32 * ((s["M"] + s["N"]) * wl.nwords(s["K"]) * 4 + 4 * s["M"] * s["N"]))
-                    for s in shapes if s["kernel"] == dom) / max(dk["launches"], 1)),
+                "algorithmic_bytes_per_launch": round(dk["bytes"] / max(dk["launches"], 1)),
                 "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
                 "flop_per_launch": dk["flop"] / dk["launches"],
                 "note": "fp4 (E2M1) matrix-core peak; 1 MAC on +1/-1 = 2 flop = 2 binary ops"}

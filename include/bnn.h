@@ -60,6 +60,14 @@ int bnn_version(void);
  * shape, for profiles and reports; a static string, "invalid" for shapes the calls reject. */
 const char* bnn_bmm_kernel_name(int M, int N, int K, int path);
 const char* bnn_bconv_kernel_name(int N, int H, int W, int C, int O, int k, int stride, int pad, int path);
+/* The same for a given output: the two calls above describe the fused threshold -> bits calls
+ * (BNN_OUT_BITS); with BNN_OUT_INT32 they describe bnn_bmm / bnn_bconv, whose full-precision output
+ * can make the library choose a smaller wave tile. */
+#define BNN_OUT_BITS 0
+#define BNN_OUT_INT32 1
+const char* bnn_bmm_kernel_name_out(int M, int N, int K, int path, int out_kind);
+const char* bnn_bconv_kernel_name_out(int N, int H, int W, int C, int O, int k, int stride, int pad, int path,
+                                      int out_kind);
 
 /* ------------------------------------------------------------------------------------------
  * BMM (Sec. 5.2, Eq. 2): C[i][j] = sum_{k<K} a[i][k] * b[j][k] = K - 2 * popc(A_i xor B_j).
@@ -204,7 +212,8 @@ int bnn_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, fl
 /* pooled[n][c] = sum over HW positions of the +1/-1 value of channel c (exact integer);
  * y[n][j] = sum_c (pooled[n][c] / HW) * w[j][c].
  *   bits [N][HW][ceil(C/32)], w [J][C] fp32, y [N][J] fp32, pooled_out [N][C] int32 or NULL.
- *   HW <= 255 and C <= 1024, else BNN_ERR_UNSUPPORTED. */
+ *   HW <= 255 and C <= 1024, else BNN_ERR_UNSUPPORTED.  With pooled_out the call runs as two kernels (pooling once
+ *   per image, then the FC on the pooled sums), which is the faster form for more than a few images. */
 int bnn_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled_out,
                  int N, int HW, int C, int J, void* stream);
 

@@ -22,7 +22,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 # every symbol include/bnn.h declares
-EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
+EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm_kernel_name_out", "bnn_bconv_kernel_name_out", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
            "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
@@ -57,6 +57,8 @@ def load() -> ctypes.CDLL:
         lib.bnn_status_string.argtypes = [ctypes.c_int]
         lib.bnn_bmm_kernel_name.restype = ctypes.c_char_p
         lib.bnn_bconv_kernel_name.restype = ctypes.c_char_p
+        lib.bnn_bmm_kernel_name_out.restype = ctypes.c_char_p
+        lib.bnn_bconv_kernel_name_out.restype = ctypes.c_char_p
         lib.bnn_bwn_workspace_bytes.restype = ctypes.c_size_t
         lib.bnn_conv_f32_split_workspace_bytes.restype = ctypes.c_size_t
         lib.bnn_bmm_general_workspace_bytes.restype = ctypes.c_size_t
@@ -79,12 +81,13 @@ def _check(status: int, what: str) -> None:
         raise BnnError(status, what)
 
 
-def bmm_kernel_name(M: int, N: int, K: int, path: int = PATH_AUTO) -> str:
-    return load().bnn_bmm_kernel_name(int(M), int(N), int(K), int(path)).decode()
+def bmm_kernel_name(M: int, N: int, K: int, path: int = PATH_AUTO, int32_out: bool = False) -> str:
+    return load().bnn_bmm_kernel_name_out(int(M), int(N), int(K), int(path), int(bool(int32_out))).decode()
 
 
-def bconv_kernel_name(N, H, W, C, O, k, stride, pad, path: int = PATH_AUTO) -> str:
-    return load().bnn_bconv_kernel_name(int(N), int(H), int(W), int(C), int(O), int(k), int(stride), int(pad), int(path)).decode()
+def bconv_kernel_name(N, H, W, C, O, k, stride, pad, path: int = PATH_AUTO, int32_out: bool = False) -> str:
+    return load().bnn_bconv_kernel_name_out(int(N), int(H), int(W), int(C), int(O), int(k), int(stride), int(pad),
+                                            int(path), int(bool(int32_out))).decode()
 
 
 def nwords(nbits: int) -> int:

@@ -96,6 +96,7 @@ int bconv_common(const uint32_t* in, const uint32_t* filt, int32_t* out, const i
     if (sums16) {       // internal callers: out / resid point at 16-bit storage of the same values
         e.out16 = reinterpret_cast<int16_t*>(out); e.out = nullptr;
         e.resid16 = reinterpret_cast<const int16_t*>(resid); e.resid = nullptr;
+        e.sums_tiled = (O % 32 == 0) ? 1 : 0;      // the buffers hold 32 rows more than the tensor (plan())
     }
     return dispatch(in, filt, g, e, path, static_cast<hipStream_t>(stream));
 }
@@ -135,6 +136,7 @@ struct Plan {
     size_t resid_bytes = 0;
     size_t bwn_off = 0, bwn_bytes = 0;   // expanded first-layer weights (first layer with binarized weights only)
     size_t sync_off = 0;                 // barrier counter and abort flag of the persistent kernel
+    size_t pool_off = 0;                 // pooled sums [batch][C] int32 of a HEAD layer
     int rc = BNN_OK;
 };
 
@@ -144,6 +146,7 @@ Plan plan(bnn_net* net, int batch) {
     int H = 1, W = 1, C = 0;
     size_t max_resid = 0;
     bool have_resid = false;
+    size_t head_pool_bytes = 0;
     long long chain_bound = 1, max_bound = 0;     // |running residual| <= chain_bound
     for (size_t i = 0; i < net->layers.size(); ++i) {
         bnn_net::Layer& L = net->layers[i];
@@ -184,6 +187,7 @@ Plan plan(bnn_net* net, int batch) {
                 break;
             case bnn_net::HEAD:
                 if (i + 1 != net->layers.size()) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                head_pool_bytes = align256((size_t)batch * C * 4);
                 L.words_per_row = 0; break;
         }
         if (H < 1 || W < 1) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
@@ -197,7 +201,7 @@ Plan plan(bnn_net* net, int batch) {
         if (L.kind == bnn_net::BLOCK) bytes *= 2;      // hidden bits h of the block, then its output
         off += align256(bytes);
         if (L.kind == bnn_net::BLOCK || L.kind == bnn_net::IN_CONV_F32 || L.kind == bnn_net::CONV)
-            max_resid = max(max_resid, (size_t)batch * H * W * C * 4);
+            max_resid = max(max_resid, ((size_t)batch * H * W + 32) * C * 4);   // + 32 rows: blocked 16-bit sums pad rows
     }
     pl.sums16 = have_resid && max_bound <= 32767;
     if (have_resid) {
@@ -211,6 +215,7 @@ Plan plan(bnn_net* net, int batch) {
         off += align256(pl.bwn_bytes);
     }
     pl.sync_off = off; off += 256;
+    pl.pool_off = off; off += head_pool_bytes;
     pl.total = off;
     return pl;
 }
@@ -234,18 +239,26 @@ const char* bnn_status_string(int status) {
 int bnn_version(void) { return 100; }
 
 const char* bnn_bmm_kernel_name(int M, int N, int K, int path) {
-    if (M < 1 || N < 1 || K < 1 || K > BNN_MAX_K) return "invalid";
-    Geom g = {};
-    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = round4(words(K)); g.bits_tap = K;
-    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g);
+    return bnn_bmm_kernel_name_out(M, N, K, path, BNN_OUT_BITS);
 }
 const char* bnn_bconv_kernel_name(int N, int H, int W, int C, int O, int k, int stride, int pad, int path) {
+    return bnn_bconv_kernel_name_out(N, H, W, C, O, k, stride, pad, path, BNN_OUT_BITS);
+}
+const char* bnn_bmm_kernel_name_out(int M, int N, int K, int path, int out_kind) {
+    if (M < 1 || N < 1 || K < 1 || K > BNN_MAX_K || (out_kind != BNN_OUT_BITS && out_kind != BNN_OUT_INT32)) return "invalid";
+    Geom g = {};
+    g.rows = M; g.cols = N; g.conv = 0; g.taps = 1; g.tw = round4(words(K)); g.bits_tap = K;
+    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g, out_kind == BNN_OUT_INT32);
+}
+const char* bnn_bconv_kernel_name_out(int N, int H, int W, int C, int O, int k, int stride, int pad, int path,
+                                      int out_kind) {
     int P, Q;
+    if (out_kind != BNN_OUT_BITS && out_kind != BNN_OUT_INT32) return "invalid";
     if (conv_shape(N, H, W, C, O, k, stride, pad, BNN_PAD_MINUS_ONE, &P, &Q) != BNN_OK) return "invalid";
     Geom g = {};
     g.rows = (long long)N * P * Q; g.cols = O; g.conv = 1; g.taps = k * k; g.tw = words(C); g.bits_tap = C;
     g.H = H; g.W = W; g.P = P; g.Q = Q; g.k = k; g.stride = stride; g.pad = pad; g.lda_w = g.tw; g.ldb_w = k * k * g.tw;
-    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g);
+    return path == BNN_PATH_VALU ? describe_valu(g) : describe_mfma(g, out_kind == BNN_OUT_INT32);
 }
 
 int bnn_bmm(const uint32_t* A, const uint32_t* B, int32_t* C, int M, int N, int K, int lda_w, int ldb_w, int ldc,
@@ -627,7 +640,8 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
             }
             case bnn_net::HEAD:
                 if (!output) return BNN_ERR_INVALID_ARG;
-                rc = bnn_head_f32(cur, static_cast<const float*>(L.w0), static_cast<float*>(output), nullptr, batch,
+                rc = bnn_head_f32(cur, static_cast<const float*>(L.w0), static_cast<float*>(output),
+                                  reinterpret_cast<int32_t*>(ws + pl.pool_off), batch,
                                   curH * curW, curC, L.a, stream);
                 break;
         }

@@ -408,6 +408,104 @@ __global__ __launch_bounds__(256) void head_kernel(const uint32_t* __restrict__ 
     if (n0 + im < N && j0 + jj < J) y[(long long)(n0 + im) * J + j0 + jj] = (p0 + p1) + (p2 + p3);
 }
 
+// The same head as two kernels, for callers that give it a place for the pooled sums: the pooling runs once per
+// image instead of once per (image group, output group) workgroup, and the FC runs on the matrix cores.
+// Pooling: four adjacent lanes share one packed word (32 channels) of one image, each counting every fourth
+// position (set bits per channel, 4 channels at a time in the bytes of one register: HW <= 255); the four partial
+// counts meet through lane exchanges, and lane t of the four writes channels q + 8 t.
+__global__ __launch_bounds__(256) void head_pool_kernel(const uint32_t* __restrict__ bits, int32_t* __restrict__ pooled_out,
+                                                        int N, int HW, int C) {
+    const int cw = (C + 31) / 32;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long item = idx >> 2;
+    const int part = (int)(idx & 3);
+    const bool live = item < (long long)N * cw;            // whole groups of four lanes are live or not
+    const int n = live ? (int)(item / cw) : 0, wi = live ? (int)(item - (long long)n * cw) : 0;
+    uint32_t cnt[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) cnt[q] = 0u;
+    const uint32_t* b = bits + (long long)n * HW * cw + wi;
+    for (int i0 = part; i0 < HW; i0 += 64) {               // 16 independent loads in flight
+        uint32_t v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = (live && i0 + 4 * u < HW) ? b[(long long)(i0 + 4 * u) * cw] : 0u;
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) cnt[q] += (v[u] >> q) & 0x01010101u;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        cnt[q] += (uint32_t)__shfl_xor((int)cnt[q], 1);
+        cnt[q] += (uint32_t)__shfl_xor((int)cnt[q], 2);
+    }
+    if (!live) return;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int c = wi * 32 + q + 8 * part;
+        if (c < C) pooled_out[(long long)n * C + c] = 2 * (int)((cnt[q] >> (8 * part)) & 0xFFu) - HW;
+    }
+}
+
+// FC on the pooled sums with the fp32 matrix instruction (exact fp32 products, fp32 accumulation): a workgroup
+// computes 32 images x 32 outputs, its four waves taking every fourth step of 8 channels; lane l holds image /
+// output l % 32 and channels 4 * (l / 32) .. + 3 of the step, one MFMA per channel pair.  The four partial tiles meet
+// in LDS; the division by HW is applied once, to the finished sum.  VEC: C is a multiple of 4 (16-byte loads).
+typedef float fc_v16f __attribute__((ext_vector_type(16)));
+constexpr int FC_STEPS = 8;                     // steps (of 8 channels) a wave requests before it multiplies them
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void head_fc_kernel(const int32_t* __restrict__ pooled, const float* __restrict__ w,
+                                                      float* __restrict__ y, int N, int HW, int C, int J) {
+    __shared__ float red[4][16 * 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int n0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+    const bool nok = n0 + l32 < N, jok = j0 + l32 < J;
+    const int32_t* prow = pooled + (long long)min(n0 + l32, N - 1) * C;
+    const float* wrow = w + (long long)min(j0 + l32, J - 1) * C;
+    fc_v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const int steps = (C + 7) / 8;
+    for (int s0 = wave; s0 < steps; s0 += 4 * FC_STEPS) {
+        float a[FC_STEPS][4], b[FC_STEPS][4];
+#pragma unroll
+        for (int u = 0; u < FC_STEPS; ++u) {
+            const int c = 8 * (s0 + 4 * u) + 4 * half;
+            if (VEC) {
+                const bool ok = c < C;                      // C % 4 == 0: the four channels are in range together
+                const int4 pa = (ok && nok) ? *reinterpret_cast<const int4*>(prow + c) : make_int4(0, 0, 0, 0);
+                const float4 wb = (ok && jok) ? *reinterpret_cast<const float4*>(wrow + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                a[u][0] = (float)pa.x; a[u][1] = (float)pa.y; a[u][2] = (float)pa.z; a[u][3] = (float)pa.w;
+                b[u][0] = wb.x; b[u][1] = wb.y; b[u][2] = wb.z; b[u][3] = wb.w;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    a[u][q] = (c + q < C && nok) ? (float)prow[c + q] : 0.f;
+                    b[u][q] = (c + q < C && jok) ? wrow[c + q] : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < FC_STEPS; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][q], b[u][q], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r * 64 + lane] = acc[r];
+    __syncthreads();
+    // thread (wave, lane) finishes accumulator registers 4 * wave .. + 3 of lane: rows 8 * wave + 4 * half + q
+    const float inv = (float)HW;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = 4 * wave + q;
+        const float sum = (red[0][r * 64 + lane] + red[1][r * 64 + lane]) + (red[2][r * 64 + lane] + red[3][r * 64 + lane]);
+        const int row = n0 + 8 * wave + 4 * half + q, col = j0 + l32;
+        if (row < N && col < J) y[(long long)row * J + col] = sum / inv;
+    }
+}
+
 }  // namespace
 
 int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, long long rows, int cols,
@@ -484,6 +582,15 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
 int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* pooled, int N, int HW, int C, int J,
                     hipStream_t s) {
     if (C > HEAD_MAXC || HW > 255) return BNN_ERR_UNSUPPORTED;
+    if (pooled != nullptr) {
+        const long long lanes = 4LL * N * ((C + 31) / 32);
+        hipLaunchKernelGGL(head_pool_kernel, dim3((unsigned)cdiv(lanes, 256)), dim3(256), 0, s, bits, pooled, N, HW, C);
+        const dim3 grid((unsigned)cdiv(N, 32), (unsigned)cdiv(J, 32));
+        const bool vec = C % 4 == 0 && ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(pooled)) & 15u) == 0;
+        if (vec) hipLaunchKernelGGL(head_fc_kernel<true>, grid, dim3(256), 0, s, pooled, w, y, N, HW, C, J);
+        else hipLaunchKernelGGL(head_fc_kernel<false>, grid, dim3(256), 0, s, pooled, w, y, N, HW, C, J);
+        return check_launch();
+    }
     const size_t lds_bytes = (size_t)2 * C * HEAD_LD * sizeof(float);
     if (lds_bytes > 64 * 1024) {
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&head_kernel),

@@ -71,12 +71,27 @@ struct Epi {
     // sums provably fit: the arithmetic stays int32, only the bytes in memory are halved
     const int16_t* resid16;
     int16_t* out16;
+    // 1: resid16 / out16 are stored in blocks of 32 rows x 32 columns (ldc a multiple of 32, rows padded to 32),
+    // each block in the order the matrix cores hand out a 32x32 accumulator (sums16_index): a lane's 16 values
+    // are 32 contiguous bytes, so the residual moves as two 16-byte accesses per lane instead of sixteen
+    // 2-byte ones.  The tensor is private to the layer chain, which produces and consumes it with these kernels.
+    int sums_tiled;
     int ldc;               // elements between rows of out / resid
     int out_f32;           // 1: `out` receives the sums converted to fp32 (exact: |v| < 2^24) instead of int32
     const int32_t* thr;    // thr[col]: bit = (v >= thr[col])
     uint32_t* bits;        // bits[row*ldbits_w + col/32]
     int ldbits_w;          // words between rows of bits; words beyond ceil(cols/32) are zeroed
 };
+
+// Position of element (row, col) of a blocked 16-bit sum tensor (Epi::sums_tiled).  Inside a block, lane
+// l = col % 32 + 32 * ((row / 4) % 2) of a wave holds the element in accumulator register
+// r = 4 * ((row % 32) / 8) + row % 4, and the block stores lane after lane, 16 registers each.
+__host__ __device__ inline long long sums16_index(long long row, int col, int ldc) {
+    const int rl = (int)(row & 31);
+    const int lane = (col & 31) + 32 * ((rl >> 2) & 1);
+    const int r = 4 * (rl >> 3) + (rl & 3);
+    return ((row >> 5) * (long long)(ldc >> 5) + (col >> 5)) * 1024 + lane * 16 + r;
+}
 
 // A chain of binarized FC layers for the whole-network persistent kernel (passed by value as a kernel argument).
 constexpr int PERSIST_MAX_LAYERS = 8;
@@ -104,7 +119,7 @@ int launch_mfma_conv_v4(const uint32_t* A, const uint32_t* B, const Geom& g, con
 int launch_mfma_conv_v2(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v1(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 // Name of the kernel variant launch_mfma / launch_valu would pick for this geometry.
-const char* describe_mfma(const Geom& g);
+const char* describe_mfma(const Geom& g, bool int32_out = false);
 const char* describe_valu(const Geom& g);
 
 int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, long long rows, int cols,

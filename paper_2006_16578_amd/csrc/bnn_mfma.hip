@@ -33,14 +33,18 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
         if (g.tw % 8 == 0) return mfma::launch_shape<4, false, false>(A, B, g, e, s);
         return mfma::launch_shape<4, false, true>(A, B, g, e, s);
     }
-    if (staged_ok(g, tile)) return launch_mfma_conv_staged(A, B, g, e, s);
+    // (blocked 16-bit sums are implemented by the direct kernel only)
+    if (!e.sums_tiled && staged_ok(g, tile)) return launch_mfma_conv_staged(A, B, g, e, s);
     if (g.tw % 8 == 0) return launch_mfma_conv_v4(A, B, g, e, s);
     if (g.tw % 4 == 0) return launch_mfma_conv_v2(A, B, g, e, s);
     return launch_mfma_conv_v1(A, B, g, e, s);
 }
 
-const char* describe_mfma(const Geom& g) {
-    const int tile = mfma::pick_tile(g);
+const char* describe_mfma(const Geom& g, bool int32_out) {
+    static int32_t some_output;
+    Epi e = {};
+    e.out = int32_out ? &some_output : nullptr;   // pick_tile only asks whether there is one
+    const int tile = mfma::pick_tile(g, &e);
     const bool st = !g.b_tiled && staged_ok(g, tile);
     switch (tile) {
         case 0: return g.conv ? (st ? "mfma_fp4_conv_lds_wg256x128" : "mfma_fp4_conv_wg256x128")

@@ -117,9 +117,11 @@ __device__ __forceinline__ bool tile_coords(int gx, int gy, int& bx, int& by) {
 template <int MT, int NT, bool CONV, bool EXCL, bool HAS_RESID>
 __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
                                                  const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
-                                                 const int (&thi)[NT], const bool (&cok)[NT], const bool row_corr) {
+                                                 const int (&thi)[NT], const bool (&cok)[NT], const bool row_corr,
+                                                 const uint4* fetched) {
     const int l32 = lane & 31;
     const int half = lane >> 5;
+    const bool tiled16 = CONV && e.sums_tiled != 0;              // blocked 16-bit sums (uniform; the layer chain's convolutions)
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         uint32_t wout[NT];
@@ -131,7 +133,39 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
         // memory latency is paid once per slab and not once per element.  (sum_out may alias
         // residual_in: each element is still read before the same thread writes it.)
         int rv[16][NT];
-        if (HAS_RESID) {
+        if (HAS_RESID && tiled16 && e.resid16 != nullptr) {
+            // a lane's 16 values of a 32x32 block are 32 contiguous bytes (sums16_index)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
+                if (fetched != nullptr) {                                // MT == NT == 1: read before the main loop
+                    lo = fetched[0]; hi = fetched[1];
+                } else if (n0 + 32 * j < g.cols) {
+                    const uint4* src = reinterpret_cast<const uint4*>(
+                        e.resid16 + ((rbase >> 5) * (long long)(e.ldc >> 5) + ((n0 >> 5) + j)) * 1024 + lane * 16);
+                    lo = src[0]; hi = src[1];
+                }
+                const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                for (int r = 0; r < 16; ++r) rv[r][j] = (r & 1) ? ((int)w[r >> 1] >> 16) : (int)(short)(w[r >> 1] & 0xffffu);
+            }
+        } else if (HAS_RESID && e.resid == nullptr && e.resid16 == nullptr) {
+            // +1/-1 taken from a packed tensor (first residual of a chain): lane t of the lower half reads the
+            // word of row rbase + t once; every row's word then comes from that lane
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const long long rrow = min(rbase + l32, g.rows - 1);
+                const int wi = min((n0 >> 5) + j, e.ld_resid_bits_w - 1);
+                const uint32_t mine = e.resid_bits[rrow * (long long)e.ld_resid_bits_w + wi];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int lo_row = 8 * (r >> 2) + (r & 3);
+                    const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)mine, lo_row);
+                    const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)mine, lo_row + 4);
+                    rv[r][j] = (((half ? w1 : w0) >> l32) & 1u) ? 1 : -1;
+                }
+            }
+        } else if (HAS_RESID) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -143,11 +177,8 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
                     if (rok && cok[j]) {
                         if (e.resid != nullptr) {
                             rv[r][j] = e.resid[row * (long long)e.ldc + col];
-                        } else if (e.resid16 != nullptr) {
+                        } else {
                             rv[r][j] = (int)e.resid16[row * (long long)e.ldc + col];
-                        } else {       // +1/-1 taken from a packed tensor (first residual of a chain)
-                            const uint32_t w = e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)];
-                            rv[r][j] = ((w >> (col & 31)) & 1u) ? 1 : -1;
                         }
                     }
                 }
@@ -158,6 +189,7 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
 #pragma unroll
                 for (int j = 0; j < NT; ++j) rv[r][j] = 0;
         }
+        uint32_t pk[NT][8];                                      // blocked 16-bit sums: two values per word
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int rloc = 8 * (r >> 2) + 4 * half + (r & 3);
@@ -178,12 +210,30 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
                 const int col = n0 + 32 * j + l32;
                 const int v = (int)acc[i][j][r] - corr + (HAS_RESID ? rv[r][j] : 0);
                 if (e.out != nullptr && rok && cok[j]) e.out[row * (long long)e.ldc + col] = e.out_f32 ? __float_as_int((float)v) : v;
-                if (e.out16 != nullptr && rok && cok[j]) e.out16[row * (long long)e.ldc + col] = (int16_t)v;
+                if (e.out16 != nullptr) {
+                    if (tiled16) {
+                        if (r & 1) pk[j][r >> 1] |= (uint32_t)v << 16;
+                        else pk[j][r >> 1] = (uint32_t)v & 0xffffu;
+                    } else if (rok && cok[j]) {
+                        e.out16[row * (long long)e.ldc + col] = (int16_t)v;
+                    }
+                }
                 if (e.bits != nullptr) {
                     const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= thi[j]);
                     const int lo_row = 8 * (r >> 2) + (r & 3);
                     wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
                     wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+                }
+            }
+        }
+        if (e.out16 != nullptr && tiled16) {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                if (n0 + 32 * j < g.cols) {      // whole blocks: cols is a multiple of 32, rows are padded to 32
+                    uint4* dst = reinterpret_cast<uint4*>(
+                        e.out16 + ((rbase >> 5) * (long long)(e.ldc >> 5) + ((n0 >> 5) + j)) * 1024 + lane * 16);
+                    dst[0] = make_uint4(pk[j][0], pk[j][1], pk[j][2], pk[j][3]);
+                    dst[1] = make_uint4(pk[j][4], pk[j][5], pk[j][6], pk[j][7]);
                 }
             }
         }
@@ -207,7 +257,8 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
 // store, threshold compare, and packing through wave ballots.
 template <int MT, int NT, bool CONV, bool EXCL>
 __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
-                                         const Geom& g, const Epi& e, const int corr_all, const int pad_tap) {
+                                         const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
+                                         const uint4* fetched = nullptr) {
     const int l32 = lane & 31;
     const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
 
@@ -256,9 +307,9 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         return;
     }
     if (e.resid != nullptr || e.resid16 != nullptr || e.resid_bits != nullptr)
-        epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
+        epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, fetched);
     else
-        epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr);
+        epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, nullptr);
 }
 
 // The optional second source of a Geom (fused 1x1 downsample shortcut): a handful of K-steps read
@@ -346,6 +397,16 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
     }
     const int bmul = g.b_tiled ? 32 : 1;                // words between consecutive 4-word groups of a row, / 4
 
+    // One-block wave tiles read their blocked 16-bit residual now, so that its latency passes behind the main
+    // loop: these are the layers with short K, where a wave otherwise waits for it after its last MFMA.
+    uint4 fetched[2] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u)};
+    const bool fetch_early = MT * NT == 1 && e.sums_tiled != 0 && e.resid16 != nullptr;
+    if (MT * NT == 1 && fetch_early && m0 < g.rows && n0 < g.cols) {
+        const uint4* src = reinterpret_cast<const uint4*>(
+            e.resid16 + ((m0 >> 5) * (long long)(e.ldc >> 5) + (n0 >> 5)) * 1024 + lane * 16);
+        fetched[0] = src[0]; fetched[1] = src[1];
+    }
+
     v16f acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -357,8 +418,15 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
     const int cpt = (g.tw + 2 * V - 1) / (2 * V);   // chunks per tap
     const int T = g.taps * cpt;                     // chunks in all
 
-    uint32_t ra[2][MT][V], rb[2][NT][V];
-    uint32_t keep[2][MT];                           // EXCL: 0 for an out-of-frame tap
+    // Chunks in flight: as many as about 48 registers hold (at least 2, at most 8).  The short-K layers of a
+    // network run a handful of chunks per wave, so the wave's time is the memory latency times the number of
+    // times it waits: with D chunks requested ahead it waits about T / D times instead of T.
+    constexpr int DWANT = 48 / ((MT + NT) * V + (CONV ? MT : 0));
+    constexpr int D = DWANT < 2 ? 2 : (DWANT > 8 ? 8 : DWANT);
+    uint32_t ra[D][MT][V], rb[D][NT][V];
+    // amask: 0 for an out-of-frame tap, bmask: 0 for words past the row's end, else all ones.  They are applied
+    // when the chunk is multiplied, not when it is loaded, so that a request does not have to wait for its own data
+    uint32_t amask[D][MT], bmask[D];
 
     // Loads chunk cc of tap tt into buffer `buf`.
     auto load_chunk = [&](int buf, int tt, int cc) {
@@ -369,29 +437,20 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             const uint32_t* p = arow[i];
-            bool ok = wok;
+            bool ok = true;
             if (CONV) {
                 const int y = y0[i] + r, x = x0[i] + s;
                 const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
                 p += (inside ? (y * g.W + x) : 0) * g.lda_w;
-                ok = ok && inside;
-                keep[buf][i] = inside ? 0xFFFFFFFFu : 0u;
+                ok = inside;
             }
             load_words<V>(p + (wok ? wo : 0), ra[buf][i]);
-            if (CONV || GUARD) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) ra[buf][i][v] = ok ? ra[buf][i][v] : 0u;
-            }
+            amask[buf][i] = ok ? 0xFFFFFFFFu : 0u;
         }
         const int boff = tt * g.tw + (wok ? wo : 0);
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            load_words<V>(brow[j] + boff * bmul, rb[buf][j]);
-            if (GUARD) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) rb[buf][j][v] = wok ? rb[buf][j][v] : 0u;
-            }
-        }
+        for (int j = 0; j < NT; ++j) load_words<V>(brow[j] + boff * bmul, rb[buf][j]);
+        bmask[buf] = wok ? 0xFFFFFFFFu : 0u;
     };
 
     auto compute_chunk = [&](int buf) {
@@ -400,14 +459,18 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
             v8i fa[MT], fb[NT];
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
-                fa[i] = expand_fp4(ra[buf][i][v], c2);
+                // an out-of-frame tap is 0 bits (-1 padding) or, with excluded padding, fp4 zeros
+                uint32_t w = ra[buf][i][v];
+                if (CONV) w &= amask[buf][i];
+                if (GUARD) w &= bmask[buf];
+                fa[i] = expand_fp4(w, c2);
                 if (EXCL) {
-                    fa[i][0] &= (int)keep[buf][i]; fa[i][1] &= (int)keep[buf][i];
-                    fa[i][2] &= (int)keep[buf][i]; fa[i][3] &= (int)keep[buf][i];
+                    const int keep = (int)amask[buf][i];
+                    fa[i][0] &= keep; fa[i][1] &= keep; fa[i][2] &= keep; fa[i][3] &= keep;
                 }
             }
 #pragma unroll
-            for (int j = 0; j < NT; ++j) fb[j] = expand_fp4(rb[buf][j][v], c2);
+            for (int j = 0; j < NT; ++j) fb[j] = expand_fp4(GUARD ? (rb[buf][j][v] & bmask[buf]) : rb[buf][j][v], c2);
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -417,20 +480,20 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
         }
     };
 
-    int tt = 0, cc = 0;
-    load_chunk(0, 0, 0);
-    for (int t = 0; t < T; t += 2) {
-        // unrolled by two so that the double buffer indices are compile-time constants
-        int t1 = tt, c1 = cc + 1;
-        if (c1 == cpt) { c1 = 0; ++t1; }
-        if (t + 1 < T) load_chunk(1, t1, c1);
-        compute_chunk(0);
-        if (t + 1 < T) {
-            int t2 = t1, c2n = c1 + 1;
-            if (c2n == cpt) { c2n = 0; ++t2; }
-            if (t + 2 < T) load_chunk(0, t2, c2n);
-            compute_chunk(1);
-            tt = t2; cc = c2n;
+    int lt = 0, lc = 0, issued = 0;                 // tap, chunk of the tap and index of the next chunk to request
+    auto request = [&](int buf) {
+        if (issued < T) load_chunk(buf, lt, lc);
+        ++issued;
+        if (++lc == cpt) { lc = 0; ++lt; }
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) request(d);
+    for (int t = 0; t < T; t += D) {
+        // unrolled by D so that the ring buffer indices are compile-time constants
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (t + d < T) compute_chunk(d);
+            request(d);
         }
     }
 
@@ -438,7 +501,8 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
     const int pad_tap = cpt * 2 * V * 32 - g.bits_tap;
     int corr2 = 0;
     if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
-    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap);
+    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap,
+                                 (MT * NT == 1 && fetch_early) ? fetched : nullptr);
 }
 
 template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
@@ -474,18 +538,23 @@ inline bool conv_stages_through_lds(const Geom& g) {
 
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
 // CUs (two workgroups each for the big tiles) enough workgroups -- unless the epilogue moves full
-// precision sums and K is short.  By bandwidth alone the traffic binds below about 500 bits of K per byte
-// moved per output (2.5 P MAC/s against 4.5 TB/s), but the epilogue's loads and stores cost more than their
-// bytes, because a wave waits for them after its last MFMA: measured on the residual layers of the ResNet
-// shapes (same-run comparison of thresholds) it pays to switch up to about 2500 bits per byte read and 1200
-// per byte written.  The small tile, with four times the resident workgroups, overlaps those waits with
-// the matrix work of others.
+// precision sums and K is short: then the call is bound by that traffic and by the waits for it, and the small
+// tile, with four times the resident workgroups, overlaps them with the matrix work of others.  Where that
+// pays was measured by same-run comparison of thresholds: for a matrix product below about 500 bits of K per
+// byte moved per output (2.5 P MAC/s against 4.5 TB/s); for the residual layers of a network (blocked 16-bit
+// sums, ResNet shapes) below 600 bits per byte read and 1200 per byte written; never for a convolution with
+// row-major int32 sums, where the big tile's wider stores win.
 inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
-    if (e != nullptr) {
+    if (e != nullptr && (!g.conv || e->sums_tiled)) {
         const int bytes_in = 4 * (e->resid != nullptr) + 2 * (e->resid16 != nullptr);
         const int bytes_out = 4 * (e->out != nullptr) + 2 * (e->out16 != nullptr);
-        if (bytes_in + bytes_out > 0 && (long long)g.taps * g.bits_tap < 2500LL * bytes_in + 1200LL * bytes_out &&
-            cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
+        const long long per_in = g.conv ? 600 : 500, per_out = g.conv ? 1200 : 500;
+        // (a network layer with four or more rounds of big tiles keeps them: the small tile only wins where the
+        // big one also leaves the chip partly idle in its last round)
+        const bool many_big = g.conv && cdiv(g.rows, g.cols <= 64 ? TileTall::ROWS : TileBig::ROWS) *
+                                                cdiv(g.cols, g.cols <= 64 ? TileTall::COLS : TileBig::COLS) >= 2048;
+        if (bytes_in + bytes_out > 0 && (long long)g.taps * g.bits_tap < per_in * bytes_in + per_out * bytes_out &&
+            !many_big && cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
             return 3;
     }
     if (g.cols <= 64) return (cdiv(g.rows, TileTall::ROWS) >= 256) ? 1 : 3;

@@ -231,7 +231,9 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
     const int processed = (nslabs - 1) * 512 + (last0 + last1) * 64;
     int corr2 = 0;
     if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
-    epilogue<MT, NT, CONV, false>(acc, m0, n0, lane, g, e, processed - g.taps * g.bits_tap + corr2, 0);
+    Epi es = e;
+    es.sums_tiled = 0;          // blocked 16-bit sums go to the direct kernel (launch_mfma): that code is left out here
+    epilogue<MT, NT, CONV, false>(acc, m0, n0, lane, g, es, processed - g.taps * g.bits_tap + corr2, 0);
 }
 
 template <class TL, int U, bool CONV>

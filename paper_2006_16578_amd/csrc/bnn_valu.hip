@@ -126,11 +126,11 @@ __global__ __launch_bounds__(256) void valu_kernel(const uint32_t* __restrict__ 
         if (col < g.cols) {
             int v = nbits - 2 * (int)acc[j];
             if (e.resid != nullptr) v += e.resid[obase + col];
-            else if (e.resid16 != nullptr) v += (int)e.resid16[obase + col];
+            else if (e.resid16 != nullptr) v += (int)e.resid16[e.sums_tiled ? sums16_index(row, col, e.ldc) : obase + col];
             else if (e.resid_bits != nullptr)
                 v += ((e.resid_bits[row * (long long)e.ld_resid_bits_w + (col >> 5)] >> (col & 31)) & 1u) ? 1 : -1;
             if (e.out != nullptr) e.out[obase + col] = e.out_f32 ? __float_as_int((float)v) : v;
-            if (e.out16 != nullptr) e.out16[obase + col] = (int16_t)v;
+            if (e.out16 != nullptr) e.out16[e.sums_tiled ? sums16_index(row, col, e.ldc) : obase + col] = (int16_t)v;
             if (e.thr != nullptr && v >= e.thr[col]) word |= (1u << j);
         }
     }

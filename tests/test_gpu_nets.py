@@ -104,16 +104,21 @@ def test_resnet18_batch256(bnn, orc):
     check_resnet(bnn, orc, p, x, 224, 0, tier=1)
 
 
-def test_resnet18_head_pooled(bnn, orc):
-    rng = np.random.default_rng(12)
-    bits = wl.random_bits(rng, (9, 7, 7), 512)
-    w = rng.normal(0, 0.02, size=(1000, 512)).astype(np.float32)
-    y, pooled = bnn.head_f32(to_dev(bits), to_dev(w), 512, want_pooled=True)
-    pr = orc.sumpool_pm1(bits, 512)
-    assert np.array_equal(host(pooled), pr)
-    ref = orc.head_fc_f32(pr, w, 49.0)
+@pytest.mark.parametrize("shape", [(9, 7, 7, 512, 1000), (35, 3, 5, 200, 70), (1, 1, 1, 33, 1), (16, 8, 8, 1024, 130), (40, 15, 17, 36, 33)])
+def test_head_pooled(bnn, orc, shape):
+    # with a pooled-sum output the head runs as two kernels (pool, then FC), without it as one fused kernel
+    N, H, W, C, J = shape
+    rng = np.random.default_rng(12 + C)
+    bits = wl.random_bits(rng, (N, H, W), C)
+    w = rng.normal(0, 0.02, size=(J, C)).astype(np.float32)
+    pr = orc.sumpool_pm1(bits, C)
+    ref = orc.head_fc_f32(pr, w, float(H * W))
     tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
+    y, pooled = bnn.head_f32(to_dev(bits), to_dev(w), C, want_pooled=True)
+    assert np.array_equal(host(pooled), pr)
     assert (np.abs(host(y) - ref) <= tol).all()
+    y1 = bnn.head_f32(to_dev(bits), to_dev(w), C)
+    assert (np.abs(host(y1) - ref) <= tol).all()
 
 
 @pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
