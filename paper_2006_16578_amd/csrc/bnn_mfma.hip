@@ -30,11 +30,13 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
         }
         // tw is a multiple of 4 words; a chunk is 8 words, so an odd number of 4-word groups
         // leaves the upper half-wave without data in the last chunk -> guarded variant
+        if (!mfma::offsets_fit(g)) return BNN_ERR_UNSUPPORTED;
         if (g.tw % 8 == 0) return mfma::launch_shape<4, false, false>(A, B, g, e, s);
         return mfma::launch_shape<4, false, true>(A, B, g, e, s);
     }
     // (blocked 16-bit sums are implemented by the direct kernel only)
     if (!e.sums_tiled && staged_ok(g, tile)) return launch_mfma_conv_staged(A, B, g, e, s);
+    if (!mfma::offsets_fit(g)) return BNN_ERR_UNSUPPORTED;
     if (g.tw % 8 == 0) return launch_mfma_conv_v4(A, B, g, e, s);
     if (g.tw % 4 == 0) return launch_mfma_conv_v2(A, B, g, e, s);
     return launch_mfma_conv_v1(A, B, g, e, s);

@@ -354,7 +354,10 @@ __device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, 
 // CONV: rows are output pixels gathered through the filter window; EXCL: out-of-frame taps
 // contribute nothing; GUARD: the last chunk of a tap may run past tw.
 // One workgroup tile (bx, by) of the product: everything from the operand loads to the epilogue.
-template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
+// CPT3 > 0: a 3x3 window whose taps are exactly CPT3 chunks each (tw == CPT3 * 2 * V): the loop over the 9 * CPT3
+// chunks is unrolled in full, so that tap and chunk indices are compile-time constants and a request is a handful of
+// instructions (the layers of a network are short: their time is instruction issue, not the matrix cores).
+template <class TL, int V, bool CONV, bool EXCL, bool GUARD, int CPT3 = 0>
 __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const uint32_t* __restrict__ B, const Geom& g,
                                           const Epi& e, const int bx, const int by) {
     constexpr int MT = TL::MT, NT = TL::NT;
@@ -368,8 +371,18 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
     uint32_t c2;
     asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c2));
 
-    // Row descriptors of the A fragments.
-    const uint32_t* arow[MT];
+    // Addresses are a uniform base (scalar registers) plus a 32-bit byte offset per lane: the base moves with the
+    // tap and the chunk, the lane's part is fixed per row, so a request costs no 64-bit vector arithmetic.  The
+    // bases belong to the workgroup tile (its first row's image, its first column), which keeps every offset
+    // non-negative and below 2^31 (checked on the host: offsets_fit).
+    const long long m0_wg = (long long)bx * TL::ROWS;               // < g.rows
+    const int n0_wg = min(by * TL::COLS, ((g.cols - 1) >> 5) << 5);
+    int n_first = 0;
+    if (CONV) n_first = fast_div((int)m0_wg, g.div_pq);
+    const uint32_t* Abase = CONV ? A + (long long)n_first * g.H * g.W * g.lda_w : A + m0_wg * g.lda_w;
+    const uint32_t* Bbase = B + (long long)n0_wg * g.ldb_w;
+
+    uint32_t aoff[MT];             // bytes from Abase to the row's pixel (y0, x0) (BMM: to the row), plus the half-wave's words
     int y0[MT], x0[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -381,19 +394,20 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
             const int p = fast_div(rem, g.div_q), q = rem - p * g.Q;
             y0[i] = p * g.stride - g.pad;
             x0[i] = q * g.stride - g.pad;
-            arow[i] = A + (long long)n * g.H * g.W * g.lda_w;
+            aoff[i] = (uint32_t)(((((n - n_first) * g.H + y0[i]) * g.W + x0[i]) * g.lda_w + half * V) * 4);
         } else {
             y0[i] = 0; x0[i] = 0;
-            arow[i] = A + row * g.lda_w;
+            aoff[i] = (uint32_t)(((int)(row - m0_wg) * g.lda_w + half * V) * 4);
         }
     }
-    const uint32_t* brow[NT];
+    uint32_t boff[NT];             // bytes from Bbase to the column's row of B, plus the half-wave's words
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int col = min(n0 + 32 * j + l32, g.cols - 1);
         // tiled B: rows are grouped by 32; a group stores, for each 16-byte step along K, its 32 rows' 16 bytes
         // back to back, so the 32 lanes of a fragment load read 512 contiguous bytes
-        brow[j] = g.b_tiled ? B + (long long)(col >> 5) * g.ldb_w * 32 + (col & 31) * 4 : B + (long long)col * g.ldb_w;
+        boff[j] = g.b_tiled ? (uint32_t)((((col >> 5) - (n0_wg >> 5)) * g.ldb_w * 32 + (col & 31) * 4 + half * V * 32) * 4)
+                            : (uint32_t)(((col - n0_wg) * g.ldb_w + half * V) * 4);
     }
     const int bmul = g.b_tiled ? 32 : 1;                // words between consecutive 4-word groups of a row, / 4
 
@@ -415,45 +429,22 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int cpt = (g.tw + 2 * V - 1) / (2 * V);   // chunks per tap
+    const int cpt = CPT3 > 0 ? CPT3 : (g.tw + 2 * V - 1) / (2 * V);   // chunks per tap
     const int T = g.taps * cpt;                     // chunks in all
 
-    // Chunks in flight: as many as about 48 registers hold (at least 2, at most 8).  The short-K layers of a
-    // network run a handful of chunks per wave, so the wave's time is the memory latency times the number of
-    // times it waits: with D chunks requested ahead it waits about T / D times instead of T.
-    constexpr int DWANT = 48 / ((MT + NT) * V + (CONV ? MT : 0));
-    constexpr int D = DWANT < 2 ? 2 : (DWANT > 8 ? 8 : DWANT);
+    // Chunks in flight: as many as about 48 registers hold (at least 2, at most 8; the unrolled 3x3 form keeps no
+    // masks per chunk and goes up to all of its chunks).  The short-K layers of a network run a handful of chunks
+    // per wave, so the wave's time is the memory latency times the number of times it waits: with D chunks
+    // requested ahead it waits about T / D times instead of T.
+    constexpr int DWANT = 48 / ((MT + NT) * V + ((CONV && CPT3 == 0) ? MT : 0));
+    constexpr int DMAX = CPT3 > 0 ? 9 * CPT3 : 8;
+    constexpr int D = DWANT < 2 ? 2 : (DWANT > DMAX ? DMAX : DWANT);
     uint32_t ra[D][MT][V], rb[D][NT][V];
-    // amask: 0 for an out-of-frame tap, bmask: 0 for words past the row's end, else all ones.  They are applied
-    // when the chunk is multiplied, not when it is loaded, so that a request does not have to wait for its own data
-    uint32_t amask[D][MT], bmask[D];
 
-    // Loads chunk cc of tap tt into buffer `buf`.
-    auto load_chunk = [&](int buf, int tt, int cc) {
-        const int wo = cc * 2 * V + half * V;       // this lane's word offset inside the tap
-        const bool wok = !GUARD || (wo < g.tw);     // tw and wo are multiples of V
-        int r = 0, s = 0;
-        if (CONV) { r = (tt * g.kinv) >> 16; s = tt - r * g.k; }
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            const uint32_t* p = arow[i];
-            bool ok = true;
-            if (CONV) {
-                const int y = y0[i] + r, x = x0[i] + s;
-                const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
-                p += (inside ? (y * g.W + x) : 0) * g.lda_w;
-                ok = inside;
-            }
-            load_words<V>(p + (wok ? wo : 0), ra[buf][i]);
-            amask[buf][i] = ok ? 0xFFFFFFFFu : 0u;
-        }
-        const int boff = tt * g.tw + (wok ? wo : 0);
-#pragma unroll
-        for (int j = 0; j < NT; ++j) load_words<V>(brow[j] + boff * bmul, rb[buf][j]);
-        bmask[buf] = wok ? 0xFFFFFFFFu : 0u;
-    };
-
-    auto compute_chunk = [&](int buf) {
+    // Multiplies the chunk in buffer `buf`; am[i]: 0 for an out-of-frame tap, bm: 0 for words past the row's end,
+    // else all ones.  The masks are applied here, not when the chunk is loaded, so that a request does not have
+    // to wait for its own data.
+    auto multiply = [&](int buf, const uint32_t (&am)[MT], uint32_t bm) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             v8i fa[MT], fb[NT];
@@ -461,16 +452,16 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
             for (int i = 0; i < MT; ++i) {
                 // an out-of-frame tap is 0 bits (-1 padding) or, with excluded padding, fp4 zeros
                 uint32_t w = ra[buf][i][v];
-                if (CONV) w &= amask[buf][i];
-                if (GUARD) w &= bmask[buf];
+                if (CONV) w &= am[i];
+                if (GUARD) w &= bm;
                 fa[i] = expand_fp4(w, c2);
                 if (EXCL) {
-                    const int keep = (int)amask[buf][i];
+                    const int keep = (int)am[i];
                     fa[i][0] &= keep; fa[i][1] &= keep; fa[i][2] &= keep; fa[i][3] &= keep;
                 }
             }
 #pragma unroll
-            for (int j = 0; j < NT; ++j) fb[j] = expand_fp4(GUARD ? (rb[buf][j][v] & bmask[buf]) : rb[buf][j][v], c2);
+            for (int j = 0; j < NT; ++j) fb[j] = expand_fp4(GUARD ? (rb[buf][j][v] & bm) : rb[buf][j][v], c2);
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -480,20 +471,94 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
         }
     };
 
-    int lt = 0, lc = 0, issued = 0;                 // tap, chunk of the tap and index of the next chunk to request
-    auto request = [&](int buf) {
-        if (issued < T) load_chunk(buf, lt, lc);
-        ++issued;
-        if (++lc == cpt) { lc = 0; ++lt; }
-    };
+    if constexpr (CPT3 > 0) {
+        // bit t of vm[i]: tap t = 3 r + s of row i is in frame
+        uint32_t vm[MT];
 #pragma unroll
-    for (int d = 0; d < D; ++d) request(d);
-    for (int t = 0; t < T; t += D) {
-        // unrolled by D so that the ring buffer indices are compile-time constants
+        for (int i = 0; i < MT; ++i) {
+            uint32_t cm = 0u;
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (t + d < T) compute_chunk(d);
-            request(d);
+            for (int d = 0; d < 3; ++d) cm |= ((unsigned)(x0[i] + d) < (unsigned)g.W) ? (1u << d) : 0u;
+            vm[i] = 0u;
+#pragma unroll
+            for (int d = 0; d < 3; ++d) vm[i] |= ((unsigned)(y0[i] + d) < (unsigned)g.H) ? (cm << (3 * d)) : 0u;
+        }
+        const uint32_t safe = (uint32_t)(half * V * 4);      // an out-of-frame tap reads the image's first pixel
+        const uint32_t row_bytes = (uint32_t)(g.W * g.lda_w * 4), pix_bytes = (uint32_t)(g.lda_w * 4);
+        auto request3 = [&](int buf, int q) {                // q: chunk index, a constant after unrolling
+            const int tt = q / CPT3, cc = q % CPT3, r = tt / 3, s = tt % 3;
+            const char* abase = reinterpret_cast<const char*>(Abase + cc * 2 * V);
+            const uint32_t tapoff = (uint32_t)r * row_bytes + (uint32_t)s * pix_bytes;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                const uint32_t in = (uint32_t)__builtin_amdgcn_sbfe((int)vm[i], tt, 1);     // all ones or 0
+                const uint32_t off = ((aoff[i] + tapoff) & in) | (safe & ~in);
+                load_words<V>(reinterpret_cast<const uint32_t*>(abase + (size_t)off), ra[buf][i]);
+            }
+            const char* bbase = reinterpret_cast<const char*>(Bbase + (tt * g.tw + cc * 2 * V) * bmul);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                load_words<V>(reinterpret_cast<const uint32_t*>(bbase + (size_t)boff[j]), rb[buf][j]);
+        };
+        constexpr int T3 = 9 * CPT3;
+#pragma unroll
+        for (int q = 0; q < D; ++q) request3(q, q);
+#pragma unroll
+        for (int q = 0; q < T3; ++q) {
+            uint32_t am[MT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) am[i] = (uint32_t)__builtin_amdgcn_sbfe((int)vm[i], q / CPT3, 1);
+            multiply(q % D, am, 0xFFFFFFFFu);
+            if (q + D < T3) request3(q % D, q + D);
+        }
+    } else {
+        uint32_t amask[D][MT], bmask[D];
+
+        // Loads chunk cc of tap tt into buffer `buf`.
+        auto load_chunk = [&](int buf, int tt, int cc) {
+            const int wo = cc * 2 * V;                  // first word of the chunk inside the tap (uniform)
+            const bool wok = !GUARD || (wo + half * V < g.tw);     // tw is a multiple of V
+            // GUARD: the chunk's word offset is added per lane, and lanes past the row's end re-read word 0 of the tap
+            const uint32_t lane_wo = !GUARD ? 0u : (wok ? (uint32_t)(wo * 4) : (uint32_t)(-(half * V * 4)));
+            int r = 0, s = 0;
+            if (CONV) { r = (tt * g.kinv) >> 16; s = tt - r * g.k; }
+            const char* abase = reinterpret_cast<const char*>(Abase + (GUARD ? 0 : wo));
+            const uint32_t tapoff = CONV ? (uint32_t)((r * g.W + s) * g.lda_w * 4) : 0u;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                uint32_t off = aoff[i] + tapoff;
+                bool ok = true;
+                if (CONV) {
+                    const int y = y0[i] + r, x = x0[i] + s;
+                    ok = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
+                    off = ok ? off : (uint32_t)(half * V * 4);      // an out-of-frame tap reads the image's first pixel
+                }
+                load_words<V>(reinterpret_cast<const uint32_t*>(abase + (size_t)(off + lane_wo)), ra[buf][i]);
+                amask[buf][i] = ok ? 0xFFFFFFFFu : 0u;
+            }
+            const char* bbase = reinterpret_cast<const char*>(Bbase + (tt * g.tw + (GUARD ? 0 : wo)) * bmul);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                load_words<V>(reinterpret_cast<const uint32_t*>(bbase + (size_t)(boff[j] + lane_wo * (uint32_t)bmul)),
+                              rb[buf][j]);
+            bmask[buf] = wok ? 0xFFFFFFFFu : 0u;
+        };
+
+        int lt = 0, lc = 0, issued = 0;             // tap, chunk of the tap and index of the next chunk to request
+        auto request = [&](int buf) {
+            if (issued < T) load_chunk(buf, lt, lc);
+            ++issued;
+            if (++lc == cpt) { lc = 0; ++lt; }
+        };
+#pragma unroll
+        for (int d = 0; d < D; ++d) request(d);
+        for (int t = 0; t < T; t += D) {
+            // unrolled by D so that the ring buffer indices are compile-time constants
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (t + d < T) multiply(d, amask[d], bmask[d]);
+                request(d);
+            }
         }
     }
 
@@ -505,13 +570,20 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
                                  (MT * NT == 1 && fetch_early) ? fetched : nullptr);
 }
 
-template <class TL, int V, bool CONV, bool EXCL, bool GUARD>
+template <class TL, int V, bool CONV, bool EXCL, bool GUARD, int CPT3 = 0>
 __global__ __launch_bounds__(256, TL::MINB) void mfma_kernel(const uint32_t* __restrict__ A,
                                                              const uint32_t* __restrict__ B, Geom g, Epi e,
                                                              int gx, int gy) {
     int bx, by;
     if (!tile_coords(gx, gy, bx, by)) return;          // uniform for the workgroup
-    mfma_tile<TL, V, CONV, EXCL, GUARD>(A, B, g, e, bx, by);
+    mfma_tile<TL, V, CONV, EXCL, GUARD, CPT3>(A, B, g, e, bx, by);
+}
+
+template <class TL, int V, bool EXCL, int CPT3>
+int launch_tile_3x3(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, int gx, int gy, unsigned nwg,
+                    hipStream_t s) {
+    hipLaunchKernelGGL((mfma_kernel<TL, V, true, EXCL, false, CPT3>), dim3(nwg), dim3(256), 0, s, A, B, g, e, gx, gy);
+    return check_launch();
 }
 
 template <class TL, int V, bool CONV, bool GUARD>
@@ -519,6 +591,16 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
     const int col_span = (e.bits != nullptr) ? max(g.cols, e.ldbits_w * 32) : g.cols;
     const int gx = (int)cdiv(g.rows, TL::ROWS), gy = (int)cdiv(col_span, TL::COLS);
     const unsigned nwg = (unsigned)(cdiv((long long)gx * gy, 8) * 8);
+    if constexpr (CONV && !GUARD) {
+        // 3x3 windows of one or two chunks per tap (C = 64 V, 128 V): the unrolled form
+        if (g.k == 3 && g.taps == 9 && (g.tw == 2 * V || (V == 4 && g.tw == 4 * V))) {
+            if (g.tw == 2 * V) return g.excl ? launch_tile_3x3<TL, V, true, 1>(A, B, g, e, gx, gy, nwg, s)
+                                             : launch_tile_3x3<TL, V, false, 1>(A, B, g, e, gx, gy, nwg, s);
+            if constexpr (V == 4)        // (narrower loads are only chosen for tw not a multiple of 8)
+                return g.excl ? launch_tile_3x3<TL, V, true, 2>(A, B, g, e, gx, gy, nwg, s)
+                              : launch_tile_3x3<TL, V, false, 2>(A, B, g, e, gx, gy, nwg, s);
+        }
+    }
     if (CONV && g.excl)
         hipLaunchKernelGGL((mfma_kernel<TL, V, CONV, CONV, GUARD>), dim3(nwg), dim3(256), 0, s, A, B, g, e, gx, gy);
     else
@@ -564,6 +646,15 @@ inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
     if (cdiv(g.rows, TileBig::ROWS) * cdiv(g.cols, TileBig::COLS) >= big_min) return 0;
     if (cdiv(g.rows, TileMid::ROWS) * cdiv(g.cols, TileMid::COLS) >= 256) return 2;
     return 3;
+}
+
+// The direct kernel addresses a workgroup tile's operands with 32-bit byte offsets from the tile's first row /
+// image and first column: 512 rows of A and 160 rows of B must span less than 2 GiB (leading dimensions below
+// 2^20 and 2^21 words), and so must the images that up to 512 consecutive output pixels touch.
+inline bool offsets_fit(const Geom& g) {
+    if (!g.conv) return g.lda_w < (1 << 20) && g.ldb_w < (1 << 21);
+    const long long images = (TileTall::ROWS - 1) / ((long long)g.P * g.Q) + 2;
+    return images * g.H * g.W * g.lda_w * 4 < (1LL << 31);
 }
 
 template <int V, bool CONV, bool GUARD>
