@@ -59,6 +59,13 @@ __device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t c2) {
     return r;
 }
 
+// A lane's 32 bytes of a blocked 16-bit residual read ahead of the main loop (passed by value, so that it stays
+// in registers).
+struct Fetched {
+    uint4 lo, hi;
+    bool valid;
+};
+
 // v_writelane_b32 through the compiler's own intrinsic (clang has no builtin for it), so that the
 // wait states the hardware needs between a VALU compare that writes an SGPR pair and the
 // v_writelane that reads it are inserted by the compiler: hand-written asm reads a stale value.
@@ -118,7 +125,7 @@ template <int MT, int NT, bool CONV, bool EXCL, bool HAS_RESID>
 __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
                                                  const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
                                                  const int (&thi)[NT], const bool (&cok)[NT], const bool row_corr,
-                                                 const uint4* fetched) {
+                                                 const Fetched fetched) {
     const int l32 = lane & 31;
     const int half = lane >> 5;
     const bool tiled16 = CONV && e.sums_tiled != 0;              // blocked 16-bit sums (uniform; the layer chain's convolutions)
@@ -138,8 +145,8 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
-                if (fetched != nullptr) {                                // MT == NT == 1: read before the main loop
-                    lo = fetched[0]; hi = fetched[1];
+                if (fetched.valid) {                                     // MT == NT == 1: read before the main loop
+                    lo = fetched.lo; hi = fetched.hi;
                 } else if (n0 + 32 * j < g.cols) {
                     const uint4* src = reinterpret_cast<const uint4*>(
                         e.resid16 + ((rbase >> 5) * (long long)(e.ldc >> 5) + ((n0 >> 5) + j)) * 1024 + lane * 16);
@@ -250,6 +257,99 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
     }
 }
 
+// Epilogue of a residual layer inside a layer chain: blocked 16-bit sums in and / or out (or the +1/-1 of packed
+// bits as the residual), threshold -> bits.  Straight-line code in fp32, where the accumulators already are:
+// every value is an integer below 2^24 in magnitude, so the arithmetic is exact.  No pixel-dependent correction.
+typedef short v2s __attribute__((ext_vector_type(2)));
+
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue_chain(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
+                                               const Geom& g, const Epi& e, const int corr_all, const int (&thi)[NT],
+                                               const bool (&cok)[NT], const Fetched fetched) {
+    const int l32 = lane & 31;
+    const float corr = (float)corr_all;
+    float thf[NT];                                           // acc + residual >= threshold + correction
+#pragma unroll
+    for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)thi[j] + corr : __builtin_inff();
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= g.rows) break;                              // uniform per wave
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            wout[j] = 0u;
+            const bool cblk = n0 + 32 * j < g.cols;              // uniform: whole blocks (cols is a multiple of 32)
+            const long long blk = ((rbase >> 5) * (long long)(e.ldc >> 5) + ((n0 >> 5) + j)) * 1024 + lane * 16;
+            float rv[16];
+            if (e.resid16 != nullptr) {
+                // a lane's 16 values of a 32x32 block are 32 contiguous bytes (sums16_index)
+                uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
+                if (fetched.valid) {                             // MT == NT == 1: read before the main loop
+                    lo = fetched.lo; hi = fetched.hi;
+                } else if (cblk) {
+                    const uint4* src = reinterpret_cast<const uint4*>(e.resid16 + blk);
+                    lo = src[0]; hi = src[1];
+                }
+                const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    rv[r] = (float)((r & 1) ? ((int)w[r >> 1] >> 16) : (int)(short)(w[r >> 1] & 0xffffu));
+            } else if (e.resid_bits != nullptr) {
+                // +1/-1 taken from a packed tensor (first residual of a chain): lane t of the lower half reads the
+                // (inverted) word of row rbase + t once; rows R and R + 4 then sit in one 64-bit scalar, which each
+                // lane shifts so that its column's bit of its own row becomes the sign of 1.0
+                const long long rrow = min(rbase + l32, g.rows - 1);
+                const int wi = min((n0 >> 5) + j, e.ld_resid_bits_w - 1);
+                const uint32_t mine = ~e.resid_bits[rrow * (long long)e.ld_resid_bits_w + wi];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int lo_row = 8 * (r >> 2) + (r & 3);
+                    const unsigned long long both =
+                        ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)mine, lo_row + 4) << 32) |
+                        (uint32_t)__builtin_amdgcn_readlane((int)mine, lo_row);
+                    const uint32_t top = (uint32_t)((both << (63 - lane)) >> 32);
+                    rv[r] = __uint_as_float((top & 0x80000000u) | 0x3f800000u);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) rv[r] = 0.f;
+            }
+            int vs[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float sum = acc[i][j][r] + rv[r];
+                vs[r] = (int)(sum - corr);
+                const unsigned long long ball = __builtin_amdgcn_ballot_w64(sum >= thf[j]);
+                const int lo_row = 8 * (r >> 2) + (r & 3);
+                wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+            }
+            if (e.out16 != nullptr && cblk) {
+                uint32_t pk[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const v2s two = __builtin_amdgcn_cvt_pk_i16(vs[2 * q], vs[2 * q + 1]);
+                    pk[q] = (uint32_t)(uint16_t)two[0] | ((uint32_t)(uint16_t)two[1] << 16);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(e.out16 + blk);
+                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            }
+        }
+        if (lane < 32) {
+            const long long row = rbase + lane;
+            if (row < g.rows) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int wi = (n0 >> 5) + j;
+                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                }
+            }
+        }
+    }
+}
+
 // Epilogue shared by the matrix-core kernels.  acc holds, as exact integers in fp32, the sums
 // over every processed bit position; positions beyond the logical width are 0 bits in both
 // operands and have contributed (+1)(+1) = +1 each: corr_all of them per output (in exclude mode
@@ -258,7 +358,7 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
 template <int MT, int NT, bool CONV, bool EXCL>
 __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
                                          const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
-                                         const uint4* fetched = nullptr) {
+                                         const Fetched fetched = Fetched{make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), false}) {
     const int l32 = lane & 31;
     const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
 
@@ -277,7 +377,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         // by the pad correction; one v_cmp per accumulator register gives two packed words.
         float thf[NT];
 #pragma unroll
-        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)(thi[j] + corr_all) : __builtin_inff();
+        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)thi[j] + (float)corr_all : __builtin_inff();
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             const long long rbase = m0 + 32 * i;
@@ -306,10 +406,14 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         }
         return;
     }
+    if (CONV && e.sums_tiled != 0 && e.bits != nullptr && e.out == nullptr && e.resid == nullptr && !row_corr) {
+        epilogue_chain<MT, NT>(acc, m0, n0, lane, g, e, corr_all, thi, cok, fetched);
+        return;
+    }
     if (e.resid != nullptr || e.resid16 != nullptr || e.resid_bits != nullptr)
         epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, fetched);
     else
-        epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, nullptr);
+        epilogue_generic<MT, NT, CONV, EXCL, false>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, fetched);
 }
 
 // The optional second source of a Geom (fused 1x1 downsample shortcut): a handful of K-steps read
@@ -413,13 +517,19 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
 
     // One-block wave tiles read their blocked 16-bit residual now, so that its latency passes behind the main
     // loop: these are the layers with short K, where a wave otherwise waits for it after its last MFMA.
-    uint4 fetched[2] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u)};
-    const bool fetch_early = MT * NT == 1 && e.sums_tiled != 0 && e.resid16 != nullptr;
-    if (MT * NT == 1 && fetch_early && m0 < g.rows && n0 < g.cols) {
-        const uint4* src = reinterpret_cast<const uint4*>(
-            e.resid16 + ((m0 >> 5) * (long long)(e.ldc >> 5) + (n0 >> 5)) * 1024 + lane * 16);
-        fetched[0] = src[0]; fetched[1] = src[1];
-    }
+    // (requested after the first chunks: the memory counter retires in order, and the residual comes from HBM
+    // while the operands mostly come from L2)
+    Fetched fetched = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), false};
+    auto fetch_residual = [&]() {
+        if (MT * NT == 1 && e.sums_tiled != 0 && e.resid16 != nullptr) {
+            fetched.valid = true;
+            if (m0 < g.rows && n0 < g.cols) {
+                const uint4* src = reinterpret_cast<const uint4*>(
+                    e.resid16 + ((m0 >> 5) * (long long)(e.ldc >> 5) + (n0 >> 5)) * 1024 + lane * 16);
+                fetched.lo = src[0]; fetched.hi = src[1];
+            }
+        }
+    };
 
     v16f acc[MT][NT];
 #pragma unroll
@@ -503,6 +613,7 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
         constexpr int T3 = 9 * CPT3;
 #pragma unroll
         for (int q = 0; q < D; ++q) request3(q, q);
+        fetch_residual();
 #pragma unroll
         for (int q = 0; q < T3; ++q) {
             uint32_t am[MT];
@@ -552,6 +663,7 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
         };
 #pragma unroll
         for (int d = 0; d < D; ++d) request(d);
+        fetch_residual();
         for (int t = 0; t < T; t += D) {
             // unrolled by D so that the ring buffer indices are compile-time constants
 #pragma unroll
@@ -566,8 +678,7 @@ __device__ __forceinline__ void mfma_tile(const uint32_t* __restrict__ A, const 
     const int pad_tap = cpt * 2 * V * 32 - g.bits_tap;
     int corr2 = 0;
     if (CONV && g.A2 != nullptr) corr2 = extra_source<MT, NT>(acc, g, m0, n0, lane, c2) - g.bits2;
-    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap,
-                                 (MT * NT == 1 && fetch_early) ? fetched : nullptr);
+    epilogue<MT, NT, CONV, EXCL>(acc, m0, n0, lane, g, e, g.taps * pad_tap + corr2, pad_tap, fetched);
 }
 
 template <class TL, int V, bool CONV, bool EXCL, bool GUARD, int CPT3 = 0>
