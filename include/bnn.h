@@ -197,6 +197,12 @@ size_t bnn_conv_f32_split_workspace_bytes(int C, int O, int k);
 int bnn_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
                            int N, int H, int W, int C, int O, int k, int stride, int pad,
                            void* workspace, size_t workspace_bytes, void* stream);
+/* products = 9: as above.  products = 6: without the three smallest term products (middle x low, low x middle,
+ * low x low), which together are below 2^-23 of x*w: each product is then as accurate as one rounded to fp32, for
+ * two thirds of the matrix work.  The layer chain (bnn_net_forward) uses 6. */
+int bnn_conv_f32_split_thr_ex(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits,
+                              int N, int H, int W, int C, int O, int k, int stride, int pad, int products,
+                              void* workspace, size_t workspace_bytes, void* stream);
 /* First layer with binarized weights only (Sec. 6.1, "BWN"): the input stays real-valued, each weight is one
  * bit that decides whether the input element is added (bit 1) or subtracted (bit 0); zero padding;
  * bits = (y >= thr[o]).  fp32 accumulation (every product is exact), 1e-4 relative like the layer above.

@@ -25,7 +25,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm_kernel_name_out", "bnn_bconv_kernel_name_out", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
            "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
-           "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
+           "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_conv_f32_split_thr_ex", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
            "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_layer_bits"]
@@ -359,8 +359,9 @@ def conv_f32_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False):
     return (bits, y) if want_f32 else bits
 
 
-def conv_f32_split_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False, workspace=None):
-    """fp32 first layer on the bf16 matrix cores (inputs and weights split exactly into three bf16 terms each)."""
+def conv_f32_split_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False, workspace=None, products: int = 9):
+    """fp32 first layer on the bf16 matrix cores (inputs and weights split exactly into three bf16 terms each;
+    products: 9 term products, or 6 without the three smallest)."""
     _dev(x, torch.float32, 4, "x"); _dev(w, torch.float32, 4, "w"); _dev(thr, torch.float32, 1, "thr")
     N, H, W, C = x.shape
     O, k, _, C2 = w.shape
@@ -373,9 +374,9 @@ def conv_f32_split_thr(x, w, thr, stride: int, pad: int, want_f32: bool = False,
     if workspace is None:
         workspace = torch.empty(max(int(load().bnn_conv_f32_split_workspace_bytes(C, O, k)), 16), dtype=torch.uint8, device=x.device)
     with torch.cuda.device(x.device):
-        _check(load().bnn_conv_f32_split_thr(_ptr(x), _ptr(w), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride),
-                                             int(pad), _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(x)),
-               "bnn_conv_f32_split_thr")
+        _check(load().bnn_conv_f32_split_thr_ex(_ptr(x), _ptr(w), _ptr(thr), _ptr(y), _ptr(bits), N, H, W, C, O, k, int(stride),
+                                                int(pad), int(products), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
+                                                _stream(x)), "bnn_conv_f32_split_thr_ex")
     return (bits, y) if want_f32 else bits
 
 

@@ -419,7 +419,13 @@ size_t bnn_conv_f32_split_workspace_bytes(int C, int O, int k) {
 int bnn_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits, int N, int H,
                            int W, int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes,
                            void* stream) {
-    if (!x || !w || (!y_f32 && !bits) || (bits && !thr)) return BNN_ERR_INVALID_ARG;
+    return bnn_conv_f32_split_thr_ex(x, w, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, 9, workspace, workspace_bytes,
+                                     stream);
+}
+int bnn_conv_f32_split_thr_ex(const float* x, const float* w, const float* thr, float* y_f32, uint32_t* bits, int N, int H,
+                              int W, int C, int O, int k, int stride, int pad, int products, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+    if (!x || !w || (!y_f32 && !bits) || (bits && !thr) || (products != 6 && products != 9)) return BNN_ERR_INVALID_ARG;
     if (N < 1 || H < 1 || W < 1 || C < 1 || O < 1 || k < 1 || stride < 1 || pad < 0) return BNN_ERR_INVALID_ARG;
     if (H + 2 * pad < k || W + 2 * pad < k) return BNN_ERR_INVALID_ARG;
     const long long P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
@@ -427,8 +433,8 @@ int bnn_conv_f32_split_thr(const float* x, const float* w, const float* thr, flo
         return BNN_ERR_UNSUPPORTED;
     if (!workspace) return BNN_ERR_WORKSPACE;
     if (!aligned16(workspace)) return BNN_ERR_ALIGNMENT;
-    return launch_conv_f32_split_thr(x, w, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, workspace, workspace_bytes,
-                                     static_cast<hipStream_t>(stream));
+    return launch_conv_f32_split_thr(x, w, thr, y_f32, bits, N, H, W, C, O, k, stride, pad, products, workspace,
+                                     workspace_bytes, static_cast<hipStream_t>(stream));
 }
 size_t bnn_bwn_workspace_bytes(int C, int O, int k) {
     if (C < 1 || O < 1 || k < 1 || (long long)k * C > (1 << 16)) return 0;
@@ -575,9 +581,9 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 rc = L.bwn ? bnn_bwn_conv_thr(static_cast<const float*>(input), static_cast<const uint32_t*>(L.w0),
                                               static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,
                                               L.stride, L.pad, ws + pl.bwn_off, pl.bwn_bytes, stream)
-                           : bnn_conv_f32_split_thr(static_cast<const float*>(input), static_cast<const float*>(L.w0),
-                                                    static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d,
-                                                    L.k, L.stride, L.pad, ws + pl.bwn_off, pl.bwn_bytes, stream);
+                           : bnn_conv_f32_split_thr_ex(static_cast<const float*>(input), static_cast<const float*>(L.w0),
+                                                       static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c,
+                                                       L.d, L.k, L.stride, L.pad, 6, ws + pl.bwn_off, pl.bwn_bytes, stream);
                 if (!L.bwn && rc == BNN_ERR_UNSUPPORTED)       // filter bank too large for the split kernel
                     rc = bnn_conv_f32_thr(static_cast<const float*>(input), static_cast<const float*>(L.w0),
                                           static_cast<const float*>(L.t0), nullptr, obits, batch, L.a, L.b, L.c, L.d, L.k,

@@ -370,9 +370,11 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwn_staged_kernel(const
 // ------------------------------------------------------------------------------------------ direct
 // MT x NT accumulator tiles of 32x32 per wave, WAVES waves per workgroup (they share the weights in LDS); the
 // workgroup covers NT*32 output channels and is persistent: its waves stride over the groups of MT*32 output pixels.
-// NPL: weight planes -- 1: +1/-1 weights (one bf16 value each); 3: real-valued weights split into three bf16 terms,
-// every one of the nine input-term x weight-term products is then formed, so each product is exact here too.
-template <int MT, int NT, int WAVES, int NPL>
+// NPL: weight planes -- 1: +1/-1 weights (one bf16 value each); 3: real-valued weights split into three bf16 terms.
+// TERMS (NPL == 3): 9 -- every input-term x weight-term product is formed, so each product x * w is exact here too;
+// 6 -- without the three smallest (middle x low, low x middle, low x low), which together lie below 2^-23 of the
+// product: as accurate as rounding each product to fp32, two thirds of the matrix work.
+template <int MT, int NT, int WAVES, int NPL, int TERMS = 3 * NPL>
 __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
                                                        const float* __restrict__ thr, float* __restrict__ y,
                                                        uint32_t* __restrict__ bits, int N, int H, int W, int C, int O,
@@ -501,7 +503,7 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
                 const uint4 xs[3] = {s.h, s.m, s.l};
                 // smallest terms first: (input term, weight term) pairs in order of decreasing index sum
 #pragma unroll
-                for (int sum = 2 + (NPL - 1); sum >= 0; --sum)
+                for (int sum = (TERMS == 3 * NPL ? 2 + (NPL - 1) : 2); sum >= 0; --sum)
 #pragma unroll
                     for (int px = 2; px >= 0; --px) {
                         const int pw = sum - px;
@@ -579,7 +581,7 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     }
 }
 
-template <int MT, int NT, int WAVES, int NPL>
+template <int MT, int NT, int WAVES, int NPL, int TERMS = 3 * NPL>
 int launch_bwn_direct(const float* x, const void* weights, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
                       int C, int O, int k, int stride, int pad, int P, int Q, void* workspace, size_t workspace_bytes,
                       hipStream_t s) {
@@ -591,7 +593,7 @@ int launch_bwn_direct(const float* x, const void* weights, const float* thr, flo
     if (lds_bytes > 160 * 1024) return BNN_ERR_UNSUPPORTED;
     if (workspace_bytes < lds_bytes * col_tiles) return BNN_ERR_WORKSPACE;
     if (lds_bytes > 64 * 1024) {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_conv_kernel<MT, NT, WAVES, NPL>),
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwn_conv_kernel<MT, NT, WAVES, NPL, TERMS>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr != hipSuccess) return BNN_ERR_DEVICE;
     }
@@ -614,7 +616,7 @@ int launch_bwn_direct(const float* x, const void* weights, const float* thr, flo
     }
     const long long wgs = min(cdiv(groups, WAVES), (long long)max(1, cus / col_tiles));
     dim3 grid((unsigned)wgs, (unsigned)col_tiles);
-    hipLaunchKernelGGL((bwn_conv_kernel<MT, NT, WAVES, NPL>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, N, H, W, C, O, k, stride,
+    hipLaunchKernelGGL((bwn_conv_kernel<MT, NT, WAVES, NPL, TERMS>), grid, dim3(WAVES * 64), lds_bytes, s, x, wexp, thr, y, bits, N, H, W, C, O, k, stride,
                        pad, P, Q, make_fastdiv(P * Q), make_fastdiv(Q));
     return check_launch();
 }
@@ -718,8 +720,11 @@ size_t conv_f32_split_workspace_bytes(int C, int O, int k) {
 }
 
 int launch_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
-                              int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes, hipStream_t s) {
+                              int C, int O, int k, int stride, int pad, int products, void* workspace, size_t workspace_bytes,
+                              hipStream_t s) {
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    if (products == 6)
+        return launch_bwn_direct<2, 2, 8, 3, 6>(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
     return launch_bwn_direct<2, 2, 8, 3>(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
 }
 

@@ -136,8 +136,8 @@ int launch_conv_f32_thr(const float* x, const float* w, const float* thr, float*
 size_t bwn_workspace_bytes(int C, int O, int k);
 size_t conv_f32_split_workspace_bytes(int C, int O, int k);
 int launch_conv_f32_split_thr(const float* x, const float* w, const float* thr, float* y, uint32_t* bits,
-                              int N, int H, int W, int C, int O, int k, int stride, int pad, void* workspace,
-                              size_t workspace_bytes, hipStream_t s);
+                              int N, int H, int W, int C, int O, int k, int stride, int pad, int products,
+                              void* workspace, size_t workspace_bytes, hipStream_t s);
 int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits,
                         int N, int H, int W, int C, int O, int k, int stride, int pad, void* workspace,
                         size_t workspace_bytes, hipStream_t s);

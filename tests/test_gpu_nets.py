@@ -279,22 +279,25 @@ def test_persistent_bits_input_and_limits(bnn, orc):
 @pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
                                    (2, 32, 32, 3, 64, 7, 4, 3), (1, 8, 8, 2, 33, 1, 1, 0), (5, 64, 64, 3, 64, 7, 4, 3),
                                    (2, 33, 31, 3, 130, 3, 1, 1)])
-def test_conv_f32_split_shapes(bnn, orc, shape):
-    # the fp32 first layer on the bf16 matrix cores (three-way exact split of inputs and weights, nine products)
+@pytest.mark.parametrize("products", [9, 6])
+def test_conv_f32_split_shapes(bnn, orc, shape, products):
+    # the fp32 first layer on the bf16 matrix cores (three-way exact split of inputs and weights; all nine term
+    # products, or the six that reach fp32 precision)
     N, H, W, C, O, k, st, pad = shape
     rng = np.random.default_rng(sum(shape) + 3)
     x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
     w = rng.normal(0, 0.05, size=(O, k, k, C)).astype(np.float32)
     thr = rng.normal(0, 0.05, size=O).astype(np.float32)
-    bits, y = bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad, want_f32=True)
+    bits, y = bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad, want_f32=True, products=products)
     ref = orc.conv_f32(x, w, st, pad)
     tol = 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))
     assert host(y).shape == ref.shape
     assert (np.abs(host(y) - ref) <= tol).all()
-    # far tighter in fact: the products are exact, only the fp32 additions round
+    # far tighter in fact: the products are exact (or, with six, as good as rounded to fp32), the fp32 additions round
     assert np.abs(host(y) - ref).max() <= 2e-6 * np.abs(w).max() * np.sqrt(k * k * C) * 4
     assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
-    assert np.array_equal(words(bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad)), words(bits))
+    assert np.array_equal(words(bnn.conv_f32_split_thr(to_dev(x), to_dev(w), to_dev(thr), st, pad, products=products)),
+                          words(bits))
 
 
 def test_conv_f32_split_exact_products(bnn, orc):
