@@ -32,7 +32,7 @@ def mlp_forward(images_u8: np.ndarray, params: dict, keep: bool = False):
 
 
 def resnet18_forward(x_f32: np.ndarray, params: dict, stem_bits: np.ndarray | None = None,
-                     tier: int = 0, keep: bool = False):
+                     tier: int = 0, keep: bool = False, pad_mode: int = orc.PAD_MINUS_ONE):
     """ResNet-18-shaped BNN (paper Table 5 structure 64C7/4-4x64C3-4x128C3-4x256C3-4x512C3).
 
     Reading used by this build (the paper leaves the details open):
@@ -43,7 +43,8 @@ def resnet18_forward(x_f32: np.ndarray, params: dict, stem_bits: np.ndarray | No
                shortcut = R_in for stride-1 blocks, bconv1x1(x, Wd, stride 2, pad 0) for the
                three stride-2 blocks (int32); y = (S >= thr2); R_out = S.
                The residual stays full precision (Sec. 6.1), here int32, and is added before
-               the threshold.  Out-of-frame inputs count as -1.
+               the threshold.  Out-of-frame inputs count as -1, or, with ``pad_mode`` =
+               PAD_EXCLUDE, contribute nothing in any convolution of a block (Sec. 5.3).
       head   : pooled = sum of +1/-1 of the last y over the 7x7 positions (exact integer);
                logits = fp32 FC(pooled / 49).
     ``stem_bits`` replaces the oracle's own x0 (used to continue from the GPU's stem bits when a
@@ -60,11 +61,11 @@ def resnet18_forward(x_f32: np.ndarray, params: dict, stem_bits: np.ndarray | No
     R = orc.unpack_pm1(x.reshape(-1, cw), C).astype(np.int32).reshape(N, H, W_, C)
     for b, blk in enumerate(params["blocks"]):
         cin, cout, stride = blk["cin"], blk["cout"], blk["stride"]
-        v1 = orc.bconv(x, blk["W1"], cin, stride, 1, orc.PAD_MINUS_ONE, tier=tier)
+        v1 = orc.bconv(x, blk["W1"], cin, stride, 1, pad_mode, tier=tier)
         h = orc.threshold_pack(v1, blk["thr1"])
-        v2 = orc.bconv(h, blk["W2"], cout, 1, 1, orc.PAD_MINUS_ONE, tier=tier)
+        v2 = orc.bconv(h, blk["W2"], cout, 1, 1, pad_mode, tier=tier)
         if "Wd" in blk:
-            shortcut = orc.bconv(x, blk["Wd"], cin, stride, 0, orc.PAD_MINUS_ONE, tier=tier)
+            shortcut = orc.bconv(x, blk["Wd"], cin, stride, 0, pad_mode, tier=tier)     # pad 0: the modes agree
         else:
             shortcut = R
         S = v2 + shortcut

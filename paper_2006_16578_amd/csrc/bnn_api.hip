@@ -198,7 +198,7 @@ Plan plan(bnn_net* net, int batch) {
         }
         L.bits_off = off;
         size_t bytes = (size_t)batch * H * W * L.words_per_row * 4;
-        if (L.kind == bnn_net::BLOCK) bytes *= 2;      // hidden bits h of the block, then its output
+        if (L.kind == bnn_net::BLOCK) bytes = 2 * align256(bytes);   // hidden bits h of the block, then (aligned) its output
         off += align256(bytes);
         if (L.kind == bnn_net::BLOCK || L.kind == bnn_net::IN_CONV_F32 || L.kind == bnn_net::CONV)
             max_resid = max(max_resid, ((size_t)batch * H * W + 32) * C * 4);   // + 32 rows: blocked 16-bit sums pad rows
@@ -617,7 +617,7 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 break;
             case bnn_net::BLOCK: {
                 uint32_t* hbits = obits;                                     // first half of the slot
-                uint32_t* ybits = obits + (size_t)batch * L.H * L.W * L.words_per_row;
+                uint32_t* ybits = obits + align256((size_t)batch * L.H * L.W * L.words_per_row * 4) / 4;
                 int32_t* Rnew = reinterpret_cast<int32_t*>(ws + pl.resid_off[(rslot + 1) % 3]);
                 // the block's sum is kept only if the next layer is a block that adds it back
                 const bool keep_sum = (i + 1 < net->layers.size()) && net->layers[i + 1].kind == bnn_net::BLOCK &&
@@ -718,7 +718,7 @@ int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int
     if (L.kind == bnn_net::HEAD || L.kind == bnn_net::IN_BITS || (L.kind == bnn_net::FC && !L.t0)) return BNN_ERR_INVALID_ARG;
     const uint32_t* p = reinterpret_cast<const uint32_t*>(net->last_ws + L.bits_off);
     const long long r = (long long)net->last_batch * L.H * L.W;
-    if (L.kind == bnn_net::BLOCK) p += (size_t)r * L.words_per_row;    // the block's output bits
+    if (L.kind == bnn_net::BLOCK) p += align256((size_t)r * L.words_per_row * 4) / 4;    // the block's output bits
     *bits = p; *rows = r; *words_per_row = L.words_per_row;
     return BNN_OK;
 }

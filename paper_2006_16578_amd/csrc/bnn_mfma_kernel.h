@@ -210,7 +210,8 @@ __device__ __forceinline__ void epilogue_generic(v16f (&acc)[MT][NT], const long
                 const int ylo = p * g.stride - g.pad, xlo = q * g.stride - g.pad;
                 const int vy = min(ylo + g.k, g.H) - max(ylo, 0);
                 const int vx = min(xlo + g.k, g.W) - max(xlo, 0);
-                corr = vy * vx * pad_tap;
+                // pad positions of the in-frame taps, plus what is not per tap (the fused second source's pad positions)
+                corr = vy * vx * pad_tap + (corr_all - g.taps * pad_tap);
             }
 #pragma unroll
             for (int j = 0; j < NT; ++j) {

@@ -40,23 +40,23 @@ def test_mlp(bnn, orc, batch, path):
     assert np.array_equal(scores, ref)
 
 
-def build_resnet(bnn, p, hw):
+def build_resnet(bnn, p, hw, pad_mode=0):
     net = bnn.Net()
     net.input_conv_f32(to_dev(p["stem_w"]), to_dev(p["stem_thr"]), hw, hw, 4, 3)
     for blk in p["blocks"]:
         net.add_block(to_dev(blk["W1"]), to_dev(blk["thr1"]), to_dev(blk["W2"]), to_dev(blk["thr2"]),
-                      to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"])
+                      to_dev(blk["Wd"]) if "Wd" in blk else None, blk["cin"], blk["cout"], blk["stride"], pad_mode)
     net.add_head_f32(to_dev(p["fc_w"]))
     return net
 
 
-def check_resnet(bnn, orc, p, x, hw, path, tier):
+def check_resnet(bnn, orc, p, x, hw, path, tier, pad_mode=0):
     """Protocol for a network whose first layer is fp32: the stem output must match within
     1e-4 * max(|o|, rms(o)); a stem bit may differ from the oracle's only where the oracle's value
     is that close to the threshold; the oracle's binarized chain is then run from the GPU's stem
     bits and every later bit tensor must match exactly; logits within the same fp32 tolerance."""
     xd = to_dev(x)
-    net = build_resnet(bnn, p, hw)
+    net = build_resnet(bnn, p, hw, pad_mode)
     logits = host(net.forward(xd, path=path))
     stem_bits_gpu = words(net.layer_bits(0)).reshape(x.shape[0], hw // 4, hw // 4, -1)
     # fp32 stem values
@@ -72,7 +72,7 @@ def check_resnet(bnn, orc, p, x, hw, path, tier):
         d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), C).reshape(stem_ref.shape) > 0
         assert (np.abs(stem_ref - p["stem_thr"])[d] <= tol[d]).all()
         print("stem bits inside the fp32 tolerance that differ:", int(d.sum()), flush=True)
-    tr = nets.resnet18_forward(x, p, stem_bits=stem_bits_gpu, tier=tier, keep=True)
+    tr = nets.resnet18_forward(x, p, stem_bits=stem_bits_gpu, tier=tier, keep=True, pad_mode=pad_mode)
     for b in range(len(p["blocks"])):
         got = words(net.layer_bits(b + 1)).reshape(tr["y%d" % b].shape)
         assert np.array_equal(got, tr["y%d" % b]), "block %d output bits" % b
@@ -87,6 +87,19 @@ def test_resnet_small(bnn, orc, path):
     p = wl.resnet18_params(blocks=blocks, classes=13, config=95)
     x = wl.resnet18_input(3, hw=32, config=95)
     check_resnet(bnn, orc, p, x, 32, path, tier=0)
+
+
+@pytest.mark.parametrize("pad_mode", [0, 1])
+@pytest.mark.parametrize("widths", [(64, 80, 80, 96), (64, 64, 128, 128)])
+def test_resnet_small_widths_and_padding(bnn, orc, widths, pad_mode):
+    # residual chains with channel counts that are not multiples of 32 (row-major 16-bit sums, pad bits inside the
+    # last word of a pixel) and with multiples of 32 (blocked sums), in both padding conventions; 5 images of 40x40
+    # make ragged 32-row blocks at every resolution
+    a, b, c, d = widths
+    blocks = ((64, a, 1), (a, b, 2), (b, c, 1), (c, d, 2), (d, d, 1))
+    p = wl.resnet18_params(blocks=blocks, classes=21, config=96)
+    x = wl.resnet18_input(5, hw=40, config=96)
+    check_resnet(bnn, orc, p, x, 40, 0, tier=0, pad_mode=pad_mode)
 
 
 def test_resnet18_batch8(bnn, orc):
