@@ -98,6 +98,8 @@ int bnn_bmm_thr_ex(const uint32_t* A, const uint32_t* B, const int32_t* thr, uin
  *   filt  [O][k][k][cw]   packed along C
  *   out   [N][P][Q][O]    int32,  P = (H + 2*pad - k)/stride + 1, Q likewise
  * pad_mode says what an out-of-frame x is (see BNN_PAD_*).  k*k*C <= BNN_MAX_K, k <= 32, pad < k.
+ * The images that 512 consecutive output pixels touch must hold less than 2 GiB of packed input
+ * ((511 / (P*Q) + 2) * H*W*cw*4 bytes), else BNN_ERR_UNSUPPORTED on the matrix-core path.
  * ---------------------------------------------------------------------------------------- */
 int bnn_bconv(const uint32_t* in, const uint32_t* filt, int32_t* out,
               int N, int H, int W, int C, int O, int k, int stride, int pad, int pad_mode, void* stream);

@@ -30,7 +30,10 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
         }
         // tw is a multiple of 4 words; a chunk is 8 words, so an odd number of 4-word groups
         // leaves the upper half-wave without data in the last chunk -> guarded variant
-        if (!mfma::offsets_fit(g)) return BNN_ERR_UNSUPPORTED;
+        if (!mfma::offsets_fit(g)) {     // leading dimensions beyond the direct kernel's 32-bit offsets
+            if (g.b_tiled) return BNN_ERR_UNSUPPORTED;
+            return mfma::launch_staged_tile<mfma::TileMid, 16, false>(A, B, g, e, s);
+        }
         if (g.tw % 8 == 0) return mfma::launch_shape<4, false, false>(A, B, g, e, s);
         return mfma::launch_shape<4, false, true>(A, B, g, e, s);
     }

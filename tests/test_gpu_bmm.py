@@ -185,3 +185,17 @@ def test_bmm_pretiled_weights(bnn, orc, shape):
 def test_probe_load_stride_runs(bnn):
     t = bnn.probe_load_stride(128, rows=256, iters=512)
     assert 1.0 < t < 1e5
+
+
+def test_wide_leading_dimensions(bnn, orc):
+    # rows of a much wider matrix (leading dimension 2^20 words): beyond the direct kernel's 32-bit lane offsets,
+    # the call must still be exact (it takes the LDS-staged kernel)
+    rng = np.random.default_rng(44)
+    M, N, K, ld = 3, 5, 200, 1 << 20
+    A = np.zeros((M, ld), np.uint32)
+    B = np.zeros((N, ld), np.uint32)
+    A[:, :8] = wl.random_bits(rng, (M,), K, ldw=8)
+    B[:, :8] = wl.random_bits(rng, (N,), K, ldw=8)
+    ref = orc.bmm(A[:, :8].copy(), B[:, :8].copy(), K)
+    for path in (0, 2):
+        assert np.array_equal(host(bnn.bmm(to_dev(A), to_dev(B), K, path=path)), ref)
