@@ -731,24 +731,18 @@ inline bool conv_stages_through_lds(const Geom& g) {
 }
 
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256
-// CUs (two workgroups each for the big tiles) enough workgroups -- unless the epilogue moves full
-// precision sums and K is short: then the call is bound by that traffic and by the waits for it, and the small
-// tile, with four times the resident workgroups, overlaps them with the matrix work of others.  Where that
-// pays was measured by same-run comparison of thresholds: for a matrix product below about 500 bits of K per
-// byte moved per output (2.5 P MAC/s against 4.5 TB/s); for the residual layers of a network (blocked 16-bit
-// sums, ResNet shapes) below 600 bits per byte read and 1200 per byte written; never for a convolution with
-// row-major int32 sums, where the big tile's wider stores win.
+// CUs (two workgroups each for the big tiles) enough workgroups -- unless a matrix product moves full-precision
+// sums and K is short: then the call is bound by that traffic (2.5 P MAC/s against 4.5 TB/s: below about 500 bits
+// of K per byte moved per output), and the small tile, with four times the resident workgroups, overlaps the waits
+// for it with the matrix work of others.  Convolutions never take the small tile for that reason: measured by
+// same-run comparison on the ResNet shapes, the big tiles win with row-major int32 sums (wider stores) and with
+// the blocked 16-bit sums of a layer chain alike, since a small-tile wave expands one word per operand for every
+// MFMA and the big ones a fraction of that.
 inline int pick_tile(const Geom& g, const Epi* e = nullptr) {
-    if (e != nullptr && (!g.conv || e->sums_tiled)) {
-        const int bytes_in = 4 * (e->resid != nullptr) + 2 * (e->resid16 != nullptr);
-        const int bytes_out = 4 * (e->out != nullptr) + 2 * (e->out16 != nullptr);
-        const long long per_in = g.conv ? 600 : 500, per_out = g.conv ? 1200 : 500;
-        // (a network layer with four or more rounds of big tiles keeps them: the small tile only wins where the
-        // big one also leaves the chip partly idle in its last round)
-        const bool many_big = g.conv && cdiv(g.rows, g.cols <= 64 ? TileTall::ROWS : TileBig::ROWS) *
-                                                cdiv(g.cols, g.cols <= 64 ? TileTall::COLS : TileBig::COLS) >= 2048;
-        if (bytes_in + bytes_out > 0 && (long long)g.taps * g.bits_tap < per_in * bytes_in + per_out * bytes_out &&
-            !many_big && cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
+    if (e != nullptr && !g.conv) {
+        const int bytes = 4 * (e->resid != nullptr) + 4 * (e->out != nullptr);
+        if (bytes > 0 && (long long)g.taps * g.bits_tap < 500LL * bytes &&
+            cdiv(g.rows, TileSmall::ROWS) * cdiv(g.cols, TileSmall::COLS) >= 2048)
             return 3;
     }
     if (g.cols <= 64) return (cdiv(g.rows, TileTall::ROWS) >= 256) ? 1 : 3;
