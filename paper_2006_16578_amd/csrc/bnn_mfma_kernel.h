@@ -723,11 +723,11 @@ int launch_tile(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 // Convolutions that the LDS-staged kernel takes (on any tile but the smallest): -1 padding, whole-word pixels of
 // 8 bytes or a multiple of 16 bytes, and a long K.  How long was measured in same-run comparisons (VGG and ResNet
 // shapes, the 64x64 sweep): pixels of a multiple of 32 bytes feed the direct kernel with 16-byte loads, and it wins
-// up to K = 8192 bits (with few slabs it has less fixed cost per workgroup); narrower pixels make it use 8- or
-// 4-byte loads, and the staged kernel wins from K = 2048 bits.
+// up to K = 10240 bits (with few slabs it has less fixed cost per workgroup); narrower pixels make it use 8- or
+// 4-byte loads, and the staged kernel wins from K = 4096 bits.
 inline bool conv_stages_through_lds(const Geom& g) {
     if (!g.conv || g.excl || g.bits_tap != g.tw * 32 || !(g.tw % 4 == 0 || g.tw == 2)) return false;
-    return g.taps * g.tw >= (g.tw % 8 == 0 ? 256 : 64);
+    return g.taps * g.tw >= (g.tw % 8 == 0 ? 320 : 128);
 }
 
 // 0: TileBig, 1: TileTall, 2: TileMid, 3: TileSmall.  The largest tile that still gives the 256

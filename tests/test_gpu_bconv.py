@@ -52,12 +52,13 @@ def test_small_shapes(bnn, orc, pname, path, pad_mode):
 
 
 # ragged shapes that select the LDS-staged convolution kernels (16-byte pixels and 8-byte pixels)
-STAGED = [(5, 60, 60, 128, 130, 5, 1, 2, "mfma_fp4_conv_lds_wg128x128"),
-          (8, 70, 70, 64, 100, 7, 1, 3, "mfma_fp4_conv_lds_wg128x128"),
+STAGED = [(5, 60, 60, 128, 130, 7, 1, 3, "mfma_fp4_conv_lds_wg128x128"),
+          (8, 70, 70, 64, 100, 9, 1, 4, "mfma_fp4_conv_lds_wg128x128"),
           (9, 57, 57, 512, 300, 3, 2, 1, "mfma_fp4_conv_wg64x64"),
-          (33, 40, 40, 384, 70, 3, 1, 1, "mfma_fp4_conv_lds_wg128x128"),
-          (70, 58, 58, 384, 40, 3, 1, 1, "mfma_fp4_conv_lds_wg512x64"),
-          (64, 64, 64, 128, 256, 5, 1, 2, "mfma_fp4_conv_lds_wg256x128")]
+          (33, 40, 40, 384, 70, 5, 1, 2, "mfma_fp4_conv_lds_wg128x128"),
+          (70, 58, 58, 384, 40, 5, 1, 2, "mfma_fp4_conv_lds_wg512x64"),
+          (5, 60, 60, 256, 130, 7, 1, 3, "mfma_fp4_conv_lds_wg128x128"),
+          (64, 64, 64, 128, 256, 7, 1, 3, "mfma_fp4_conv_lds_wg256x128")]
 
 
 @pytest.mark.parametrize("shape", STAGED)
