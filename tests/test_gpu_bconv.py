@@ -39,7 +39,11 @@ SMALL = [  # N, H, W, C, O, k, stride, pad
     (1, 1, 1, 1, 1, 1, 1, 0), (1, 3, 3, 1, 1, 3, 1, 1), (2, 5, 4, 3, 3, 3, 1, 1), (2, 5, 4, 32, 3, 3, 2, 1),
     (2, 7, 6, 33, 5, 3, 1, 1), (3, 8, 8, 64, 40, 3, 1, 1), (2, 9, 7, 96, 33, 3, 2, 1), (2, 6, 6, 128, 64, 1, 2, 0),
     (1, 11, 10, 160, 70, 5, 2, 2), (2, 12, 12, 256, 96, 3, 1, 1), (1, 7, 7, 512, 130, 3, 1, 1),
-    (5, 14, 14, 64, 128, 3, 2, 1), (3, 10, 9, 192, 65, 3, 1, 0), (2, 8, 8, 320, 32, 1, 1, 0)]
+    (5, 14, 14, 64, 128, 3, 2, 1), (3, 10, 9, 192, 65, 3, 1, 0), (2, 8, 8, 320, 32, 1, 1, 0),
+    # 3x3 windows of 64 / 128 / 256 / 512 channels (the unrolled form) without padding, with pad 2, with images
+    # smaller than the window, with stride 3
+    (2, 9, 8, 64, 33, 3, 1, 0), (2, 9, 8, 128, 33, 3, 2, 2), (1, 2, 2, 256, 8, 3, 1, 1), (2, 11, 13, 512, 64, 3, 3, 2),
+    (3, 1, 5, 128, 40, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("pad_mode", [0, 1])
