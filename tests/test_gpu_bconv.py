@@ -134,3 +134,35 @@ def test_general_bconv_f32(bnn, orc, shape, pad_mode):
     f = rng.normal(size=(O, k, k, C)).astype(np.float32)
     got = host(bnn.bconv_general_f32(to_dev(x), to_dev(f), st, pad, pad_mode))
     assert got.dtype == np.float32 and np.array_equal(got, orc.general_bconv_f32(x, f, st, pad, pad_mode))
+
+
+def _random_conv_shapes(seed, count):
+    """Seeded random convolution shapes inside the documented limits, biased to the cases the kernels branch on:
+    channel counts around multiples of 32 / 64 / 128 / 256, windows 1..7, strides 1..3, every legal padding."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        C = int(rng.choice([1, 31, 32, 33, 64, 65, 96, 128, 160, 192, 256, 257, 384, 512]))
+        k = int(rng.choice([1, 2, 3, 3, 3, 4, 5, 7]))
+        st = int(rng.integers(1, 4))
+        pad = int(rng.integers(0, k))
+        H, W = int(rng.integers(1, 15)), int(rng.integers(1, 15))
+        if H + 2 * pad < k or W + 2 * pad < k or k * k * C > 20000:
+            continue
+        N = int(rng.integers(1, 5))
+        O = int(rng.choice([1, 7, 32, 33, 64, 70, 128, 130]))
+        shapes.append((N, H, W, C, O, k, st, pad))
+    return shapes
+
+
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_random_shapes_all_paths(bnn, orc, seed):
+    # 60 random shapes per seed: int32 sums, threshold -> bits, residual in and sum out, both padding conventions,
+    # on the automatic choice and on both explicit paths
+    for idx, (N, H, W, C, O, k, st, pad) in enumerate(_random_conv_shapes(seed, 60)):
+        print("conv", N, H, W, C, O, k, st, pad, flush=True)
+        case = wl.bconv_case(seed, N, H, W, C, O, k, st, pad, index0=10 * idx)
+        for pad_mode in (0, 1):
+            ref = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode)
+            for path in (0, 1, 2):
+                run_conv(bnn, orc, case, path, pad_mode, ref=ref)

@@ -199,3 +199,23 @@ def test_wide_leading_dimensions(bnn, orc):
     ref = orc.bmm(A[:, :8].copy(), B[:, :8].copy(), K)
     for path in (0, 2):
         assert np.array_equal(host(bnn.bmm(to_dev(A), to_dev(B), K, path=path)), ref)
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_shapes_all_paths(bnn, orc, seed):
+    # 30 random shapes per seed (M, N around tile edges, K around word / 128-bit / chunk edges), int32 and bits out
+    rng = np.random.default_rng(seed)
+    for idx in range(30):
+        M = int(rng.choice([1, 5, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 300]))
+        N = int(rng.choice([1, 7, 31, 32, 33, 64, 65, 100, 128, 129, 260]))
+        K = int(rng.choice([1, 31, 32, 33, 64, 100, 127, 128, 129, 255, 256, 257, 384, 500, 512, 1000, 1024, 1100, 4096, 5000]))
+        print("bmm", M, N, K, flush=True)
+        ld = wl.round_up(wl.nwords(K), 4)
+        A = wl.random_bits(rng, (M,), K, ldw=ld)
+        B = wl.random_bits(rng, (N,), K, ldw=ld)
+        tau = wl.random_thresholds(rng, N, -40, 40)
+        ref = orc.bmm(A, B, K)
+        for path in (0, 1, 2):
+            assert np.array_equal(host(bnn.bmm(to_dev(A), to_dev(B), K, path=path)), ref)
+            bits = words(bnn.bmm_thr(to_dev(A), to_dev(B), to_dev(tau), K, path=path))
+            assert np.array_equal(bits, orc.threshold_pack(ref, tau, ldb_w=bits.shape[1]))
