@@ -166,3 +166,21 @@ def test_random_shapes_all_paths(bnn, orc, seed):
             ref = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode)
             for path in (0, 1, 2):
                 run_conv(bnn, orc, case, path, pad_mode, ref=ref)
+
+
+# shapes large enough for each of the bigger workgroup tiles of the direct kernel (512x64, 256x128, 128x128), with
+# ragged last tiles, odd channel counts, strides and paddings; residual in and sum out as well
+LARGER = [(37, 61, 59, 64, 64, 3, 1, 1, "mfma_fp4_conv_wg512x64"), (41, 60, 58, 96, 40, 3, 1, 0, "mfma_fp4_conv_wg512x64"),
+          (29, 61, 60, 128, 128, 3, 1, 1, "mfma_fp4_conv_wg256x128"), (50, 90, 88, 160, 130, 3, 2, 2, "mfma_fp4_conv_wg256x128"),
+          (13, 59, 57, 256, 100, 3, 1, 1, "mfma_fp4_conv_wg128x128"), (11, 63, 61, 33, 128, 2, 1, 1, "mfma_fp4_conv_wg128x128")]
+
+
+@pytest.mark.parametrize("shape", LARGER)
+def test_larger_tiles_direct_kernel(bnn, orc, shape):
+    N, H, W, C, O, k, st, pad, kernel = shape
+    assert bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad) == kernel
+    case = wl.bconv_case(95, N, H, W, C, O, k, st, pad, index0=C % 89)
+    for pad_mode in (0, 1):
+        ref1 = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode, tier=1)
+        assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, st, pad, pad_mode, N - 1, 1), ref1[N - 1:])
+        run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)
