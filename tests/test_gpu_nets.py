@@ -102,6 +102,27 @@ def test_resnet_small_widths_and_padding(bnn, orc, widths, pad_mode):
     check_resnet(bnn, orc, p, x, 40, 0, tier=0, pad_mode=pad_mode)
 
 
+@pytest.mark.parametrize("seed", [301, 302, 303, 304, 305, 306])
+def test_resnet_random_chains(bnn, orc, seed):
+    # random residual chains: widths on and off multiples of 32, stride-1 and stride-2 blocks with and without a
+    # 1x1 shortcut, random batch and image size, both padding conventions
+    rng = np.random.default_rng(seed)
+    widths = [int(rng.choice([32, 64, 80, 96, 128, 160])) for _ in range(5)]
+    blocks, cin = [], widths[0]
+    for b in range(int(rng.integers(3, 6))):
+        cout = cin if rng.random() < 0.5 else int(rng.choice(widths))
+        stride = 2 if (cout != cin and rng.random() < 0.6) else 1
+        blocks.append((cin, cout, stride))
+        cin = cout
+    hw = int(rng.choice([24, 40, 56]))
+    batch = int(rng.integers(1, 7))
+    pad_mode = int(rng.integers(0, 2))
+    print("chain", blocks, "hw", hw, "batch", batch, "pad_mode", pad_mode, flush=True)
+    p = wl.resnet18_params(blocks=tuple(blocks), classes=int(rng.integers(3, 40)), config=seed)
+    x = wl.resnet18_input(batch, hw=hw, config=seed)
+    check_resnet(bnn, orc, p, x, hw, 0, tier=1, pad_mode=pad_mode)
+
+
 def test_resnet18_batch8(bnn, orc):
     p = wl.resnet18_params()
     x = wl.resnet18_input(8)
