@@ -411,6 +411,46 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
         epilogue_chain<MT, NT>(acc, m0, n0, lane, g, e, corr_all, thi, cok, fetched);
         return;
     }
+    if (e.out != nullptr && e.bits == nullptr && e.out16 == nullptr && e.resid == nullptr && e.resid16 == nullptr &&
+        e.resid_bits == nullptr && !row_corr) {
+        // Sums only (int32, or the same values as fp32): blocks of 32 x 32 that lie inside the matrix are stored
+        // without per-element tests, from a scalar base per accumulator register (its row) plus one 32-bit offset
+        // per lane (its column and half) -- no vector address arithmetic; the edge blocks test every element.
+        const int half = lane >> 5;
+        const long long m0u = ((long long)__builtin_amdgcn_readfirstlane((int)(m0 >> 32)) << 32) |
+                              (uint32_t)__builtin_amdgcn_readfirstlane((int)m0);          // wave-uniform, made scalar
+        const int n0u = __builtin_amdgcn_readfirstlane(n0);
+        const float corrf = (float)corr_all;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const long long rbase = m0u + 32 * i;
+            if (rbase >= g.rows) break;
+            const bool rows_in = rbase + 32 <= g.rows;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int cbase = n0u + 32 * j;
+                const uint32_t lane_off = (uint32_t)((4 * half * e.ldc + l32) * 4);
+                if (rows_in && cbase + 32 <= g.cols) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        char* row_base = reinterpret_cast<char*>(e.out + (rbase + 8 * (r >> 2) + (r & 3)) * (long long)e.ldc + cbase);
+                        const float v = acc[i][j][r] - corrf;            // exact: integers below 2^24
+                        *reinterpret_cast<int32_t*>(row_base + (size_t)lane_off) = e.out_f32 ? __float_as_int(v) : (int)v;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
+                        const int col = cbase + l32;
+                        const float v = acc[i][j][r] - corrf;
+                        if (row < g.rows && col < g.cols)
+                            e.out[row * (long long)e.ldc + col] = e.out_f32 ? __float_as_int(v) : (int)v;
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (e.resid != nullptr || e.resid16 != nullptr || e.resid_bits != nullptr)
         epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, fetched);
     else
