@@ -199,6 +199,15 @@ __global__ __launch_bounds__(256, TL::MINB) void mfma_staged_kernel(const uint32
                     for (int j = 0; j < NT; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                             ea[i], eb[j], acc[i][j], 4 /*A: E2M1*/, 4 /*B: E2M1*/, 0, 0, 0, 0);
+                if constexpr (FULL) {
+                    // ask the scheduler for an even mix: each MFMA followed by its share of the next K-step's
+                    // expansion (vector ALU), so that the matrix pipe and the vector ALU run side by side
+#pragma unroll
+                    for (int q = 0; q < MT * NT; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, (MT + NT) * 7 / (MT * NT), 0);          // VALU
+                    }
+                }
             }
         }
     };
