@@ -388,7 +388,8 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
     const int nruns = k * rpr;
     // one MFMA K-step takes two runs (one per half-wave); the step count is rounded up to a multiple of 3 (the
     // depth of the prefetch rotation), the added steps multiply by zero weights
-    const int nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
+    const int nreal = (nruns + 1) / 2;                       // steps that hold data
+    const int nsteps = (nreal + 2) / 3 * 3;
     const int last0 = seg >= 8 ? seg - 8 : 0;                // first float of the last run of a filter row
     const int rowlen = W * C;
     const long long total = (long long)N * H * rowlen;       // floats in x
@@ -542,9 +543,9 @@ __global__ __launch_bounds__(WAVES * 64) void bwn_conv_kernel(const float* __res
             next(run2);
             multiply(step, run0);
             next(run0);
-            multiply(step + 1, run1);
+            if (step + 1 < nreal) multiply(step + 1, run1);     // the padding steps of the last round only fetch
             next(run1);
-            multiply(step + 2, run2);
+            if (step + 2 < nreal) multiply(step + 2, run2);
         }
 
 #pragma unroll
