@@ -108,6 +108,32 @@ def test_cfg4_full_size(bnn, orc, which):
             run_conv(bnn, orc, case, path, pad_mode, ref=ref1, with_resid=(path == 0))
 
 
+@pytest.mark.parametrize("pad_mode", [0, 1])
+@pytest.mark.parametrize("pname,path", [("auto", 0)] + PATHS)
+def test_threshold_edge_values(bnn, orc, pname, path, pad_mode):
+    # thresholds at and beyond the range of the sums and at the ends of int32.  An all +1 image under all +1 /
+    # all -1 filters makes interior sums reach +k*k*C and -k*k*C exactly, so tau = +-K decides real equalities
+    imin, imax = np.iinfo(np.int32).min, np.iinfo(np.int32).max
+    for (N, H, W, C, O, k, st, pad) in ((2, 9, 8, 64, 48, 3, 1, 1), (1, 12, 12, 128, 40, 3, 1, 1), (2, 7, 7, 40, 33, 3, 2, 1),
+                                        (1, 6, 6, 96, 64, 1, 1, 0)):
+        case = wl.bconv_case(95, N, H, W, C, O, k, st, pad, index0=C % 83)
+        K = k * k * C
+        ones = np.full(wl.nwords(C), 0xFFFFFFFF, dtype=np.uint32)
+        if C % 32:
+            ones[-1] = np.uint32((1 << (C % 32)) - 1)
+        case["x"][0] = ones                                  # image 0 is all +1
+        edge = [K, K + 1, -K, -K - 1, K - 1, -K + 1, imin, imax, imin + 1, imax - 1, 0, 1 << 24, -(1 << 24)]
+        for j, t in enumerate(edge):
+            case["tau"][j] = t
+            case["tau"][O - 1 - j] = t
+            case["filt"][j] = ones if j % 2 == 0 else 0
+            case["filt"][O - 1 - j] = 0 if j % 2 == 0 else ones
+        ref = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode)
+        assert (ref == K).any() and (ref == -K).any()
+        print("edge thresholds conv", N, H, W, C, O, k, st, pad, pname, pad_mode, flush=True)
+        run_conv(bnn, orc, case, path, pad_mode, ref=ref)
+
+
 def test_error_codes(bnn):
     x = torch.zeros((1, 4, 4, 1), dtype=torch.int32, device="cuda")
     f = torch.zeros((2, 3, 3, 1), dtype=torch.int32, device="cuda")

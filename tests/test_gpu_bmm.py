@@ -102,8 +102,9 @@ def test_sweep_fc(bnn, orc, name):
 
 @pytest.mark.parametrize("n", [8192, 16384])
 def test_sweep_large_auto_path(bnn, orc, n):
-    # the sizes bench.py times, in the launch configuration it uses (automatic path): the fused
-    # threshold bits in full against tier 1, int32 on sampled rows against tier 0
+    # the sizes bench.py times, in the launch configuration it uses (automatic path): the fused threshold bits
+    # AND the whole int32 matrix against the packed tier-1 oracle, tier 1 itself against the naive tier 0 on
+    # sampled rows
     case = wl.cfg2_case("sq%d" % n)
     A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
     bits = words(bnn.bmm_thr(A, B, tau, n))
@@ -111,12 +112,37 @@ def test_sweep_large_auto_path(bnn, orc, n):
     torch.cuda.synchronize()
     ref1 = orc.bmm(case["A"], case["B"], n, tier=1)
     assert np.array_equal(bits, orc.threshold_pack(ref1, case["tau"], ldb_w=bits.shape[1]))
-    del ref1
     for r0 in (0, n // 3, n - 8):
-        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], n, r0, 8), host(C[r0:r0 + 8]))
-    # properties that hold at any size
-    Ch = host(C)
-    assert ((Ch - n) % 2 == 0).all() and (np.abs(Ch) <= n).all()
+        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], n, r0, 8), ref1[r0:r0 + 8])
+    step = 2048                                            # row chunks keep the host copies small
+    for r0 in range(0, n, step):
+        got = host(C[r0:r0 + step])
+        assert np.array_equal(got, ref1[r0:r0 + step]), "int32 rows %d..%d: %d wrong" % (
+            r0, r0 + step, int((got != ref1[r0:r0 + step]).sum()))
+
+
+@pytest.mark.parametrize("pname,path", [("auto", 0)] + PATHS)
+def test_threshold_edge_values(bnn, orc, pname, path):
+    # thresholds at and beyond the range of the sums, and at the ends of int32: columns whose B row equals or
+    # complements an A row make the sums reach +K and -K exactly, so tau = K (bit 1), K + 1 (bit 0), -K (1),
+    # -K - 1 (1) all decide a real equality; INT_MAX is never reached, INT_MIN always
+    imin, imax = np.iinfo(np.int32).min, np.iinfo(np.int32).max
+    for (M, N, K) in ((70, 96, 100), (130, 64, 1024), (33, 40, 4100), (300, 300, 777)):
+        case = wl.bmm_case(94, M, N, K, index0=K % 91)
+        edge = [K, K + 1, -K, -K - 1, K - 1, -K + 1, imin, imax, imin + 1, imax - 1, 0, 1, -1, 1 << 24, -(1 << 24), (1 << 24) + 1]
+        for j, t in enumerate(edge):
+            case["tau"][j] = t
+            case["tau"][N - 1 - j] = t
+            case["B"][j] = case["A"][j % M] if j % 2 == 0 else ~case["A"][j % M]
+            case["B"][N - 1 - j] = ~case["A"][(j + 3) % M] if j % 2 == 0 else case["A"][(j + 3) % M]
+        kw = wl.nwords(K)
+        if K % 32:
+            case["B"][:, kw - 1] &= np.uint32((1 << (K % 32)) - 1)          # complemented rows: pad bits back to 0
+        case["B"][:, kw:] = 0
+        ref = orc.bmm(case["A"], case["B"], K)
+        assert (ref == K).any() and (ref == -K).any()
+        print("edge thresholds", M, N, K, pname, flush=True)
+        run_case(bnn, orc, case, path, ref=ref)
 
 
 def test_threshold_pack_and_packs(bnn, orc):

@@ -50,6 +50,18 @@ def build_resnet(bnn, p, hw, pad_mode=0):
     return net
 
 
+def first_layer_values(bnn, xd, w, thr, stride, pad):
+    """fp32 output of a real-weight first layer from the kernel bnn_net_forward runs for it: the bf16 split
+    kernel with six term products, or the fp32 matrix-core kernel when the filter bank does not fit it."""
+    try:
+        _, y = bnn.conv_f32_split_thr(xd, w, thr, stride, pad, want_f32=True, products=6)
+    except bnn.BnnError as e:
+        if e.status != -3:
+            raise
+        _, y = bnn.conv_f32_thr(xd, w, thr, stride, pad, want_f32=True)
+    return y
+
+
 def check_resnet(bnn, orc, p, x, hw, path, tier, pad_mode=0):
     """Protocol for a network whose first layer is fp32: the stem output must match within
     1e-4 * max(|o|, rms(o)); a stem bit may differ from the oracle's only where the oracle's value
@@ -59,19 +71,24 @@ def check_resnet(bnn, orc, p, x, hw, path, tier, pad_mode=0):
     net = build_resnet(bnn, p, hw, pad_mode)
     logits = host(net.forward(xd, path=path))
     stem_bits_gpu = words(net.layer_bits(0)).reshape(x.shape[0], hw // 4, hw // 4, -1)
-    # fp32 stem values
-    _, y = bnn.conv_f32_thr(xd, to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 4, 3, want_f32=True)
+    # fp32 stem values, from the kernel the layer chain runs (bf16 x 3 split, six term products)
+    y = first_layer_values(bnn, xd, to_dev(p["stem_w"]), to_dev(p["stem_thr"]), 4, 3)
     stem_ref = orc.conv_f32(x, p["stem_w"], 4, 3)
     tol = 1e-4 * np.maximum(np.abs(stem_ref), np.sqrt((stem_ref.astype(np.float64) ** 2).mean()))
-    assert (np.abs(host(y) - stem_ref) <= tol).all()
+    err = np.abs(host(y) - stem_ref)
+    print("stem: max |gpu - oracle| = %.3e, max error / tolerance = %.3e" % (err.max(), (err / tol).max()), flush=True)
+    assert (err <= tol).all()
     ref_bits = orc.pack_f32(stem_ref, p["stem_thr"])
     diff = stem_bits_gpu ^ ref_bits
+    ndiff = 0
     if diff.any():
         # every differing bit must belong to a value inside the tolerance of its threshold
         C = p["stem_w"].shape[0]
         d = orc.unpack_pm1(diff.reshape(-1, diff.shape[-1]), C).reshape(stem_ref.shape) > 0
         assert (np.abs(stem_ref - p["stem_thr"])[d] <= tol[d]).all()
-        print("stem bits inside the fp32 tolerance that differ:", int(d.sum()), flush=True)
+        ndiff = int(d.sum())
+    print("stem bits that differ from the oracle's (all inside the fp32 tolerance): %d of %d" % (ndiff, stem_ref.size),
+          flush=True)
     tr = nets.resnet18_forward(x, p, stem_bits=stem_bits_gpu, tier=tier, keep=True, pad_mode=pad_mode)
     for b in range(len(p["blocks"])):
         got = words(net.layer_bits(b + 1)).reshape(tr["y%d" % b].shape)
@@ -201,11 +218,13 @@ def check_cnn(bnn, orc, spec, x, path, tier):
         ref0 = orc.bwn_conv_f32(x, L0["W"], L0["C"], L0["stride"], L0["pad"])
         cout = L0["W"].shape[0]
     else:
-        _, y = bnn.conv_f32_thr(xd, to_dev(L0["w"]), to_dev(L0["thr"]), L0["stride"], L0["pad"], want_f32=True)
+        y = first_layer_values(bnn, xd, to_dev(L0["w"]), to_dev(L0["thr"]), L0["stride"], L0["pad"])
         ref0 = orc.conv_f32(x, L0["w"], L0["stride"], L0["pad"])
         cout = L0["w"].shape[0]
     tol = 1e-4 * np.maximum(np.abs(ref0), np.sqrt((ref0.astype(np.float64) ** 2).mean()))
-    assert (np.abs(host(y) - ref0) <= tol).all()
+    err = np.abs(host(y) - ref0)
+    print("first layer: max |gpu - oracle| = %.3e, max error / tolerance = %.3e" % (err.max(), (err / tol).max()), flush=True)
+    assert (err <= tol).all()
     ref_bits = orc.pack_f32(ref0, L0["thr"])
     bits0 = words(net.layer_bits(0)).reshape(ref_bits.shape)
     diff = bits0 ^ ref_bits

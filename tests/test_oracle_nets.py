@@ -104,3 +104,98 @@ def test_cnn_forward_vgg_like_vs_torch(orc):
     a = np.where(v >= L[5]["thr"], 1, -1)
     assert (np_unpack_pm1(outs[5], 40) == a).all() and (outs[5][:, 2:] == 0).all()
     assert (outs[6] == a @ np_unpack_pm1(L[6]["W"], 40).T).all()
+
+
+def _torch_conv_pm1(x_pm1, f_words, C, stride, pad, pad_value):
+    """Independent +1/-1 convolution: torch float64 conv2d over an input explicitly padded with `pad_value`
+    (-1: out-of-frame inputs count as -1; 0: out-of-frame taps contribute nothing)."""
+    xt = torch.from_numpy(x_pm1.astype(np.float64)).permute(0, 3, 1, 2)
+    ft = torch.from_numpy(unpack4(f_words, C).astype(np.float64)).permute(0, 3, 1, 2)
+    xt = torch.nn.functional.pad(xt, (pad, pad, pad, pad), value=float(pad_value))
+    return torch.nn.functional.conv2d(xt, ft, stride=stride).permute(0, 2, 3, 1).numpy().astype(np.int64)
+
+
+def test_resnet_exclude_padding_vs_torch(orc):
+    # the paper's padding convention (Sec. 5.3: out-of-frame taps are excluded) through the whole residual
+    # chain: every convolution of every block against torch on an input padded with ZEROS.  Forgetting the
+    # pad mode on any one of the three convolutions of a block changes the border sums of that block.
+    blocks = ((64, 64, 1), (64, 96, 2), (96, 96, 1), (96, 128, 2))
+    p = wl.resnet18_params(blocks=blocks, classes=13, config=97)
+    x = wl.resnet18_input(2, hw=32, config=97)
+    tr = nets.resnet18_forward(x, p, keep=True, pad_mode=orc.PAD_EXCLUDE)
+    tr_m1 = nets.resnet18_forward(x, p, keep=True)
+    stem = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2),
+                                      torch.from_numpy(p["stem_w"]).double().permute(0, 3, 1, 2),
+                                      stride=4, padding=3).permute(0, 2, 3, 1).numpy()
+    assert np.abs(stem).min() > 1e-6
+    a = np.where(stem >= 0, 1, -1).astype(np.int64)
+    R = a.copy()
+    differs_from_minus_one = 0
+    for b, (cin, cout, st) in enumerate(blocks):
+        blk = p["blocks"][b]
+        v1 = _torch_conv_pm1(a, blk["W1"], cin, st, 1, 0)
+        h = np.where(v1 >= blk["thr1"], 1, -1)
+        assert (unpack4(tr["h%d" % b], cout) == h).all(), "block %d hidden bits" % b
+        v2 = _torch_conv_pm1(h, blk["W2"], cout, 1, 1, 0)
+        sc = _torch_conv_pm1(a, blk["Wd"], cin, st, 0, 0) if "Wd" in blk else R
+        S = v2 + sc
+        assert (tr["S%d" % b] == S).all(), "block %d sums" % b
+        a = np.where(S >= blk["thr2"], 1, -1)
+        assert (unpack4(tr["y%d" % b], cout) == a).all()
+        R = S
+        differs_from_minus_one += int((tr["S%d" % b] != tr_m1["S%d" % b]).sum())
+    assert differs_from_minus_one > 0                  # the two conventions are really different on this case
+    assert (tr["pooled"] == a.sum(axis=(1, 2))).all()
+    tr1 = nets.resnet18_forward(x, p, keep=True, tier=1, pad_mode=orc.PAD_EXCLUDE)
+    for key in tr:
+        assert np.array_equal(tr[key], tr1[key]), key
+
+
+def test_cnn_forward_bwn_and_blocks_vs_torch(orc):
+    # bwn first layer -> bconv -> identity block (residual starts from the bits) -> block with a 1x1 shortcut
+    # -> identity block (residual is the previous block's sum) -> fc, against an independent torch / numpy chain
+    rng = np.random.default_rng(77)
+
+    def block(cin, cout, stride):
+        b = {"op": "block", "cin": cin, "cout": cout, "stride": stride,
+             "W1": wl.random_bits(rng, (cout, 3, 3), cin), "thr1": wl.random_thresholds(rng, cout, -30, 30),
+             "W2": wl.random_bits(rng, (cout, 3, 3), cout), "thr2": wl.random_thresholds(rng, cout, -30, 30)}
+        if stride != 1 or cin != cout:
+            b["Wd"] = wl.random_bits(rng, (cout, 1, 1), cin)
+        return b
+
+    L = [{"op": "bwn", "W": wl.random_bits(rng, (40, 3, 3), 3), "thr": rng.normal(0, 0.3, size=40).astype(np.float32),
+          "C": 3, "stride": 1, "pad": 1},
+         {"op": "bconv", "W": wl.random_bits(rng, (64, 3, 3), 40), "thr": wl.random_thresholds(rng, 64, -30, 30),
+          "C": 40, "stride": 1, "pad": 1},
+         block(64, 64, 1), block(64, 96, 2), block(96, 96, 1),
+         {"op": "fc", "W": wl.random_bits(rng, 9, 5 * 5 * 96, wl.round_up(wl.nwords(5 * 5 * 96), 4)), "thr": None,
+          "K": 5 * 5 * 96}]
+    x = rng.uniform(-1, 1, size=(2, 10, 10, 3)).astype(np.float32)
+    outs = nets.cnn_forward(x, L, keep=True)
+    # first layer: weight bit 1 adds the input element, bit 0 subtracts it; zero padding; fp32 threshold
+    w_pm1 = torch.from_numpy(unpack4(L[0]["W"], 3).astype(np.float64)).permute(0, 3, 1, 2)
+    y0 = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2), w_pm1, padding=1)
+    y0 = y0.permute(0, 2, 3, 1).numpy()
+    assert np.abs(y0 - L[0]["thr"]).min() > 1e-5          # no value sits on its threshold in this case
+    a = np.where(y0 >= L[0]["thr"].astype(np.float64), 1, -1).astype(np.int64)
+    assert (unpack4(outs[0], 40) == a).all()
+    assert (outs[0][..., 1] >> 8 == 0).all()              # pad bits of the 40-channel pixel are zero
+    a = np.where(_torch_conv_pm1(a, L[1]["W"], 40, 1, 1, -1) >= L[1]["thr"], 1, -1)
+    assert (unpack4(outs[1], 64) == a).all()
+    R = a.copy()                                          # first block of the chain: residual = +1/-1 of its input
+    for i in (2, 3, 4):
+        B = L[i]
+        v1 = _torch_conv_pm1(a, B["W1"], B["cin"], B["stride"], 1, -1)
+        h = np.where(v1 >= B["thr1"], 1, -1)
+        v2 = _torch_conv_pm1(h, B["W2"], B["cout"], 1, 1, -1)
+        sc = _torch_conv_pm1(a, B["Wd"], B["cin"], B["stride"], 0, -1) if "Wd" in B else R
+        S = v2 + sc
+        a = np.where(S >= B["thr2"], 1, -1)
+        assert (unpack4(outs[i], B["cout"]) == a).all(), "block layer %d" % i
+        R = S
+    assert (outs[5] == a.reshape(2, -1) @ np_unpack_pm1(L[5]["W"], 5 * 5 * 96).T).all()
+    # the residual entering the last block really is the previous sum, not +-1: dropping it changes the bits
+    Lmut = [dict(l) for l in L]
+    Lmut[4] = dict(L[4]); Lmut[4]["Wd"] = wl.random_bits(rng, (96, 1, 1), 96)
+    assert not np.array_equal(nets.cnn_forward(x, Lmut, keep=True)[4], outs[4])
