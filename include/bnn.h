@@ -47,7 +47,8 @@ typedef enum bnn_status {
 /* Which arithmetic pipeline computes the +1/-1 products.  CDNA4 has no 1-bit matrix type, so the
  * library has two: XOR + popcount on the vector ALUs (Eq. 2 literally), and the matrix cores fed
  * with +1/-1 expanded on the fly to 4-bit floats (exact: products are +-1, sums stay below 2^24).
- * BNN_PATH_AUTO picks by shape. */
+ * BNN_PATH_AUTO takes the matrix cores (the faster pipeline for every shape measured) and falls back to the
+ * vector-ALU kernel for operands beyond the matrix-core kernels' 32-bit addressing range. */
 #define BNN_PATH_AUTO 0
 #define BNN_PATH_VALU 1
 #define BNN_PATH_MFMA 2
@@ -81,9 +82,8 @@ int bnn_bmm(const uint32_t* A, const uint32_t* B, int32_t* C,
 int bnn_bmm_ex(const uint32_t* A, const uint32_t* B, int32_t* C,
                int M, int N, int K, int lda_w, int ldb_w, int ldc, int path, void* stream);
 
-/* BMM with the threshold of Sec. 6.1 fused into the epilogue (Sec. 5.2, "the output can be
- * binarized before the store"): Cbits[i] bit j = (C[i][j] >= thr[j]); the int32 matrix never
- * reaches memory.
+/* BMM with the threshold of Sec. 6.1 applied in the epilogue, so that the int32 matrix is never
+ * stored (the bit-in / bit-out form of Sec. 5.2): Cbits[i] bit j = (C[i][j] >= thr[j]).
  *   thr   [N] int32;  Cbits [M][ldcb_w], ldcb_w >= ceil(N/32); pad bits up to ldcb_w*32 are 0,
  *   so Cbits is directly the A operand of the next layer. */
 int bnn_bmm_thr(const uint32_t* A, const uint32_t* B, const int32_t* thr, uint32_t* Cbits,
@@ -133,8 +133,6 @@ int bnn_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits,
 int bnn_pack_u8(const uint8_t* x, int thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
 /* bits[r] bit c = (x[r][c] >= thr[c]);  x [rows][cols] fp32, thr [cols] fp32. */
 int bnn_pack_f32(const float* x, const float* thr, uint32_t* bits, int64_t rows, int cols, int ldb_w, void* stream);
-/* out[r][c] = +1 / -1 as int32 from bits [rows][ldb_w]; out [rows][ldo].  Seeds the int32
- * residual chain from a bit tensor. */
 /* Pre-tiled weight operand, in the spirit of the paper's FSB format (Sec. 5.1: store the operand in the order the
  * matrix unit's tile loads consume it), with this chip's tile: rows are grouped by 32, and a group stores, for
  * every 16-byte step along K, the 16 bytes of its 32 rows back to back, so that the 32 lanes of an MFMA fragment
@@ -172,6 +170,8 @@ size_t bnn_bconv_general_workspace_bytes(int N, int H, int W, int C, int O, int 
 int bnn_bconv_general_f32(const float* in, const float* filt, float* out, int N, int H, int W, int C, int O, int k,
                           int stride, int pad, int pad_mode, void* workspace, size_t workspace_bytes, void* stream);
 
+/* out[r][c] = +1 / -1 as int32 from bits [rows][ldb_w]; out [rows][ldo] (e.g. to seed an int32
+ * residual tensor from a bit tensor). */
 int bnn_unpack_i32(const uint32_t* bits, int32_t* out, int64_t rows, int cols, int ldb_w, int ldo, void* stream);
 
 /* Max-pooling of packed +1/-1 activations: behind the threshold the maximum over a window is the
@@ -271,13 +271,24 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch,
  * barrier between layers).  Supported: an input layer (u8 or bits) followed by fully-connected layers only, at
  * most 8 of them; anything else returns BNN_ERR_UNSUPPORTED (use bnn_net_forward).  Same arguments, workspace
  * and results as bnn_net_forward.  The grid never exceeds what the device holds at once; a barrier
- * that is not reached by all workgroups within about 0.1 s makes every workgroup leave the kernel, the output
- * is then undefined.  Calls that overlap on one device must use different workspaces.
- * flags: 0, or BNN_PERSIST_NO_SYNC = skip the barriers -- the results are then UNDEFINED; it exists only to
- * measure what the barriers cost. */
+ * that is not reached by all workgroups within a few tenths of a second (other work holding the compute units)
+ * makes every workgroup leave the kernel: the output is then undefined and bnn_net_persistent_status reports
+ * it.  Calls that overlap on one device must use different workspaces.
+ * flags: 0, or a combination of
+ *   BNN_PERSIST_NO_SYNC          skip the barriers -- the results are then UNDEFINED; it exists only to measure
+ *                                what the barriers cost;
+ *   BNN_PERSIST_GIVE_UP_AT_ONCE  a workgroup that finds a barrier not yet complete gives up at its first poll
+ *                                (every workgroup still leaves the kernel normally) -- results UNDEFINED; it
+ *                                exists to exercise the time-out path and its status report. */
 #define BNN_PERSIST_NO_SYNC 1
+#define BNN_PERSIST_GIVE_UP_AT_ONCE 2
 int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch,
                                void* workspace, size_t workspace_bytes, int flags, void* stream);
+/* Whether the LAST bnn_net_forward_persistent of this net gave up at a barrier: *aborted = 1 (its output is
+ * undefined), else 0.  `stream` must be the stream of that forward, its workspace must still be allocated.
+ * This is the one call of the library that waits for the device (it synchronises `stream`).
+ * BNN_ERR_WORKSPACE when the net has not run a persistent forward. */
+int bnn_net_persistent_status(bnn_net* net, int* aborted, void* stream);
 /* After a forward: device pointer (inside the workspace) and shape of the packed bits produced by
  * layer `layer` (0 = input layer), for layer-by-layer checking.  words_per_row receives the row
  * length in words, rows the number of rows (batch, or batch*P*Q). */

@@ -28,7 +28,7 @@ EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_conv_f32_split_thr_ex", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
-           "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_layer_bits"]
+           "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_persistent_status", "bnn_net_layer_bits"]
 
 
 class BnnError(RuntimeError):
@@ -465,6 +465,9 @@ class Net:
         if thr is not None:
             _dev(thr, torch.int32, 1, "thr")
         N = W.shape[0]
+        if W.shape[1] != round_up(nwords(K), 4):
+            raise ValueError("W rows must be ceil(K/32) words rounded up to a multiple of 4 (%d), got %d"
+                             % (round_up(nwords(K), 4), W.shape[1]))
         _check(load().bnn_net_add_fc(self._h, _ptr(W), _ptr(thr), int(K), N), "bnn_net_add_fc")
         if thr is None:
             self._out_kind, self._out_cols = torch.int32, N
@@ -542,9 +545,21 @@ class Net:
                                           int(path), _stream(x)), "bnn_net_forward")
         return out
 
-    def forward_persistent(self, x, out=None, no_sync: bool = False):
-        """Same forward in one cooperative kernel launch (FC chains only).  no_sync skips the device-wide
-        barriers: results undefined, for timing the barriers only."""
+    def persistent_status(self, device=None) -> bool:
+        """True if the last forward_persistent gave up at a barrier (its output is then undefined).  Waits for the
+        current stream."""
+        aborted = ctypes.c_int(-1)
+        dev = self._ws.device if device is None else device
+        with torch.cuda.device(dev):
+            _check(load().bnn_net_persistent_status(self._h, ctypes.byref(aborted),
+                                                    ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)),
+                   "bnn_net_persistent_status")
+        return aborted.value != 0
+
+    def forward_persistent(self, x, out=None, no_sync: bool = False, give_up_at_once: bool = False):
+        """Same forward in one kernel launch (FC chains only).  no_sync skips the device-wide barriers (results
+        undefined, for timing the barriers only); give_up_at_once makes every barrier wait time out at its first
+        poll (results undefined, for testing the time-out report)."""
         _dev(x, self._in_dtype, None, "input")
         batch = x.shape[0]
         need = self.workspace_bytes(batch)
@@ -554,7 +569,8 @@ class Net:
             out = torch.empty((batch, self._out_cols), dtype=self._out_kind, device=x.device)
         with torch.cuda.device(x.device):
             _check(load().bnn_net_forward_persistent(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws),
-                                                     ctypes.c_size_t(self._ws.numel()), 1 if no_sync else 0, _stream(x)),
+                                                     ctypes.c_size_t(self._ws.numel()),
+                                                     (1 if no_sync else 0) | (2 if give_up_at_once else 0), _stream(x)),
                    "bnn_net_forward_persistent")
         return out
 

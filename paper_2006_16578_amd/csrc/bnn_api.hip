@@ -15,8 +15,13 @@ inline int round4(int v) { return (v + 3) / 4 * 4; }
 int dispatch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, int path, hipStream_t s) {
     switch (path) {
         case BNN_PATH_VALU: return launch_valu(A, B, g, e, s);
-        case BNN_PATH_AUTO:
         case BNN_PATH_MFMA: return launch_mfma(A, B, g, e, s);
+        case BNN_PATH_AUTO: {
+            // the matrix cores for everything they take; a shape beyond their kernels' 32-bit offsets (nothing has
+            // been enqueued then) goes to the vector-ALU kernel, which addresses with 64 bits
+            const int rc = launch_mfma(A, B, g, e, s);
+            return rc == BNN_ERR_UNSUPPORTED ? launch_valu(A, B, g, e, s) : rc;
+        }
         default: return BNN_ERR_INVALID_ARG;
     }
 }
@@ -120,6 +125,7 @@ struct bnn_net {
     std::vector<Layer> layers;
     // results of the last forward, for bnn_net_layer_bits
     const char* last_ws = nullptr; int last_batch = 0;
+    const unsigned* last_persist_sync = nullptr;   // barrier counter and abort flag of the last persistent forward
 };
 
 namespace {
@@ -162,6 +168,12 @@ Plan plan(bnn_net* net, int batch) {
             case bnn_net::FC:
                 if (H * W * words(C) * 32 != H * W * C && H * W != 1) { pl.rc = BNN_ERR_UNSUPPORTED; return pl; }
                 if (H * W * C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
+                // the flattened activation is the A operand as it lies in memory: its row stride (H*W pixels of
+                // words(C) words for a spatial producer) must satisfy the BMM's 128-bit row alignment
+                if (i > 0 && net->layers[i - 1].kind != bnn_net::FC && net->layers[i - 1].kind != bnn_net::IN_U8 &&
+                    net->layers[i - 1].kind != bnn_net::IN_BITS && (H * W * words(C)) % 4 != 0) {
+                    pl.rc = BNN_ERR_UNSUPPORTED; return pl;
+                }
                 H = W = 1; C = L.b; L.words_per_row = round4(words(C)); break;
             case bnn_net::CONV:
                 if (C != L.a) { pl.rc = BNN_ERR_INVALID_ARG; return pl; }
@@ -660,7 +672,7 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
 int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch, void* workspace,
                                size_t workspace_bytes, int flags, void* stream) {
     if (!net || !input || !output || batch < 1 || net->layers.size() < 2) return BNN_ERR_INVALID_ARG;
-    if (flags & ~BNN_PERSIST_NO_SYNC) return BNN_ERR_INVALID_ARG;
+    if (flags & ~(BNN_PERSIST_NO_SYNC | BNN_PERSIST_GIVE_UP_AT_ONCE)) return BNN_ERR_INVALID_ARG;
     for (size_t i = 0; i < net->layers.size(); ++i) {
         const bnn_net::Kind kd = net->layers[i].kind;
         const bool ok = (i == 0) ? (kd == bnn_net::IN_U8 || kd == bnn_net::IN_BITS) : (kd == bnn_net::FC);
@@ -707,8 +719,23 @@ int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, in
         }
         P.gx = (int)cdiv(batch, 64); P.gy = (int)cdiv(col_span, 64);
     }
+    net->last_persist_sync = reinterpret_cast<const unsigned*>(ws + pl.sync_off);
+    // a waiter polls about once a microsecond: 2^17 polls are a few tenths of a second
+    const int spin_limit = (flags & BNN_PERSIST_GIVE_UP_AT_ONCE) ? 0 : (1 << 17);
     return launch_persist_fc(pn, reinterpret_cast<unsigned*>(ws + pl.sync_off), (flags & BNN_PERSIST_NO_SYNC) ? 0 : 1,
-                             static_cast<hipStream_t>(stream));
+                             spin_limit, static_cast<hipStream_t>(stream));
+}
+
+int bnn_net_persistent_status(bnn_net* net, int* aborted, void* stream) {
+    if (!net || !aborted) return BNN_ERR_INVALID_ARG;
+    if (!net->last_persist_sync) return BNN_ERR_WORKSPACE;          // no persistent forward has been enqueued
+    unsigned flag = 0u;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&flag, net->last_persist_sync + 1, sizeof(flag), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return BNN_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return BNN_ERR_DEVICE;
+    *aborted = flag != 0u ? 1 : 0;
+    return BNN_OK;
 }
 
 int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int64_t* rows, int* words_per_row) {

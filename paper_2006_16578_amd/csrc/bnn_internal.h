@@ -110,7 +110,7 @@ struct PersistNet {
     int in_cols, in_thr, in_ldw;
     PersistLayer layer[PERSIST_MAX_LAYERS];
 };
-int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, hipStream_t s);
+int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, int spin_limit, hipStream_t s);
 
 int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);

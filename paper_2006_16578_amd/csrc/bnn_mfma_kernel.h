@@ -10,12 +10,14 @@
 // Products are +-1 and are accumulated in fp32, exact while |sum| < 2^24 (K <= 2^20 here).
 //
 // Operand delivery: in the 32x32x64 shape lane l supplies row (l % 32) and the 32 K-values of
-// K-group (l / 32) -- exactly one packed word.  Bits are so dense (64 B per row feed 8 MFMAs of
-// a 128x128 wave tile) that fragments are read straight from global memory / L2 into registers,
-// 16 B per lane at a time, with a register double buffer; there is no LDS stage to conflict on.
+// K-group (l / 32) -- exactly one packed word.  This file holds the DIRECT kernel: fragments are read
+// straight from global memory / L2 into registers, 4 to 16 bytes per lane and request, through a ring
+// of up to 8 chunk buffers that are all requested before the first multiply (the layers of a network
+// have short K: their time is memory latency and instruction issue, not the matrix pipe).  The
+// LDS-staged kernel for long K is in bnn_mfma_staged.h and shares the epilogue below.
 //
-// Tiling: a workgroup is 2 x 2 waves, a wave owns MT x NT accumulator tiles of 32 x 32
-// (MT = NT = 4: 128 x 128 per wave, 256 accumulator registers per lane).
+// Tiling: a workgroup is 4 waves, a wave owns MT x NT accumulator tiles of 32 x 32: 256 x 128 per
+// workgroup (waves 2 x 2, 4 x 2 tiles each), 512 x 64, 128 x 128 or 64 x 64 (see Tile below).
 //
 // Epilogue: in the 32x32 accumulator layout register r of lane l holds row 8*(r/4) + 4*(l/32)
 // + r%4, column l%32.  A threshold compare of one register therefore yields, as a 64-bit wave

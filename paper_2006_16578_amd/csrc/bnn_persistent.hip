@@ -84,19 +84,18 @@ __global__ void persist_clear_kernel(unsigned* ctr) {
 }  // namespace
 
 // ctr: two words of device memory (barrier counter, abort flag).  sync == 0 skips the barriers: the results
-// are then undefined; it exists to time the cost of the barriers alone.
-int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, hipStream_t s) {
-    static int max_wg = 0;
-    if (max_wg == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return BNN_ERR_DEVICE;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return BNN_ERR_DEVICE;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&persist_fc_kernel), 256, 0) !=
-            hipSuccess)
-            return BNN_ERR_DEVICE;
-        if (cus < 1 || per_cu < 1) return BNN_ERR_DEVICE;
-        max_wg = cus * per_cu;
-    }
+// are then undefined; it exists to time the cost of the barriers alone.  spin_limit: polls (each an s_sleep and
+// one device-scope load, about a microsecond) before a waiter gives up.
+int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, int spin_limit, hipStream_t s) {
+    // workgroups the current device holds at once (queried per call: the property belongs to the device)
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return BNN_ERR_DEVICE;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return BNN_ERR_DEVICE;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&persist_fc_kernel), 256, 0) !=
+        hipSuccess)
+        return BNN_ERR_DEVICE;
+    if (cus < 1 || per_cu < 1) return BNN_ERR_DEVICE;
+    const int max_wg = cus * per_cu;
     int want = 1;
     for (int l = 0; l < net.nlayers; ++l) want = max(want, net.layer[l].gx * net.layer[l].gy);
     if (net.in_u8 != nullptr) {
@@ -105,7 +104,6 @@ int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, hipStream_
     }
     const int grid = min(want, max_wg);
     hipLaunchKernelGGL(persist_clear_kernel, dim3(1), dim3(64), 0, s, ctr);
-    const int spin_limit = 1 << 20;                    // about 0.1 s of polling before a waiter gives up
     hipLaunchKernelGGL(persist_fc_kernel, dim3((unsigned)grid), dim3(256), 0, s, net, ctr, spin_limit, sync);
     return check_launch();
 }

@@ -301,10 +301,40 @@ def test_mlp_persistent(bnn, orc, batch):
     x = to_dev(imgs)
     for rep in range(3):                                   # the barrier counter is re-armed on every call
         got = host(net.forward_persistent(x))
+        assert not net.persistent_status(), "a barrier gave up in call %d" % rep
         assert np.array_equal(got, ref), "call %d" % rep
     for l in range(3):
         assert np.array_equal(words(net.layer_bits(l + 1)), hidden[l])
     assert np.array_equal(host(net.forward(x)), ref)       # and the per-layer path still agrees
+
+
+def test_persistent_timeout_is_reported(bnn, orc):
+    # the time-out path, forced from the host: with a poll limit of zero the first workgroup that finds a barrier
+    # incomplete raises the abort flag, every workgroup leaves the kernel normally, and the status call says so;
+    # the next ordinary call re-arms the barrier and is exact again
+    params = wl.mlp_params()
+    imgs = wl.mlp_images(2048)
+    net = build_mlp(bnn, params)
+    x = to_dev(imgs)
+    net.forward_persistent(x, give_up_at_once=True)
+    assert net.persistent_status()
+    got = host(net.forward_persistent(x))
+    assert not net.persistent_status()
+    assert np.array_equal(got, nets.mlp_forward(imgs, params))
+
+
+def test_fc_after_unaligned_spatial_layer_is_refused(bnn):
+    # an FC whose operand rows (H*W pixels of ceil(C/32) words) are not a multiple of 128 bits: refused when the
+    # workspace is sized, not part-way through the forward
+    rng = np.random.default_rng(8)
+    net = bnn.Net()
+    net.input_conv_f32(to_dev(rng.normal(size=(64, 3, 3, 3)).astype(np.float32)), to_dev(np.zeros(64, np.float32)), 3, 3, 1, 0)
+    net.add_fc(to_dev(wl.random_bits(rng, 10, 64, 4)), None, 64)         # 1x1x64: rows of 2 words
+    with pytest.raises(bnn.BnnError) as e:
+        net.workspace_bytes(4)
+    assert e.value.status == -3
+    with pytest.raises(ValueError):
+        bnn.Net().add_fc(to_dev(wl.random_bits(rng, 10, 64, 2)), None, 64)
 
 
 def test_persistent_bits_input_and_limits(bnn, orc):
