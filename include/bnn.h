@@ -267,6 +267,22 @@ int bnn_net_workspace_bytes(const bnn_net* net, int batch, size_t* bytes);
  * workspace: device memory of at least bnn_net_workspace_bytes(), 256-byte aligned. */
 int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch,
                     void* workspace, size_t workspace_bytes, int path, void* stream);
+/* bnn_net_forward for callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: the workspace is a fixed buffer of BNN_STATIC_WORKSPACE_BYTES that
+ * lives in the library's code object, one copy per GPU, held until the process ends.  The call (and
+ * bnn_static_workspace_init) calls no hipMalloc / hipFree or other allocating routine; inputs, output and weights
+ * are still the caller's.  Same kernels, arguments and results as bnn_net_forward.
+ *   BNN_ERR_WORKSPACE when bnn_net_workspace_bytes(net, batch) exceeds BNN_STATIC_WORKSPACE_BYTES (nothing is
+ *   enqueued): e.g. the 784-1024-1024-1024-10 MLP fits up to batch 65536, the ResNet-18-shaped network up to batch 12.
+ * Every call on a GPU uses that GPU's one buffer, which keeps the previous call's contents (nothing in it needs
+ * clearing: each forward writes what it reads): calls that OVERLAP on one GPU -- two streams, two threads -- race;
+ * calls on one stream are ordered and safe.  bnn_net_layer_bits afterwards points into that buffer.
+ * bnn_static_workspace_init looks up the buffer's address for the current device; call it once per device at
+ * set-up (outside any graph capture).  bnn_net_forward_static does the same on its first call on a device if
+ * it has not been done. */
+#define BNN_STATIC_WORKSPACE_BYTES (32u << 20)
+int bnn_static_workspace_init(void);
+int bnn_net_forward_static(bnn_net* net, const void* input, void* output, int batch, int path, void* stream);
 /* The same forward as ONE kernel launch (Sec. 6.2: every layer a device function of one kernel, a device-wide
  * barrier between layers).  Supported: an input layer (u8 or bits) followed by fully-connected layers only, at
  * most 8 of them; anything else returns BNN_ERR_UNSUPPORTED (use bnn_net_forward).  Same arguments, workspace

@@ -28,7 +28,7 @@ EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_conv_f32_split_thr_ex", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
-           "bnn_net_forward", "bnn_net_forward_persistent", "bnn_net_persistent_status", "bnn_net_layer_bits"]
+           "bnn_net_forward", "bnn_net_forward_static", "bnn_static_workspace_init", "bnn_net_forward_persistent", "bnn_net_persistent_status", "bnn_net_layer_bits"]
 
 
 class BnnError(RuntimeError):
@@ -543,6 +543,18 @@ class Net:
         with torch.cuda.device(x.device):
             _check(load().bnn_net_forward(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws), ctypes.c_size_t(self._ws.numel()),
                                           int(path), _stream(x)), "bnn_net_forward")
+        return out
+
+    def forward_static(self, x, out=None, path: int = PATH_AUTO):
+        """bnn_net_forward_static: the same forward on the library's fixed per-GPU workspace (no allocation inside
+        the library; the output tensor must be passed in for a call that allocates nothing at all)."""
+        _dev(x, self._in_dtype, None, "input")
+        batch = x.shape[0]
+        if out is None:
+            out = torch.empty((batch, self._out_cols), dtype=self._out_kind, device=x.device)
+        with torch.cuda.device(x.device):
+            _check(load().bnn_net_forward_static(self._h, _ptr(x), _ptr(out), batch, int(path), _stream(x)),
+                   "bnn_net_forward_static")
         return out
 
     def persistent_status(self, device=None) -> bool:

@@ -1,4 +1,5 @@
 // C ABI of libbnn: argument validation, shape bookkeeping and kernel dispatch.
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -736,6 +737,48 @@ int bnn_net_persistent_status(bnn_net* net, int* aborted, void* stream) {
     if (hipStreamSynchronize(s) != hipSuccess) return BNN_ERR_DEVICE;
     *aborted = flag != 0u ? 1 : 0;
     return BNN_OK;
+}
+
+// ---- forward for callers that cannot allocate -----------------------------------------------
+// The workspace of bnn_net_forward_static: one fixed array per GPU in the library's code object (every GPU the
+// library runs on holds its own copy, at its own address, until the process ends).  In host code `scratch` is
+// only a handle for hipGetSymbolAddress; the device address is looked up once per device and kept here.
+static __device__ __align__(256) unsigned char scratch[BNN_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+int static_workspace(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return BNN_ERR_DEVICE;
+    if (dev < 0 || dev >= kMaxDevices) return BNN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return BNN_ERR_DEVICE;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return BNN_OK;
+}
+}  // namespace
+
+int bnn_static_workspace_init(void) {
+    void* p = nullptr;
+    return static_workspace(&p);
+}
+
+int bnn_net_forward_static(bnn_net* net, const void* input, void* output, int batch, int path, void* stream) {
+    if (!net || !input || batch < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    Plan pl = plan(net, batch);
+    if (pl.rc != BNN_OK) return pl.rc;
+    if (pl.total > (size_t)BNN_STATIC_WORKSPACE_BYTES) return BNN_ERR_WORKSPACE;   // this net at this batch needs more
+    void* ws = nullptr;
+    const int rc = static_workspace(&ws);
+    if (rc != BNN_OK) return rc;
+    return bnn_net_forward(net, input, output, batch, ws, (size_t)BNN_STATIC_WORKSPACE_BYTES, path, stream);
 }
 
 int bnn_net_layer_bits(const bnn_net* net, int layer, const uint32_t** bits, int64_t* rows, int* words_per_row) {
