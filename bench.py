@@ -52,8 +52,9 @@ def main() -> int:
     ap.add_argument("--shapes", default="", help="comma-separated subset of the sweep, e.g. sq8192 (profiling runs)")
     ap.add_argument("--variant", choices=["both", "bits", "int32"], default="both", help="epilogues to run (profiling runs)")
     ap.add_argument("--only", default="", help="run only these extra sections (comma-separated: bconv, bconv_sweep, general, "
-                                               "layout, mlp, resnet18, table5) and print them; the BMM sweep is skipped (profiling runs)")
+                                               "layout, mlp, resnet18, table5, cfg1; or roofline alone) and print them; the BMM sweep is skipped (profiling runs)")
     ap.add_argument("--resnet-batches", default="256,8", help="batch sizes of the ResNet-18 section (profiling runs)")
+    ap.add_argument("--table5-nets", default="cifar_vgg,cifar_resnet14,alexnet,vgg16", help="networks of the table5 section (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="only run a plain device copy of this many MiB three times (calibrates the HBM byte counters)")
     args = ap.parse_args()
@@ -89,8 +90,12 @@ def main() -> int:
         return 0
 
     rb = tuple(int(t) for t in args.resnet_batches.split(",") if t)
+    t5 = set(t for t in args.table5_nets.split(",") if t)
+    if args.only == "roofline":
+        print(json.dumps({"only": "roofline", "measured_ceilings": run_roofline(bnn, torch, dev)}))
+        return 0
     if args.only:
-        print(json.dumps({"only": args.only, **run_extras(bnn, wl, np, torch, to_dev, dev, set(args.only.split(",")), rb)}))
+        print(json.dumps({"only": args.only, **run_extras(bnn, wl, np, torch, to_dev, dev, set(args.only.split(",")), rb, t5)}))
         return 0
 
     # ------------------------------------------------------------------ BMM sweep, resident in HBM
@@ -138,29 +143,47 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value_tops = macs_step * 2.0 / (ms_per_step * 1e-3) / 1e12
 
+    # Per-shape figures.  A lone launch between two events reads no less than the launch gap of the stream, and a
+    # Python loop of launches no less than the host's 10 us per call, so every shape is ALSO timed as a train of
+    # launches queued behind a long-running kernel (_Train): `*_ms` is the GPU time per launch inside the train,
+    # `*_single_launch_ms` the in-step figure (what one isolated call costs, launch gap included).
     per_shape = []
+    train = _Train(bnn, torch, dev)
     for s in shapes:
-        thr_ms = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9)
-        i32_ms = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9)
+        thr_1 = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9) if do_bits else None
+        i32_1 = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9) if do_i32 else None
+        reps = lambda one_ms: int(min(200, max(5, 2.0 / max(one_ms, 1e-3))))
+        thr_ms = train.time(lambda: bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path),
+                            reps(thr_1)) if do_bits else None
+        i32_ms = train.time(lambda: bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path), reps(i32_1)) if do_i32 else None
         ops = 2.0 * s["M"] * s["N"] * s["K"]
         kw = wl.nwords(s["K"]) * 4
         bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
         bytes_i32 = s["M"] * kw + s["N"] * kw + s["M"] * s["N"] * 4
-        per_shape.append({"shape": s["name"], "M": s["M"], "N": s["N"], "K": s["K"], "kernel": s["kernel"],
-                          "bits_out_ms": round(thr_ms, 5), "bits_out_tops": round(ops / thr_ms / 1e9, 2),
-                          "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
-                          "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
-                          "int32_out_kernel": s["kernel_i32"],
-                          "int32_out_ms": round(i32_ms, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
-                          "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1)})
+        row = {"shape": s["name"], "M": s["M"], "N": s["N"], "K": s["K"]}
+        if do_bits:
+            row.update({"kernel": s["kernel"], "bits_out_ms": round(thr_ms, 5), "bits_out_single_launch_ms": round(thr_1, 5),
+                        "bits_out_tops": round(ops / thr_ms / 1e9, 2),
+                        "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                        "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
+                        "bits_out_frac_hbm_peak": round(bytes_thr / thr_ms / 1e6 / PEAK_HBM_GBS, 4)})
+        if do_i32:
+            row.update({"int32_out_kernel": s["kernel_i32"], "int32_out_ms": round(i32_ms, 5),
+                        "int32_out_single_launch_ms": round(i32_1, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
+                        "int32_out_frac_fp4_mfma_peak": round(ops / i32_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                        "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1),
+                        "int32_out_frac_hbm_peak": round(bytes_i32 / i32_ms / 1e6 / PEAK_HBM_GBS, 4)})
+        row["in_step_ms"] = {"bits": round(thr_1, 5) if do_bits else None, "int32": round(i32_1, 5) if do_i32 else None}
+        per_shape.append(row)
 
     # roofline of the dominant kernel: the launches (both epilogues) of the kernel variant that
     # takes the most time in a step
     by_kernel = {}
     for s, ps in zip(shapes, per_shape):
         kw = (s["M"] + s["N"]) * wl.nwords(s["K"]) * 4
-        for on, kern, ms, out_bytes in ((do_bits, s["kernel"], ps["bits_out_ms"], s["M"] * wl.nwords(s["N"]) * 4),
-                                        (do_i32, s["kernel_i32"], ps["int32_out_ms"], 4 * s["M"] * s["N"])):
+        # launch durations measured inside the timed region (events on the launch stream around every launch)
+        for on, kern, ms, out_bytes in ((do_bits, s["kernel"], ps["in_step_ms"]["bits"], s["M"] * wl.nwords(s["N"]) * 4),
+                                        (do_i32, s["kernel_i32"], ps["in_step_ms"]["int32"], 4 * s["M"] * s["N"])):
             if on:
                 d = by_kernel.setdefault(kern, {"ms": 0.0, "flop": 0.0, "launches": 0, "bytes": 0})
                 d["ms"] += ms
@@ -170,18 +193,27 @@ def main() -> int:
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     dk = by_kernel[dom]
     achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
+    probe_buf = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+    measured_peak = bnn.probe_pipeline("mfma_fp4", probe_buf, iters=4000)[0] / 1e12
+    measured_loop = bnn.probe_pipeline("mfma_fp4_expand", probe_buf, iters=4000)[0] / 1e12
+    del probe_buf
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_FP4_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4),
+                "measured_peak": round(measured_peak, 1), "frac_of_measured_peak": round(achieved / measured_peak, 4),
+                "measured_expand_plus_mfma_loop": round(measured_loop, 1),
+                "frac_of_measured_loop": round(achieved / measured_loop, 4),
                 "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
                             else None),
                 "algorithmic_bytes_per_launch": round(dk["bytes"] / max(dk["launches"], 1)),
                 "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
                 "flop_per_launch": dk["flop"] / dk["launches"],
-                "note": "fp4 (E2M1) matrix-core peak; 1 MAC on +1/-1 = 2 flop = 2 binary ops"}
+                "note": "peak: published fp4 (E2M1) dense matrix-core rate; measured_peak: the same MFMA alone, register-"
+                        "resident, in this run; measured_expand_plus_mfma_loop: the kernel's inner loop without memory "
+                        "(bnn_probe_pipeline); 1 MAC on +1/-1 = 2 flop = 2 binary ops"}
 
     extras = {}
     if not args.skip_extras:
-        extras = run_extras(bnn, wl, np, torch, to_dev, dev, None, rb)
+        extras = run_extras(bnn, wl, np, torch, to_dev, dev, None, rb, t5)
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline(wl, np)
@@ -205,6 +237,27 @@ def main() -> int:
     return 0
 
 
+def run_roofline(bnn, torch, dev):
+    """The measured ceilings of this chip for every pipeline the library uses or decided against (bnn_probe_pipeline)."""
+    small = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+    big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)       # well beyond the 256 MB last-level cache
+    out = {}
+    for name, buf, unit, scale, pub in (
+            ("mfma_fp4", small, "PFLOP/s", 1e15, 10.1), ("mfma_fp4_expand", small, "PFLOP/s", 1e15, None),
+            ("mfma_i8", small, "POP/s", 1e15, 5.0), ("mfma_bf16", small, "PFLOP/s", 1e15, 2.5),
+            ("valu_xor_popc", small, "binary POP/s", 1e15, 1.26), ("lds_read", small, "TB/s", 1e12, None),
+            ("hbm_read", big, "TB/s", 1e12, 8.0), ("hbm_write", big, "TB/s", 1e12, 8.0), ("hbm_copy", big, "TB/s", 1e12, 8.0)):
+        rate, sec = bnn.probe_pipeline(name, buf, iters=4000)
+        out[name] = {"measured": round(rate / scale, 3), "unit": unit, "launch_ms": round(sec * 1e3, 4)}
+        if pub is not None:
+            out[name]["published_or_derived_peak"] = pub
+            out[name]["frac"] = round(rate / scale / pub, 3)
+    out["notes"] = ("mfma_fp4_expand = 8 MFMAs + 6 word expansions per K-step of a 4x2 wave tile, no memory traffic; "
+                    "valu_xor_popc peak derived: 256 CUs x 64 lanes x 2.4 GHz x 32 bits / 2 instructions x 2 ops; "
+                    "hbm_copy counts bytes read + written")
+    return out
+
+
 def _time_gpu(torch, fn, iters, warmup=3):
     for _ in range(warmup):
         fn()
@@ -218,6 +271,37 @@ def _time_gpu(torch, fn, iters, warmup=3):
     return e0.elapsed_time(e1) / iters
 
 
+class _Train:
+    """Device time per launch of a small kernel.  Launching from Python costs about 10 us per call, more than such
+    a kernel runs, so a plain loop measures the host.  Here a long-running kernel is enqueued first; while it
+    keeps the GPU busy the host enqueues `n` launches of `fn` behind it, and the events on either side of the
+    train then bracket GPU time only (kernel time plus the command processor's gap between dependent launches)."""
+
+    def __init__(self, bnn, torch, dev):
+        self.bnn, self.torch = bnn, torch
+        self.buf = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+        self.iters = 4000
+        rate, sec = bnn.probe_pipeline("mfma_i8", self.buf, iters=self.iters, reps=1)
+        self.iters = max(1000, int(self.iters * 4e-3 / sec))          # a blocker of about 4 ms
+
+    def time(self, fn, n=100):
+        torch = self.torch
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            self.bnn.probe_pipeline_enqueue("mfma_i8", self.buf, self.iters)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / n
+            best = ms if best is None else min(best, ms)
+        return best
+
+
 def _time_graph(torch, fn, iters):
     """The same call captured once into a HIP graph and replayed: per-layer launch cost without the host."""
     fn()
@@ -229,12 +313,32 @@ def _time_graph(torch, fn, iters):
     return _time_gpu(torch, g.replay, iters)
 
 
-def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 8)):
+def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 8), table5_nets=None):
     out = {}
 
     def want(section):
         return only is None or section in only
 
+    # ---- config 1 (BMM 1024^3): latency-bound; one isolated launch and a train of 100
+    if want("cfg1"):
+        case = wl.cfg1()
+        A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+        C = torch.empty((1024, 1024), dtype=torch.int32, device=dev)
+        Cb = torch.empty((1024, 32), dtype=torch.int32, device=dev)
+        ops = 2.0 * 1024 ** 3
+        r = {"kernel": bnn.bmm_kernel_name(1024, 1024, 1024), "int32_out_kernel": bnn.bmm_kernel_name(1024, 1024, 1024, int32_out=True)}
+        for key, fn, nbytes in (("int32_out", lambda: bnn.bmm(A, B, 1024, out=C), 2 * 131072 + 4 * 1024 * 1024),
+                                ("bits_out", lambda: bnn.bmm_thr(A, B, tau, 1024, out=Cb), 3 * 131072)):
+            single = float(np.median([_time_gpu(torch, fn, 1, warmup=1) for _ in range(20)]))
+            train = _Train(bnn, torch, dev).time(fn, 100)
+            r[key] = {"single_launch_ms": round(single, 5), "train_of_100_ms_per_launch": round(train, 5),
+                      "note": "train: 100 launches queued behind a long-running kernel, GPU time per launch",
+                      "tops_in_train": round(ops / train / 1e9, 1),
+                      "frac_fp4_mfma_peak_in_train": round(ops / train / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                      "hbm_gbs_in_train": round(nbytes / train / 1e6, 1),
+                      "frac_hbm_peak_in_train": round(nbytes / train / 1e6 / PEAK_HBM_GBS, 4)}
+        out["bmm_1024_config1"] = r
+        del A, B, C, Cb
     # ---- single BConv layers (config 4)
     if want("bconv"):
         convs = []
@@ -245,13 +349,17 @@ def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 
             bits = torch.empty((N, P, Q, wl.nwords(O)), dtype=torch.int32, device=dev)
             y = torch.empty((N, P, Q, O), dtype=torch.int32, device=dev)
             ops = 2.0 * N * P * Q * O * k * k * C
-            t_b = _time_gpu(torch, lambda: bnn.bconv_thr(x, f, tau, C, st, pad, bnn.PAD_MINUS_ONE, out=bits), 20)
-            t_i = _time_gpu(torch, lambda: bnn.bconv(x, f, C, st, pad, bnn.PAD_MINUS_ONE, out=y), 20)
+            tr = _Train(bnn, torch, dev)
+            t_b = tr.time(lambda: bnn.bconv_thr(x, f, tau, C, st, pad, bnn.PAD_MINUS_ONE, out=bits), 50)
+            t_i = tr.time(lambda: bnn.bconv(x, f, C, st, pad, bnn.PAD_MINUS_ONE, out=y), 50)
             convs.append({"shape": name, "kernel": bnn.bconv_kernel_name(N, H, W, C, O, k, st, pad),
                           "bits_out_ms": round(t_b, 5), "bits_out_tops": round(ops / t_b / 1e9, 2),
                           "bits_out_frac_fp4_mfma_peak": round(ops / t_b / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
                           "int32_out_ms": round(t_i, 5), "int32_out_tops": round(ops / t_i / 1e9, 2),
-                          "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1)})
+                          "bits_out_hbm_gbs": round((x.numel() + bits.numel() + f.numel()) * 4 / t_b / 1e6, 1),
+                          "bits_out_frac_hbm_peak": round((x.numel() + bits.numel() + f.numel()) * 4 / t_b / 1e6 / PEAK_HBM_GBS, 4),
+                          "int32_out_hbm_gbs": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6, 1),
+                          "int32_out_frac_hbm_peak": round((y.numel() * 4 + x.numel() * 4) / t_i / 1e6 / PEAK_HBM_GBS, 4)})
             del x, f, bits, y
         out["bconv_shapes"] = convs
     # ---- the paper's BConv sweep (Sec. 7.3): batch 16, 64x64 input, 3x3, stride 1, C = O
@@ -379,6 +487,8 @@ def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 
     if want("table5"):
         t5 = {}
         for name, big in (("cifar_vgg", 1024), ("cifar_resnet14", 1024), ("alexnet", 512), ("vgg16", 512)):
+            if table5_nets is not None and name not in table5_nets:
+                continue
             spec = wl.cnn_layers(name)
             net5 = bnn.Net.from_layers(spec["layers"], spec["in_hw"], device=dev)
             r = {}

@@ -153,6 +153,33 @@ int bnn_bmm_thr_tiled(const uint32_t* A, const uint32_t* B_tiled, const int32_t*
 int bnn_probe_load_stride(const uint32_t* zeros, int64_t* cycles, int stride_bytes, int rows, int iters, int dependent,
                           void* stream);
 
+/* Diagnostic, after the method of Sec. 4 (measure the machine's ceilings by microbenchmark and design against
+ * those): ONE kernel that keeps a single pipeline busy, operands resident in registers where the pipeline allows.
+ * The caller times the launch (events on `stream`) and divides *work_per_launch by the elapsed time.
+ *   which                        work unit   what runs
+ *   BNN_PROBE_MFMA_FP4           flop        v_mfma_f32_32x32x64_f8f6f4 on E2M1 operands alone (8 accumulators per wave)
+ *   BNN_PROBE_MFMA_FP4_EXPAND    flop        the BMM kernel's inner loop without memory: per K-step 6 packed words
+ *                                            expanded to E2M1 (7 vector-ALU instructions each) feeding 8 MFMAs
+ *   BNN_PROBE_MFMA_I8            op          v_mfma_i32_32x32x32_i8 alone (the +1/-1-as-int8 alternative)
+ *   BNN_PROBE_MFMA_BF16          flop        v_mfma_f32_32x32x16_bf16 alone (first layer with real-valued input)
+ *   BNN_PROBE_VALU_XOR_POPC      binary op   v_xor_b32 + v_bcnt_u32_b32 (Eq. 2 literally), 2 ops per bit product
+ *   BNN_PROBE_LDS_READ           byte        ds_read_b128, conflict-free
+ *   BNN_PROBE_HBM_READ / _WRITE  byte        streams buf with 16-byte accesses (use a buffer larger than the caches)
+ *   BNN_PROBE_HBM_COPY           byte        first half of buf -> second half; counts bytes read + written
+ * buf: device scratch, 256-byte aligned; the compute and LDS probes write one word per thread into it (at least
+ * 2 MiB), the memory probes stream all buf_bytes of it.  iters: loop trips per wave (compute and LDS probes).
+ * 2 workgroups of 256 threads per compute unit (compute, LDS), 8 per compute unit (memory). */
+#define BNN_PROBE_MFMA_FP4 0
+#define BNN_PROBE_MFMA_FP4_EXPAND 1
+#define BNN_PROBE_MFMA_I8 2
+#define BNN_PROBE_MFMA_BF16 3
+#define BNN_PROBE_VALU_XOR_POPC 4
+#define BNN_PROBE_LDS_READ 5
+#define BNN_PROBE_HBM_READ 6
+#define BNN_PROBE_HBM_WRITE 7
+#define BNN_PROBE_HBM_COPY 8
+int bnn_probe_pipeline(int which, void* buf, size_t buf_bytes, int iters, double* work_per_launch, void* stream);
+
 /* Binarization by sign (Eq. 1): bit = (x >= 0).  x [rows][ldx] fp32 -> bits [rows][ldb_w] (pad bits and pad words 0). */
 int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream);
 

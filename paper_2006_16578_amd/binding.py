@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "conv_f32_split_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "probe_pipeline", "probe_pipeline_enqueue", "PROBES", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "conv_f32_split_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm_kernel_name_out", "bnn_bconv_kernel_name_out", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
+           "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_probe_pipeline", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_conv_f32_split_thr_ex", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
@@ -268,6 +268,40 @@ def probe_load_stride(stride_bytes: int, rows: int | None = None, iters: int = 4
             _check(load().bnn_probe_load_stride(_ptr(buf), _ptr(cyc), int(stride_bytes), int(rows), int(iters),
                                                 1 if dependent else 0, _stream(buf)), "bnn_probe_load_stride")
     return float(cyc[0].item()) / iters
+
+
+PROBES = {"mfma_fp4": 0, "mfma_fp4_expand": 1, "mfma_i8": 2, "mfma_bf16": 3, "valu_xor_popc": 4, "lds_read": 5,
+          "hbm_read": 6, "hbm_write": 7, "hbm_copy": 8}
+
+
+def probe_pipeline(which: str, buf, iters: int = 2000, reps: int = 3):
+    """Runs one ceiling microbenchmark (bnn_probe_pipeline) `reps` times after a warm-up launch; returns
+    (work units per second of the fastest launch, seconds of that launch).  buf: a uint8 device tensor."""
+    _dev(buf, torch.uint8, 1, "buf")
+    work = ctypes.c_double(0.0)
+    best = None
+    with torch.cuda.device(buf.device):
+        for rep in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            _check(load().bnn_probe_pipeline(PROBES[which], _ptr(buf), ctypes.c_size_t(buf.numel()), int(iters),
+                                             ctypes.byref(work), _stream(buf)), "bnn_probe_pipeline")
+            e1.record()
+            e1.synchronize()
+            sec = e0.elapsed_time(e1) * 1e-3
+            if rep > 0 and (best is None or sec < best):
+                best = sec
+    return work.value / best, best
+
+
+def probe_pipeline_enqueue(which: str, buf, iters: int) -> float:
+    """Enqueues one launch of a ceiling microbenchmark without waiting for it; returns its work units."""
+    _dev(buf, torch.uint8, 1, "buf")
+    work = ctypes.c_double(0.0)
+    with torch.cuda.device(buf.device):
+        _check(load().bnn_probe_pipeline(PROBES[which], _ptr(buf), ctypes.c_size_t(buf.numel()), int(iters),
+                                         ctypes.byref(work), _stream(buf)), "bnn_probe_pipeline")
+    return work.value
 
 
 def sign_pack_f32(x, ldb_w: int | None = None):

@@ -354,6 +354,12 @@ int bnn_probe_load_stride(const uint32_t* zeros, int64_t* cycles, int stride_byt
                                static_cast<hipStream_t>(stream));
 }
 
+int bnn_probe_pipeline(int which, void* buf, size_t buf_bytes, int iters, double* work_per_launch, void* stream) {
+    if (!buf || !work_per_launch) return BNN_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(buf) & 255u) return BNN_ERR_ALIGNMENT;
+    return launch_probe_pipeline(which, buf, buf_bytes, iters, work_per_launch, static_cast<hipStream_t>(stream));
+}
+
 int bnn_sign_pack_f32(const float* x, uint32_t* bits, int64_t rows, int cols, int ldx, int ldb_w, void* stream) {
     if (!x || !bits || rows < 1 || cols < 1 || ldx < cols || ldb_w < words(cols)) return BNN_ERR_INVALID_ARG;
     if (rows > (1LL << 33)) return BNN_ERR_UNSUPPORTED;

@@ -114,6 +114,13 @@ int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, int spin_l
 
 int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+// Skinny matrix products (at most 128 rows): workgroups of 32 columns x all rows whose waves split K.
+bool mfma_skinny_takes(const Geom& g);
+const char* describe_mfma_skinny(const Geom& g);
+int launch_mfma_skinny(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+// Large matrix products: 256 x 256 workgroup tiles whose operands are expanded once, on their way into LDS.
+bool mfma_wide_takes(const Geom& g, const Epi& e);
+int launch_mfma_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_staged(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v4(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v2(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
@@ -128,6 +135,7 @@ int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, in
 int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s);
 int launch_tile_b(const uint32_t* B, uint32_t* Bt, int N, int ldb_w, hipStream_t s);
 int launch_probe_stride(const uint32_t* buf, long long* cycles, int stride_bytes, int rows, int iters, int dependent, hipStream_t s);
+int launch_probe_pipeline(int which, void* buf, size_t buf_bytes, int iters, double* work, hipStream_t s);
 int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_unpack_i32(const uint32_t* bits, int32_t* out, long long rows, int cols, int ldb_w, int ldo, hipStream_t s);
 int launch_maxpool_or(const uint32_t* in, uint32_t* out, int N, int H, int W, int C, int win, int stride, hipStream_t s);

@@ -19,7 +19,9 @@ bool staged_ok(const Geom& g, int tile) {
 }  // namespace
 
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    if (mfma_skinny_takes(g)) return launch_mfma_skinny(A, B, g, e, s);
     const int tile = mfma::pick_tile(g, &e);
+    if (tile == 0 && mfma_wide_takes(g, e)) return launch_mfma_wide(A, B, g, e, s);
     if (!g.conv) {
         if (!g.b_tiled && staged_ok(g, tile)) {
             switch (tile) {
@@ -46,10 +48,12 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 }
 
 const char* describe_mfma(const Geom& g, bool int32_out) {
+    if (mfma_skinny_takes(g)) return describe_mfma_skinny(g);
     static int32_t some_output;
     Epi e = {};
     e.out = int32_out ? &some_output : nullptr;   // pick_tile only asks whether there is one
     const int tile = mfma::pick_tile(g, &e);
+    if (tile == 0 && mfma_wide_takes(g, e)) return "mfma_fp4_bmm_xlds_wg256x256";
     const bool st = !g.b_tiled && staged_ok(g, tile);
     switch (tile) {
         case 0: return g.conv ? (st ? "mfma_fp4_conv_lds_wg256x128" : "mfma_fp4_conv_wg256x128")

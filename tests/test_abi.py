@@ -46,8 +46,12 @@ def test_status_strings_and_null_checks():
 def test_kernel_choice_is_host_logic():
     # which kernel variant a shape gets is decided on the host: no device needed to ask
     import paper_2006_16578_amd as b
-    assert b.bmm_kernel_name(16384, 16384, 16384) == "mfma_fp4_bmm_lds_wg256x128"
-    assert b.bmm_kernel_name(8, 4096, 4096) == "mfma_fp4_bmm_wg64x64"
+    assert b.bmm_kernel_name(16384, 16384, 16384) == "mfma_fp4_bmm_xlds_wg256x256"
+    assert b.bmm_kernel_name(4096, 4096, 4096) == "mfma_fp4_bmm_xlds_wg256x256"        # 256 tiles: one per compute unit
+    assert b.bmm_kernel_name(2048, 2048, 2048) == "mfma_fp4_bmm_lds_wg128x128"         # too few 256 x 256 tiles
+    assert b.bmm_kernel_name(8, 4096, 4096) == "mfma_fp4_bmm_skinny_m32"               # at most 128 rows: K split over waves
+    assert b.bmm_kernel_name(128, 4096, 4096) == "mfma_fp4_bmm_skinny_m128"
+    assert b.bmm_kernel_name(129, 4096, 4096) == "mfma_fp4_bmm_wg64x64"
     assert b.bmm_kernel_name(4096, 4096, 4096, b.PATH_VALU) == "valu_xor_popc_bmm"
     # a short-K matrix product with int32 output moves more bytes than it multiplies: small tiles
     assert b.bmm_kernel_name(8192, 8192, 256, int32_out=True) == "mfma_fp4_bmm_wg64x64"

@@ -46,8 +46,12 @@ def test_ragged_shapes(bnn, orc, pname, path):
 
 
 # ragged shapes large enough to select each LDS-staged tile of the matrix-core path
-STAGED = [(3000, 2500, 1000, "mfma_fp4_bmm_lds_wg128x128"), (5000, 5100, 1234, "mfma_fp4_bmm_lds_wg256x128"),
-          (131100, 50, 200, "mfma_fp4_bmm_lds_wg512x64"), (4097, 3001, 4100, "mfma_fp4_bmm_lds_wg256x128")]
+STAGED = [(3000, 2500, 1000, "mfma_fp4_bmm_lds_wg128x128"), (5000, 5100, 1234, "mfma_fp4_bmm_xlds_wg256x256"),
+          (131100, 50, 200, "mfma_fp4_bmm_lds_wg512x64"), (4097, 3001, 4100, "mfma_fp4_bmm_lds_wg256x128"),
+          # the 256 x 256 tile with operands expanded into LDS: ragged edges on both sides, a last slab that is
+          # half empty (K words = 4 mod 8), a single slab pair, and a short K that keeps the 256 x 128 kernel
+          (4097, 3700, 1100, "mfma_fp4_bmm_xlds_wg256x256"), (3850, 4200, 1024, "mfma_fp4_bmm_xlds_wg256x256"),
+          (4000, 4000, 800, "mfma_fp4_bmm_lds_wg256x128")]
 
 
 @pytest.mark.parametrize("M,N,K,kernel", STAGED)
@@ -143,6 +147,33 @@ def test_threshold_edge_values(bnn, orc, pname, path):
         assert (ref == K).any() and (ref == -K).any()
         print("edge thresholds", M, N, K, pname, flush=True)
         run_case(bnn, orc, case, path, ref=ref)
+
+
+@pytest.mark.parametrize("M", [1, 7, 8, 9, 32, 33, 64, 65, 127, 128])
+def test_skinny_rows(bnn, orc, M):
+    # at most 128 rows: workgroups of 32 columns x all rows whose four waves split K.  K with one chunk, a ragged
+    # last chunk (upper half-wave past the row's end), fewer chunks than waves, and many rounds per wave; N ragged
+    assert bnn.bmm_kernel_name(M, 4096, 4096).startswith("mfma_fp4_bmm_skinny_m")
+    assert bnn.bmm_kernel_name(129, 4096, 4096) != bnn.bmm_kernel_name(128, 4096, 4096)
+    for idx, (N, K) in enumerate(((4096, 4096), (10, 1024), (1000, 784), (33, 100), (130, 257), (64, 5000), (96, 40000))):
+        print("skinny", M, N, K, flush=True)
+        case = wl.bmm_case(97, M, N, K, index0=(M * 7 + idx) % 89)
+        ref = orc.bmm(case["A"], case["B"], K, tier=1)
+        nr = min(M, 4)
+        assert np.array_equal(orc.bmm_rows(case["A"], case["B"], K, M - nr, nr), ref[M - nr:])
+        run_case(bnn, orc, case, 0, ref=ref, ld_extra=4 if idx % 2 else 0)
+
+
+def test_skinny_max_k(bnn, orc):
+    # K at the library's maximum through the skinny kernel (4096 chunks, 1024 rounds per wave): exact +-K
+    K = 1 << 20
+    for M in (8, 128):
+        case = wl.bmm_case(98, M, 70, K, index0=M)
+        case["B"][3] = case["A"][5]
+        case["B"][4] = ~case["A"][6]
+        ref = orc.bmm(case["A"], case["B"], K, tier=1)
+        assert ref[5, 3] == K and ref[6, 4] == -K
+        run_case(bnn, orc, case, 0, ref=ref)
 
 
 def test_threshold_pack_and_packs(bnn, orc):
