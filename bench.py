@@ -31,7 +31,7 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
-TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_lds_wg256x128": 7.149e+08}
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 3.849e+08}
 
 
 # Table 6 of the paper, BTC-FMT row (RTX 2080; trained weights, real data): context only
@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--only", default="", help="run only these extra sections (comma-separated: bconv, bconv_sweep, general, "
                                                "layout, mlp, resnet18, table5, cfg1; or roofline alone) and print them; the BMM sweep is skipped (profiling runs)")
     ap.add_argument("--resnet-batches", default="256,8", help="batch sizes of the ResNet-18 section (profiling runs)")
+    ap.add_argument("--skip-trains", action="store_true",
+                    help="no per-shape launch trains after the timed steps: the run then launches each sweep kernel "
+                         "exactly (steps + warmup) times per shape and epilogue (profiling runs)")
     ap.add_argument("--table5-nets", default="cifar_vgg,cifar_resnet14,alexnet,vgg16", help="networks of the table5 section (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="only run a plain device copy of this many MiB three times (calibrates the HBM byte counters)")
@@ -148,14 +151,15 @@ def main() -> int:
     # launches queued behind a long-running kernel (_Train): `*_ms` is the GPU time per launch inside the train,
     # `*_single_launch_ms` the in-step figure (what one isolated call costs, launch gap included).
     per_shape = []
-    train = _Train(bnn, torch, dev)
+    train = None if args.skip_trains else _Train(bnn, torch, dev)
     for s in shapes:
         thr_1 = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9) if do_bits else None
         i32_1 = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9) if do_i32 else None
         reps = lambda one_ms: int(min(200, max(5, 2.0 / max(one_ms, 1e-3))))
-        thr_ms = train.time(lambda: bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path),
-                            reps(thr_1)) if do_bits else None
-        i32_ms = train.time(lambda: bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path), reps(i32_1)) if do_i32 else None
+        thr_ms = (thr_1 if args.skip_trains else
+                  train.time(lambda: bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path), reps(thr_1))) if do_bits else None
+        i32_ms = (i32_1 if args.skip_trains else
+                  train.time(lambda: bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path), reps(i32_1))) if do_i32 else None
         ops = 2.0 * s["M"] * s["N"] * s["K"]
         kw = wl.nwords(s["K"]) * 4
         bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
@@ -217,6 +221,7 @@ def main() -> int:
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline(wl, np)
+        extras["cpu_oracle_per_shape"] = cpu_oracle_detail(wl, np)
 
     line = {
         "metric": "binary TOPS for BMM/BConv (fraction of roofline); BNN ResNet-18 images/s",
@@ -540,6 +545,71 @@ def cpu_baseline(wl, np):
             "seconds": round(secs, 2),
             "sample": "tier-0 oracle (unpacked int8 +1/-1, naive loops, includes unpacking B) on the first 768 rows of A "
                       "of every sweep shape (all rows where M < 768), int32 output"}
+
+
+def cpu_oracle_detail(wl, np):
+    """The CPU oracle per shape, next to the GPU figures (a baseline, never the target): the packed tier-1 oracle
+    (uint64 xor + popcount, plain C, OpenMP over rows) in full on every sweep shape; the naive tier-0 oracle
+    (+1/-1 as int8) in full where that takes seconds, else on a slab of rows / images scaled linearly and labelled
+    extrapolated; config 1 also on a single thread."""
+    import ctypes
+
+    import oracle as orc
+    from oracle import nets
+    orc.build()
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    gomp = ctypes.CDLL("libgomp.so.1")
+
+    def timed(fn):
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    out = {"cores": cores, "bmm": [], "note": "seconds on the host CPU; tops = binary TOPS = 2 x bit-MAC/s / 1e12"}
+    for name, M, N, K, _ in [("cfg1_sq1024", 1024, 1024, 1024, 0)] + wl.cfg2_shapes():
+        case = wl.cfg1() if name == "cfg1_sq1024" else wl.cfg2_case(name)
+        macs = float(M) * N * K
+        row = {"shape": name}
+        rows1 = M if macs <= 6e11 else M // 8                 # tier 1 in full up to n = 8192
+        t1 = timed(lambda: orc.bmm(case["A"][:rows1], case["B"], K, tier=1)) * M / rows1
+        row["tier1_packed_s"] = round(t1, 4)
+        row["tier1_tops"] = round(2 * macs / t1 / 1e12, 4)
+        row["tier1_sample"] = "full" if rows1 == M else "first %d rows of A, extrapolated" % rows1
+        rows = M if macs <= 8e10 else 64                      # tier 0 in full up to n = 4096
+        t0 = timed(lambda: orc.bmm_rows(case["A"], case["B"], K, 0, rows))
+        row["tier0_naive_s"] = round(t0 * M / rows, 4)
+        row["tier0_tops"] = round(2 * macs / (t0 * M / rows) / 1e12, 5)
+        row["tier0_sample"] = "full" if rows == M else "first %d rows of A, extrapolated" % rows
+        if name == "cfg1_sq1024":
+            gomp.omp_set_num_threads(1)
+            t0s = timed(lambda: orc.bmm_rows(case["A"], case["B"], K, 0, M))
+            t1s = timed(lambda: orc.bmm(case["A"], case["B"], K, tier=1))
+            gomp.omp_set_num_threads(cores)
+            row["tier0_naive_single_thread_s"] = round(t0s, 4)
+            row["tier1_packed_single_thread_s"] = round(t1s, 4)
+        out["bmm"].append(row)
+    convs = []
+    for name, case in (("conv_56x56_c128_o128_s1", wl.cfg4a()), ("conv_56x56_c64_o128_s2", wl.cfg4b())):
+        N, H, W, C, O, k, st, pad = (case[q] for q in ("N", "H", "W", "C", "O", "k", "stride", "pad"))
+        P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+        macs = float(N) * P * Q * O * k * k * C
+        t1 = timed(lambda: orc.bconv(case["x"], case["filt"], C, st, pad, orc.PAD_MINUS_ONE, tier=1))
+        t0 = timed(lambda: orc.bconv_images(case["x"], case["filt"], C, st, pad, orc.PAD_MINUS_ONE, 0, 2))
+        convs.append({"shape": name, "tier1_packed_s": round(t1, 4), "tier1_tops": round(2 * macs / t1 / 1e12, 4),
+                      "tier0_naive_s": round(t0 * N / 2, 3), "tier0_tops": round(2 * macs / (t0 * N / 2) / 1e12, 5),
+                      "tier0_sample": "2 of %d images, extrapolated" % N})
+    out["bconv"] = convs
+    p = wl.resnet18_params()
+    x2 = wl.resnet18_input(2)
+    t0 = timed(lambda: nets.resnet18_forward(x2, p, tier=0))
+    t1 = timed(lambda: nets.resnet18_forward(x2, p, tier=1))
+    out["resnet18_224"] = {"tier0_naive_images_per_s": round(2 / t0, 3), "tier1_packed_images_per_s": round(2 / t1, 3),
+                           "sample": "whole forward (fp32 stem and head in double) on 2 images"}
+    params = wl.mlp_params()
+    imgs = wl.mlp_images(1024)
+    t0 = timed(lambda: nets.mlp_forward(imgs, params))
+    out["mlp_784_1024x3_10"] = {"tier0_naive_images_per_s": round(1024 / t0, 1), "sample": "batch 1024, full"}
+    return out
 
 
 if __name__ == "__main__":

@@ -118,12 +118,15 @@ __global__ __launch_bounds__(256) void conv_f32_expand_kernel(const float* __res
         const int r = rho / rpr, j = rho - r * rpr;
         const int e0 = min(8 * j, last0);
         const float* wrow = w + ((long long)o * k + r) * seg;        // the k*C weights of filter row r are contiguous
+        float xs[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) xs[s] = wrow[min(e0 + s, seg - 1)];     // all eight loads in flight at once; masked below
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             const int e = e0 + s;
             uint32_t val = 0u;
             if (e < seg && e >= 8 * j) {
-                const float x0 = wrow[e];
+                const float x0 = xs[s];
                 const uint32_t a = __float_as_uint(x0);
                 const float r1 = x0 - __uint_as_float(a & 0xffff0000u);
                 const uint32_t b = __float_as_uint(r1);
