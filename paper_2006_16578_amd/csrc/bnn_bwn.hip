@@ -36,6 +36,7 @@ namespace {
 typedef float v16f_bwn __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf_bwn __attribute__((ext_vector_type(8)));
 typedef float float4_ub __attribute__((ext_vector_type(4), aligned(4)));
+typedef float float2_ub __attribute__((ext_vector_type(2), aligned(4)));
 extern "C" __device__ int bnn_bwn_writelane_i32(int val, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
 
 struct Split3 {
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void bwn_expand_kernel(const uint32_t* __restr
 // Same layout for real-valued weights w [O][k][k][C]: each weight is split exactly into three bf16 terms
 // (as the input values are) and the three terms go to three planes, wexp [col_tiles][3][2 * nsteps][cols] units.
 __global__ __launch_bounds__(256) void conv_f32_expand_kernel(const float* __restrict__ w, uint4* __restrict__ wexp, int C, int O,
-                                                              int k, int cols, int nsteps, int nunits) {
+                                                              int k, int cols, int nsteps, int nunits, int moveback) {
     const int u = (int)(blockIdx.x * 256 + threadIdx.x);
     if (u >= nunits) return;
     const int seg = k * C, rpr = (seg + 7) >> 3, nruns = k * rpr;
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256) void conv_f32_expand_kernel(const float* __res
     uint32_t pk[4] = {0u, 0u, 0u, 0u};
     if (rho < nruns && o < O) {
         const int r = rho / rpr, j = rho - r * rpr;
-        const int e0 = min(8 * j, last0);
+        const int e0 = moveback ? min(8 * j, last0) : 8 * j;
         const float* wrow = w + ((long long)o * k + r) * seg;        // the k*C weights of filter row r are contiguous
         float xs[8];
 #pragma unroll
@@ -608,7 +609,7 @@ int launch_bwn_direct(const float* x, const void* weights, const float* thr, flo
                            wexp, C, C, O, k, COLS, 1, nsteps, nunits);
     else
         hipLaunchKernelGGL(conv_f32_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s,
-                           static_cast<const float*>(weights), wexp, C, O, k, COLS, nsteps, nunits);
+                           static_cast<const float*>(weights), wexp, C, O, k, COLS, nsteps, nunits, 1);
     // one workgroup per CU (registers allow no more), resident for the whole call
     const long long groups = cdiv(npix, MT * 32);
     static int cus = 0;
@@ -717,6 +718,293 @@ int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr,
     return launch_bwn_direct<1, 4, 8, 1>(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
 }
 
+// ------------------------------------------------------------------------------------------ wave-private patches
+// Real-valued first layer (three weight planes) for one filter geometry fixed at compile time (the 7x7 stride-4 stem
+// of 3-channel images): every wave on its own.  A wave owns a rectangle of FP x FQ = 32 output pixels, keeps the input
+// patch under it in a private slice of LDS as three bf16 planes, and walks the K loop from LDS only: with the geometry
+// known, every LDS address of the loop is a lane base plus an immediate, so a K-step is twelve MFMAs, twelve LDS reads
+// and one vector instruction (the direct kernel above issues ten vector instructions per MFMA for loading, masking
+// and splitting its runs).  The patch of the wave's NEXT rectangle is requested from global memory before the K loop
+// (coalesced 8-byte loads into registers, one scalar address per patch row) and is split and written to LDS after the
+// epilogue, so the only memory wait a wave sees is one it has had a whole rectangle of MFMA work to cover; the eight
+// waves of a workgroup share nothing but the weights (copied to LDS once: the workgroups are persistent) and drift
+// apart, so that on every SIMD one wave stages while the other multiplies.  No barrier after the weights are in.
+template <int KS_, int STRIDE_, int CIN_, int FP_, int FQ_>
+struct WaveGeom {
+    static constexpr int KS = KS_, STRIDE = STRIDE_, CIN = CIN_, FP = FP_, FQ = FQ_;
+    static constexpr int PR = (FP - 1) * STRIDE + KS;                        // patch rows
+    static constexpr int ROW_ELEMS = ((FQ - 1) * STRIDE + KS) * CIN;         // input values of a patch row
+    static constexpr int SEG = KS * CIN;                                     // values of one filter row
+    static constexpr int RPR = (SEG + 7) / 8;                                // runs of 8 per filter row
+    static constexpr int NRUNS = KS * RPR;
+    static constexpr int NSTEPS = (NRUNS + 1) / 2;                           // MFMA K-steps (two runs each)
+    static constexpr int REACH = (FQ - 1) * STRIDE * CIN + 8 * RPR;          // farthest element a run reads from a patch row, + 1
+    static constexpr int PITCH = (2 * (REACH > ROW_ELEMS ? REACH : ROW_ELEMS) + 7) / 8 * 8;    // bytes between patch rows
+    static constexpr int PAIRS = PITCH / 4;                                  // 2-element units written per patch row (data + zeroed slack)
+    static constexpr int PLANE = PR * PITCH;                                 // bytes of one bf16 plane of a patch
+    static constexpr int WUNITS = NRUNS * 64;                                // 16-byte units of one weight plane in LDS
+    static constexpr int WAVES = 8;
+    static constexpr size_t LDS = (size_t)3 * WUNITS * 16 + (size_t)WAVES * 3 * PLANE;
+    static_assert(FP * FQ == 32 && PAIRS <= 64 && (STRIDE * CIN * 2) % 8 == 0, "one lane per pair; 8-byte aligned runs");
+};
+
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, F, I + 1>(static_cast<F&&>(f));
+    }
+}
+
+struct WaveArgs {
+    int N, H, W, O, pad, P, Q;
+    int tiles_p, tiles_q;
+    int ntiles;              // N * tiles_p * tiles_q
+    int ws_plane_units;      // 16-byte units per weight plane and channel tile in the workspace (2 * nsteps * 64)
+    FastDiv div_tiles, div_tq;
+};
+
+template <class G, int TERMS, bool WANT_Y>
+__global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
+                                                                        const float* __restrict__ thr, float* __restrict__ y,
+                                                                        uint32_t* __restrict__ bits, WaveArgs g) {
+    constexpr int NT = 2, COLS = 64;
+    extern __shared__ uint4 smem[];
+    uint4* wlds = smem;                                                // [3 planes][NRUNS][64 columns] units of 8 bf16
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: everything derived from the rectangle index stays scalar
+    char* patch = reinterpret_cast<char*>(smem) + 3 * G::WUNITS * 16 + wave * (3 * G::PLANE);     // this wave's three planes
+    const int n0 = (int)blockIdx.y * COLS;
+
+    {   // weights of this channel tile -> LDS (the first NRUNS run slots of each plane hold data)
+        const uint4* src = wexp + (long long)blockIdx.y * 3 * g.ws_plane_units;
+        for (int u = tid; u < 3 * G::WUNITS; u += G::WAVES * 64) {
+            const int pl = u / G::WUNITS, v = u - pl * G::WUNITS;
+            wlds[u] = src[pl * g.ws_plane_units + v];
+        }
+    }
+    __syncthreads();                                                   // the only barrier
+
+    float th[NT];
+    bool cok[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < g.O;
+        th[j] = ((!WANT_Y || bits != nullptr) && cok[j]) ? thr[col] : __builtin_inff();
+    }
+    const int ow = (g.O + 31) / 32;
+
+    // this lane's output pixel inside a rectangle; where its runs start in a patch plane; its column in a weight plane,
+    // the upper half-wave one run further (its run index is 2 * step + 1)
+    // (rows vary fastest over the lanes: with 4 rows of 864 bytes and pixels 24 bytes apart, the sixteen 8-byte reads
+    // LDS serves together then fall on sixteen different bank pairs)
+    const int dp = l32 % G::FP, dq = l32 / G::FP;
+    const char* abase = patch + dp * (G::STRIDE * G::PITCH) + dq * (G::STRIDE * G::CIN * 2);
+    const char* bbase = reinterpret_cast<const char*>(wlds + l32) + half * (COLS * 16);
+    const int rowlen = g.W * G::CIN;                                 // values per image row (H * W * C < 2^31: checked on the host)
+
+    // ---- patch prefetch: lane l holds elements 2l, 2l + 1 of every patch row.  A pair may hang over the left or right
+    // edge of the image row by one element (the padding is not a multiple of 2 elements): it is then loaded one element
+    // further in, and stage() picks the element that is image data.
+    float2_ub pre[G::PR];
+    auto tile_origin = [&](int t, int& n, int& p0, int& q0) {
+        n = fast_div(t, g.div_tiles);
+        const int rem = t - n * (g.tiles_p * g.tiles_q);
+        const int tp = fast_div(rem, g.div_tq);
+        p0 = tp * G::FP;
+        q0 = (rem - tp * g.tiles_q) * G::FQ;
+    };
+    auto request = [&](int t) {                // issues the loads of rectangle t's patch; nothing waits here
+        int n, p0, q0;
+        tile_origin(t, n, p0, q0);
+        const int y0 = p0 * G::STRIDE - g.pad;
+        const int e0 = (q0 * G::STRIDE - g.pad) * G::CIN + 2 * lane;                // first element of this lane's pair in the image row
+        const uint32_t lane_bytes = (uint32_t)min(max(e0, 0), rowlen - 2) * 4u;          // rowlen >= 2 (checked on the host)
+        const float* img = x + (long long)n * g.H * rowlen;                             // uniform
+#pragma unroll
+        for (int r = 0; r < G::PR; ++r) {
+            const int yy = min(max(y0 + r, 0), g.H - 1);                                // uniform: rows outside the image are zeroed in stage()
+            const char* rowp = reinterpret_cast<const char*>(img + yy * rowlen);        // uniform: scalar base + lane offset
+            pre[r] = *reinterpret_cast<const float2_ub*>(rowp + lane_bytes);            // 8 bytes, 4-byte aligned
+        }
+    };
+    auto stage = [&](int t) {                  // splits the prefetched patch of rectangle t into the wave's three planes
+        int n, p0, q0;
+        tile_origin(t, n, p0, q0);
+        const int y0 = p0 * G::STRIDE - g.pad;
+        const int e0 = (q0 * G::STRIDE - g.pad) * G::CIN + 2 * lane;
+        const bool shifted = min(max(e0, 0), rowlen - 2) != e0;
+        // element validity as bit masks: inside the image row and inside the patch row's data (beyond it the row's slack
+        // is zeroed); rows above / below the image are zeroed through a wave-uniform mask -- no branch in the loop
+        const uint32_t m0 = (e0 >= 0 && e0 < rowlen && 2 * lane < G::ROW_ELEMS) ? 0xFFFFFFFFu : 0u;
+        const uint32_t m1 = (e0 + 1 >= 0 && e0 + 1 < rowlen && 2 * lane + 1 < G::ROW_ELEMS) ? 0xFFFFFFFFu : 0u;
+        static_assert(2 * (G::PAIRS - 1) >= G::ROW_ELEMS, "the last pair is slack: the lanes past it repeat its stores of zeros");
+        char* dst = patch + 4 * min(lane, G::PAIRS - 1);
+#pragma unroll
+        for (int r = 0; r < G::PR; ++r) {
+            const uint32_t ym = (unsigned)(y0 + r) < (unsigned)g.H ? 0xFFFFFFFFu : 0u;     // uniform
+            // shifted by one element: the left-edge pair holds its second element first, the right-edge pair its first element second
+            const uint32_t ua = __float_as_uint(shifted ? pre[r][1] : pre[r][0]) & m0 & ym;
+            const uint32_t ub = __float_as_uint(shifted ? pre[r][0] : pre[r][1]) & m1 & ym;
+            const float a = __uint_as_float(ua), b = __uint_as_float(ub);
+            const float ra = a - __uint_as_float(ua & 0xffff0000u), rb = b - __uint_as_float(ub & 0xffff0000u);
+            const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
+            const float la = ra - __uint_as_float(va & 0xffff0000u), lb = rb - __uint_as_float(vb & 0xffff0000u);
+            *reinterpret_cast<uint32_t*>(dst + r * G::PITCH) = __builtin_amdgcn_perm(ub, ua, 0x07060302u);
+            *reinterpret_cast<uint32_t*>(dst + r * G::PITCH + G::PLANE) = __builtin_amdgcn_perm(vb, va, 0x07060302u);
+            *reinterpret_cast<uint32_t*>(dst + r * G::PITCH + 2 * G::PLANE) =
+                __builtin_amdgcn_perm(__float_as_uint(lb), __float_as_uint(la), 0x07060302u);
+        }
+    };
+
+    const int step = (int)gridDim.x * G::WAVES;
+    int t = (int)blockIdx.x * G::WAVES + wave;
+    if (t < g.ntiles) { request(t); stage(t); }
+    for (; t < g.ntiles; t += step) {
+        const bool more = t + step < g.ntiles;
+        if (more) request(t + step);
+
+        // ---- K loop, unrolled in full: run index of this lane = 2 * step + half; every offset is a compile-time constant
+        v16f_bwn acc[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+        // two operand sets: the LDS reads of step st + 1 are issued before the MFMAs of step st
+        uint4 oa[2][3], ob[2][3][NT];
+        auto fetch = [&](auto st_tag) {
+            constexpr int st = decltype(st_tag)::value;
+            constexpr int rho0 = 2 * st, rho1 = 2 * st + 1;
+            constexpr bool upper_real = rho1 < G::NRUNS;               // false only in the last step of an odd run count
+            constexpr int off0 = (rho0 / G::RPR) * G::PITCH + (rho0 % G::RPR) * 16;
+            constexpr int off1 = upper_real ? (rho1 / G::RPR) * G::PITCH + (rho1 % G::RPR) * 16 : off0;
+            const char* asrc = abase + (half ? off1 : off0);           // one vector instruction: the offsets are constants
+            // the upper half-wave's weights: one run further (built into bbase); a run that does not exist re-reads the
+            // lower one's slot and multiplies zeroed inputs
+            const char* bsrc = upper_real ? bbase + rho0 * (COLS * 16) : bbase - half * (COLS * 16) + rho0 * (COLS * 16);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) {
+                const uint2 lo = *reinterpret_cast<const uint2*>(asrc + pl * G::PLANE);
+                const uint2 hi = *reinterpret_cast<const uint2*>(asrc + pl * G::PLANE + 8);
+                oa[st & 1][pl] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    ob[st & 1][pl][j] = *reinterpret_cast<const uint4*>(bsrc + pl * (G::WUNITS * 16) + j * (32 * 16));
+            }
+        };
+        auto multiply = [&](auto st_tag) {
+            constexpr int st = decltype(st_tag)::value;
+            if (2 * st + 1 >= G::NRUNS && half) {
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) oa[st & 1][pl] = make_uint4(0u, 0u, 0u, 0u);
+            }
+            // smallest terms first: (input term, weight term) pairs in order of decreasing index sum
+#pragma unroll
+            for (int sum = (TERMS == 9 ? 4 : 2); sum >= 0; --sum)
+#pragma unroll
+                for (int px = 2; px >= 0; --px) {
+                    const int pw = sum - px;
+                    if (pw < 0 || pw > 2) continue;
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, oa[st & 1][px]),
+                                                                         __builtin_bit_cast(v8bf_bwn, ob[st & 1][pw][j]), acc[j], 0, 0, 0);
+                }
+        };
+        fetch(std::integral_constant<int, 0>{});
+        static_for<G::NSTEPS>([&](auto st_tag) {
+            constexpr int st = decltype(st_tag)::value;
+            if constexpr (st + 1 < G::NSTEPS) fetch(std::integral_constant<int, st + 1>{});
+            multiply(st_tag);
+        });
+
+        // ---- epilogue: threshold -> packed bits (and / or the fp32 sums)
+        int n, p0, q0;
+        tile_origin(t, n, p0, q0);
+        const long long img_pix = (long long)n * g.P * g.Q;
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int lo_row = 8 * (r >> 2) + (r & 3);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const float v = acc[j][r];
+                if (WANT_Y) {
+                    const int m = lo_row + 4 * half;                   // rectangle pixel of this register in this lane
+                    const int mp = m % G::FP, mq = m / G::FP;
+                    if (p0 + mp < g.P && q0 + mq < g.Q && cok[j])
+                        y[(img_pix + (long long)(p0 + mp) * g.Q + q0 + mq) * g.O + n0 + 32 * j + l32] = v;
+                }
+                if (!WANT_Y || bits != nullptr) {
+                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(v >= th[j]);
+                    wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)ball, lo_row, (int)wout[j]);
+                    wout[j] = (uint32_t)bnn_bwn_writelane_i32((int)(uint32_t)(ball >> 32), lo_row + 4, (int)wout[j]);
+                }
+            }
+        }
+        if ((!WANT_Y || bits != nullptr) && lane < 32 && p0 + dp < g.P && q0 + dq < g.Q) {
+            const long long pix = img_pix + (long long)(p0 + dp) * g.Q + q0 + dq;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int wi = (n0 >> 5) + j;
+                if (wi < ow) bits[pix * ow + wi] = wout[j];
+            }
+        }
+        if (more) stage(t + step);             // every read of this rectangle's patch has been consumed by its MFMAs
+    }
+}
+
+template <class G, int TERMS, bool WANT_Y>
+int launch_conv_f32_wave_v(const float* x, const float* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int O,
+                           int pad, int P, int Q, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    const int col_tiles = (int)cdiv(O, 64);
+    WaveArgs g;
+    g.N = N; g.H = H; g.W = W; g.O = O; g.pad = pad; g.P = P; g.Q = Q;
+    g.tiles_p = (int)cdiv(P, G::FP); g.tiles_q = (int)cdiv(Q, G::FQ);
+    g.ntiles = N * g.tiles_p * g.tiles_q;
+    g.ws_plane_units = 2 * G::NSTEPS * 64;
+    g.div_tiles = make_fastdiv((uint32_t)(g.tiles_p * g.tiles_q));
+    g.div_tq = make_fastdiv((uint32_t)g.tiles_q);
+    const size_t per_tile_units = (size_t)3 * g.ws_plane_units;
+    if (workspace_bytes < per_tile_units * 16 * col_tiles) return BNN_ERR_WORKSPACE;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_f32_wave_kernel<G, TERMS, WANT_Y>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
+    if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    uint4* wexp = static_cast<uint4*>(workspace);
+    const int nunits = (int)(per_tile_units * col_tiles);
+    hipLaunchKernelGGL(conv_f32_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, w, wexp, G::CIN, O, G::KS, 64, G::NSTEPS, nunits, 0);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return BNN_ERR_DEVICE;
+    const long long wgs = min(cdiv(g.ntiles, G::WAVES), (long long)max(1, cus / col_tiles));
+    hipLaunchKernelGGL((conv_f32_wave_kernel<G, TERMS, WANT_Y>), dim3((unsigned)wgs, (unsigned)col_tiles), dim3(G::WAVES * 64), G::LDS, s, x,
+                       wexp, thr, y, bits, g);
+    return check_launch();
+}
+
+// The geometries the wave-private kernel is built for.  true: launched (rc receives the status).
+bool try_conv_f32_wave(const float* x, const float* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int C, int O,
+                       int k, int stride, int pad, int P, int Q, int products, void* workspace, size_t workspace_bytes, hipStream_t s,
+                       int* rc) {
+    if (!(k == 7 && stride == 4 && C == 3)) return false;
+    if ((long long)W * C < 2 || (long long)H * W * C >= (1LL << 31)) return false;
+    constexpr int FP = 4, FQ = 8;
+    typedef WaveGeom<7, 4, 3, FP, FQ> G;
+    static_assert(G::LDS <= LDS_MAX, "weights and eight patches fit LDS");
+    if ((long long)N * cdiv(P, FP) * cdiv(Q, FQ) >= (1LL << 31) - 65536) return false;
+    if (y != nullptr)
+        *rc = products == 6 ? launch_conv_f32_wave_v<G, 6, true>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s)
+                            : launch_conv_f32_wave_v<G, 9, true>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s);
+    else
+        *rc = products == 6 ? launch_conv_f32_wave_v<G, 6, false>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s)
+                            : launch_conv_f32_wave_v<G, 9, false>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s);
+    return true;
+}
+
 // Real-valued weights on the same kernel: three weight planes, nine exact products per element pair.
 size_t conv_f32_split_workspace_bytes(int C, int O, int k) {
     const long long seg = (long long)k * C, nruns = k * ((seg + 7) / 8), nsteps = ((nruns + 1) / 2 + 2) / 3 * 3;
@@ -727,6 +1015,9 @@ int launch_conv_f32_split_thr(const float* x, const float* w, const float* thr, 
                               int C, int O, int k, int stride, int pad, int products, void* workspace, size_t workspace_bytes,
                               hipStream_t s) {
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    int rc = BNN_OK;
+    if (try_conv_f32_wave(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, products, workspace, workspace_bytes, s, &rc))
+        return rc;                             // wave-private patches in LDS for the filter geometries that kernel is built for
     if (products == 6)
         return launch_bwn_direct<2, 2, 8, 3, 6>(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);
     return launch_bwn_direct<2, 2, 8, 3>(x, w, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s);

@@ -361,7 +361,13 @@ def test_persistent_bits_input_and_limits(bnn, orc):
 
 @pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
                                    (2, 32, 32, 3, 64, 7, 4, 3), (1, 8, 8, 2, 33, 1, 1, 0), (5, 64, 64, 3, 64, 7, 4, 3),
-                                   (2, 33, 31, 3, 130, 3, 1, 1)])
+                                   (2, 33, 31, 3, 130, 3, 1, 1),
+                                   # the kernel with wave-private patches in LDS (pixel step a multiple of 8 bytes in bf16):
+                                   # ragged rectangles, pad 0 and pad > 0, several channel tiles, one-pixel outputs, a 4-channel
+                                   # stride-1 layer, more images than waves
+                                   (3, 37, 41, 3, 64, 7, 4, 3), (2, 30, 30, 3, 100, 7, 4, 0), (1, 7, 7, 3, 64, 7, 4, 0),
+                                   (2, 19, 23, 4, 40, 3, 1, 1), (1, 5, 6, 8, 33, 3, 1, 1), (300, 9, 9, 3, 64, 5, 4, 2),
+                                   (2, 48, 52, 6, 64, 3, 2, 1), (1, 224, 224, 3, 64, 7, 4, 3)])
 @pytest.mark.parametrize("products", [9, 6])
 def test_conv_f32_split_shapes(bnn, orc, shape, products):
     # the fp32 first layer on the bf16 matrix cores (three-way exact split of inputs and weights; all nine term
