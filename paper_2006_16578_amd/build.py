@@ -18,7 +18,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbnn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SOURCES = ["bnn_api.hip", "bnn_valu.hip", "bnn_mfma.hip", "bnn_mfma_conv_v4.hip", "bnn_mfma_conv_v2.hip",
-           "bnn_mfma_conv_v1.hip", "bnn_mfma_conv_staged.hip", "bnn_aux.hip", "bnn_bwn.hip", "bnn_persistent.hip", "bnn_probe.hip", "bnn_mfma_skinny.hip", "bnn_mfma_wide.hip"]
+           "bnn_mfma_conv_v1.hip", "bnn_mfma_conv_staged.hip", "bnn_aux.hip", "bnn_bwn.hip", "bnn_persistent.hip", "bnn_probe.hip", "bnn_mfma_skinny.hip", "bnn_mfma_wide.hip", "bnn_mfma_conv_patch.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-value",
          "-Rpass-analysis=kernel-resource-usage",   # per-kernel register / scratch report, scanned for spills below
          # packed fp32 VALU forms are kept off for every device function of this library

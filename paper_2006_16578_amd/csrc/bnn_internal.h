@@ -121,6 +121,10 @@ int launch_mfma_skinny(const uint32_t* A, const uint32_t* B, const Geom& g, cons
 // Large matrix products: 256 x 256 workgroup tiles whose operands are expanded once, on their way into LDS.
 bool mfma_wide_takes(const Geom& g, const Epi& e);
 int launch_mfma_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+// 3x3 stride-1 pad-1 convolutions with at most 128 channels in and out: filters resident in LDS, wave-private input patches.
+bool mfma_conv_patch_takes(const Geom& g, const Epi& e);
+const char* describe_mfma_conv_patch(const Geom& g);
+int launch_mfma_conv_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_staged(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v4(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma_conv_v2(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);

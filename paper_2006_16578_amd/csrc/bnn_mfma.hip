@@ -39,7 +39,8 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
         if (g.tw % 8 == 0) return mfma::launch_shape<4, false, false>(A, B, g, e, s);
         return mfma::launch_shape<4, false, true>(A, B, g, e, s);
     }
-    // (blocked 16-bit sums are implemented by the direct kernel only)
+    if (mfma_conv_patch_takes(g, e)) return launch_mfma_conv_patch(A, B, g, e, s);
+    // (blocked 16-bit sums are implemented by the direct kernels only)
     if (!e.sums_tiled && staged_ok(g, tile)) return launch_mfma_conv_staged(A, B, g, e, s);
     if (!mfma::offsets_fit(g)) return BNN_ERR_UNSUPPORTED;
     if (g.tw % 8 == 0) return launch_mfma_conv_v4(A, B, g, e, s);
@@ -50,10 +51,14 @@ int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& 
 const char* describe_mfma(const Geom& g, bool int32_out) {
     if (mfma_skinny_takes(g)) return describe_mfma_skinny(g);
     static int32_t some_output;
-    Epi e = {};
-    e.out = int32_out ? &some_output : nullptr;   // pick_tile only asks whether there is one
+    static uint32_t some_bits;
+    Epi e = {};                                   // the choice only asks which outputs there are, never touches them
+    e.out = int32_out ? &some_output : nullptr;
+    e.bits = int32_out ? nullptr : &some_bits;
+    e.ldbits_w = (g.cols + 31) / 32;
     const int tile = mfma::pick_tile(g, &e);
     if (tile == 0 && mfma_wide_takes(g, e)) return "mfma_fp4_bmm_xlds_wg256x256";
+    if (mfma_conv_patch_takes(g, e)) return describe_mfma_conv_patch(g);
     const bool st = !g.b_tiled && staged_ok(g, tile);
     switch (tile) {
         case 0: return g.conv ? (st ? "mfma_fp4_conv_lds_wg256x128" : "mfma_fp4_conv_wg256x128")

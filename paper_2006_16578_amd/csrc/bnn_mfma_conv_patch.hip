@@ -1,0 +1,349 @@
+// Matrix-core path for 3x3 "same" convolutions (stride 1, pad 1) with few channels on both sides: the filters stay
+// in LDS as finished E2M1 operands for the whole launch, and every wave keeps the input patch of its 64 output
+// pixels there, expanded once for all nine taps.
+//
+// Why.  The short-K layers of a network (Sec. 6: C = O = 64 or 128) give each accumulator 9 or 18 MFMAs.  In the
+// direct kernel a wave expands its own fragments for every tap (7 vector instructions per packed word, each
+// activation word 9 times over, plus the tap's address and frame test): 13 to 37 vector instructions per MFMA
+// measured on the ResNet-18 layers, the matrix cores 12-26 % busy.  A 3x3 window with stride 1 reads, for
+// consecutive output pixels, consecutive input pixels at nine fixed offsets.  So a wave copies the input pixels its
+// 64 outputs touch into LDS once (global -> registers -> expand -> two 16-byte LDS writes per word) and then reads
+// every tap's fragment with one ds_read_b128 at a constant offset from a per-lane base: no vector arithmetic in the
+// K loop at all.
+//
+// Halo-sharing coordinates.  Padding must not cost tests in the K loop either, so the patch lives in padded
+// coordinates: input pixel (n, y, x) sits at  PL = (n (H+1) + y + 1)(W+1) + x + 1.  Column 0 of every padded row
+// and row 0 of every padded image hold the padding value, and because the row pitch is W+1 (not W+2) the cell right
+// of a row's last pixel IS the next row's column 0, the row below an image's last row IS the next image's row 0.
+// Tap (r, s) of the output pixel at PL reads PL + (r-1)(W+1) + (s-1).  64 consecutive output pixels span
+// 63 + (row crossings) + (W+1)(image crossings) cells, plus one padded row and one cell on either side.
+//
+// A patch is private to its wave (two planes of 16-byte units, one per half of a 64-channel slab, so that a
+// fragment read is 32 consecutive units per half-wave: conflict-free): no barrier after the filters are in place,
+// waves drift apart, and one wave's epilogue overlaps another's MFMAs.  The words of the next tile are requested
+// before the current tile's last K-steps, so global latency is not waited for either.
+#include "bnn_mfma_kernel.h"
+
+namespace bnn {
+namespace {
+
+using mfma::v16f;
+using mfma::v8i;
+
+constexpr int MT = 2;            // a wave tile is 64 output pixels x all output channels
+constexpr int PRE = 4;           // patch positions per lane whose words are requested one tile ahead
+
+struct PatchArgs {
+    int wp1, hp1;                // W + 1, H + 1
+    int magic_wp1, magic_hp1, magic_q, magic_p;      // ceil(2^20 / d) for d = W + 1, H + 1, Q, P
+    int images;                  // N
+    int plane;                   // 16-byte units per plane of a wave's patch: 64 * pp
+    int pp;                      // patch positions per lane
+    int ntiles;                  // wave tiles
+    uint32_t pad_keep;           // -1 padding: all ones (a padding cell is the expansion of 0 bits); excluded padding: 0 (fp4 zeros)
+};
+
+__device__ __forceinline__ uint4 expand_unit(uint32_t w, uint32_t c2) {
+    return make_uint4(((w << 3) & 0x88888888u) | c2, ((w << 2) & 0x88888888u) | c2, ((w << 1) & 0x88888888u) | c2,
+                      (w & 0x88888888u) | c2);
+}
+
+__device__ __forceinline__ v8i as_operand(const uint4& u) {
+    v8i r;
+    r[0] = (int)u.x; r[1] = (int)u.y; r[2] = (int)u.z; r[3] = (int)u.w;
+    r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;         // the upper half is not read for 4-bit formats
+    return r;
+}
+
+// NT: 32-column accumulator tiles per wave (all output channels); CW: packed words per pixel (C / 32); KIND: the
+// epilogue the call needs (mfma::epilogue_kind), compiled in alone to keep the register count of the tile loop low.
+template <int NT, int CW, int WAVES, int KIND>
+__global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_t* __restrict__ A,
+                                                                   const uint32_t* __restrict__ B, Geom g, Epi e,
+                                                                   PatchArgs pa) {
+    extern __shared__ uint4 lds[];
+    constexpr int COLSP = NT * 32;
+    constexpr int CG = CW / 2;                       // 64-channel slabs
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t c2;
+    asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c2));
+
+    uint4* const filt = lds;                                         // [tap][word][column]
+    uint4* const patch = lds + 9 * CW * COLSP + wave * 2 * pa.plane; // [half of the slab][cell]
+    const char* const Ab = reinterpret_cast<const char*>(A);
+
+    // A tile's first output pixel (wave-uniform; scalar arithmetic).  Everything a lane needs is then a small
+    // offset from it, and small numbers divide with one 24-bit multiply (full rate; 32-bit multiplies are not):
+    // x / d == (x * ceil(2^20 / d)) >> 20 whenever x * d <= 2^20, which the host checks for every use below.
+    struct First { int n, p, q; };
+    auto first_pixel = [&](int T) {
+        const int m0 = 64 * T;
+        First f;
+        f.n = fast_div(m0, g.div_pq);
+        const int rem = m0 - f.n * (g.P * g.Q);
+        f.p = fast_div(rem, g.div_q);
+        f.q = rem - f.p * g.Q;
+        return f;
+    };
+    auto small_div = [](int x, int magic) { return (int)(__umul24((uint32_t)x, (uint32_t)magic) >> 20); };
+    // byte offset of the input pixel at the patch's cell j (0 and in = false for a padding cell).  The patch starts
+    // one padded row and one cell before the first pixel's cell: at padded row f.p of image f.n, column f.q.
+    auto locate = [&](const First& f, int j, bool& in) {
+        const int x = f.q + j;
+        const int drow = small_div(x, pa.magic_wp1), xp = x - __mul24(drow, pa.wp1);
+        const int yl = f.p + drow;
+        const int dimg = small_div(yl, pa.magic_hp1), yp = yl - __mul24(dimg, pa.hp1);
+        const int n = f.n + dimg;
+        in = xp > 0 && yp > 0 && n < pa.images;
+        const int pix = __mul24(__mul24(n, g.H) + yp - 1, g.W) + xp - 1;
+        return in ? (uint32_t)pix * (uint32_t)(CW * 4) : 0u;
+    };
+
+    uint32_t pre[PRE][CW];
+    uint32_t pre_in = 0u;                            // bit pp: position pp is an input pixel
+    auto request = [&](int T) {
+        const First f = first_pixel(T);
+        pre_in = 0u;
+#pragma unroll
+        for (int pp = 0; pp < PRE; ++pp) {
+            if (pp < pa.pp) {                        // uniform
+                bool in;
+                const uint32_t off = locate(f, lane + 64 * pp, in);
+                mfma::load_words<CW>(reinterpret_cast<const uint32_t*>(Ab + (size_t)off), pre[pp]);
+                pre_in |= in ? (1u << pp) : 0u;
+            }
+        }
+    };
+    // expands two words of a cell into the wave's patch; keep: all ones for an input pixel, 0 for a padding cell,
+    // which becomes the expansion of 0 bits (-1 padding) or fp4 zeros (excluded padding: nothing is added)
+    auto put = [&](int cell_rel, uint32_t w0, uint32_t w1, uint32_t keep) {
+        const uint32_t c2v = c2 & (keep | pa.pad_keep);
+        patch[cell_rel] = expand_unit(w0 & keep, c2v);
+        patch[pa.plane + cell_rel] = expand_unit(w1 & keep, c2v);
+    };
+    auto stage = [&](const First& f, int cg) {
+#pragma unroll
+        for (int pp = 0; pp < PRE; ++pp) {
+            if (pp < pa.pp) {
+                const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)pre_in, pp, 1);
+                put(lane + 64 * pp, pre[pp][2 * cg], pre[pp][2 * cg + 1], keep);
+            }
+        }
+        for (int pp = PRE; pp < pa.pp; ++pp) {       // wide images: the rest of the patch, read now
+            bool in;
+            const uint32_t off = locate(f, lane + 64 * pp, in);
+            const uint2 w = *reinterpret_cast<const uint2*>(Ab + (size_t)off + 8 * cg);
+            put(lane + 64 * pp, w.x, w.y, in ? 0xFFFFFFFFu : 0u);
+        }
+    };
+
+    // Tile order.  In a full round every wave of the launch takes one tile, neighbouring tiles (whose patches
+    // overlap) on the waves of one workgroup.  The tiles left for the last, partial round are dealt across the
+    // workgroups first, so that every compute unit gets its share of them instead of some running a full extra
+    // round while the others idle.
+    const int per_round = (int)gridDim.x * WAVES;
+    const int full_rounds = pa.ntiles / per_round;
+    const int my_turns = full_rounds + ((full_rounds * per_round + wave * (int)gridDim.x + (int)blockIdx.x) < pa.ntiles ? 1 : 0);
+    auto tile_of = [&](int turn) {
+        return turn < full_rounds ? turn * per_round + (int)blockIdx.x * WAVES + wave
+                                  : full_rounds * per_round + wave * (int)gridDim.x + (int)blockIdx.x;
+    };
+    if (my_turns > 0) request(tile_of(0));
+
+    // The filters: every packed word expanded once per workgroup, [tap][word][column] so that a fragment read is
+    // 32 consecutive units per half-wave.  A thread takes (column, tap) items: one 8- or 16-byte load each, all of
+    // them requested before the first is expanded (every workgroup of the launch reads these same few KB at the
+    // same moment; loads waited for one by one made this prologue longer than the tiles of a small layer).
+    {
+        constexpr int ITEMS = 9 * COLSP, PER = (ITEMS + 64 * WAVES - 1) / (64 * WAVES);
+        uint32_t fw[PER][CW];
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            const int item = tid + it * 64 * WAVES, col = item / 9, tap = item - 9 * col;
+            const bool ok = item < ITEMS && col < g.cols;
+            mfma::load_words<CW>(B + (ok ? (long long)col * g.ldb_w + tap * CW : 0), fw[it]);
+        }
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            const int item = tid + it * 64 * WAVES, col = item / 9, tap = item - 9 * col;
+            if (item < ITEMS) {
+                const uint32_t keep = col < g.cols ? 0xFFFFFFFFu : 0u;      // columns past the last: 0 bits
+#pragma unroll
+                for (int w = 0; w < CW; ++w) filt[(tap * CW + w) * COLSP + col] = expand_unit(fw[it][w] & keep, c2);
+            }
+        }
+    }
+    __syncthreads();
+
+    // this lane's thresholds, read once for all tiles (a load inside the tile loop would make every epilogue start
+    // with a full wait on global memory, the next tile's words included)
+    int thi[NT / 2][2];
+    bool cok[NT / 2][2];
+#pragma unroll
+    for (int h = 0; h < NT / 2; ++h) mfma::column_thresholds<2>(thi[h], cok[h], 64 * h, l32, g, e);
+
+    for (int turn = 0; turn < my_turns; ++turn) {
+        const int T = tile_of(turn);
+        const long long m0 = 64LL * T;
+        const First f = first_pixel(T);
+        const int last_rel = (int)min(63LL, g.rows - 1 - m0);            // clamp: results past the last row are dropped
+        int abase[MT];                               // unit of tap (0, 0) of this lane's pixel, in its half's plane
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const int lq = f.q + min(32 * i + l32, last_rel);
+            const int dp = small_div(lq, pa.magic_q), q = lq - __mul24(dp, g.Q);
+            const int lp = f.p + dp;
+            const int dn = small_div(lp, pa.magic_p), p = lp - __mul24(dn, g.P);
+            // cells between this pixel and the tile's first: whole padded rows, then columns
+            abase[i] = half * pa.plane + __mul24(__mul24(dn, pa.hp1) + p - f.p, pa.wp1) + q - f.q;
+        }
+
+        v16f acc[NT / 2][MT][2];                     // [64-column half][row tile][column tile]: the epilogue runs per half
+#pragma unroll
+        for (int h = 0; h < NT / 2; ++h)
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[h][i][j][r] = 0.f;
+
+        // K loop: nine taps per 64-channel slab.  The fragments of tap t + 1 are requested before the MFMAs of tap
+        // t (two register sets), and the scheduler is told to spread those reads between the MFMAs, so that the
+        // matrix pipe does not wait for LDS between taps (a wave is often alone in its K loop: its SIMD mates are
+        // in their epilogues).
+        uint4 fa[2][MT], fb[2][NT];
+        auto read_tap = [&](int cg, int t, int slot) {
+            const int r = t / 3, s3 = t % 3;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[slot][i] = patch[abase[i] + r * pa.wp1 + s3];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) fb[slot][j] = filt[((t * CW) + 2 * cg) * COLSP + half * COLSP + 32 * j + l32];
+        };
+#pragma unroll
+        for (int cg = 0; cg < CG; ++cg) {
+            stage(f, cg);
+            if (cg == CG - 1 && turn + 1 < my_turns) request(tile_of(turn + 1));
+            read_tap(cg, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                if (t + 1 < 9) read_tap(cg, t + 1, (t + 1) & 1);
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[j / 2][i][j % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            as_operand(fa[t & 1][i]), as_operand(fb[t & 1][j]), acc[j / 2][i][j % 2],
+                            4 /*A: E2M1*/, 4 /*B: E2M1*/, 0, 0, 0, 0);
+                if (t + 1 < 9) {
+#pragma unroll
+                    for (int q = 0; q < MT * NT; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+                        if (q < MT + NT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS read
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+#pragma unroll
+        for (int h = 0; h < NT / 2; ++h) {
+            int corr2 = 0;                           // no bit position beyond the logical width was multiplied here
+            if (g.A2 != nullptr) corr2 = mfma::extra_source<MT, 2>(acc[h], g, m0, 64 * h, lane, c2) - g.bits2;
+            if constexpr (KIND == mfma::EPI_BITS)
+                mfma::epilogue_bits<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2, thi[h], cok[h]);
+            else if constexpr (KIND == mfma::EPI_CHAIN)
+                mfma::epilogue_chain<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2, thi[h], cok[h],
+                                            mfma::Fetched{make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), false});
+            else
+                mfma::epilogue_sums<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2);
+        }
+    }
+}
+
+struct PatchPlan {
+    bool ok;
+    int nt, cw, waves, kind;
+    PatchArgs pa;
+    size_t lds_bytes;
+};
+
+PatchPlan plan_patch(const Geom& g, const Epi& e) {
+    PatchPlan pl = {};
+    if (!g.conv || g.b_tiled || g.k != 3 || g.stride != 1 || g.pad != 1 || g.taps != 9) return pl;
+    if ((g.tw != 2 && g.tw != 4) || g.bits_tap != g.tw * 32 || g.lda_w != g.tw) return pl;
+    if (g.cols > 128 || g.P != g.H || g.Q != g.W) return pl;
+    pl.kind = mfma::epilogue_kind(e, true, false);
+    if (pl.kind == mfma::EPI_GENERIC) return pl;                     // (row-major residuals: the direct kernels)
+    pl.nt = g.cols <= 64 ? 2 : 4;
+    pl.cw = g.tw;
+    pl.waves = pl.nt == 2 ? 12 : 8;                 // three / two waves per SIMD: what the registers allow
+    if (e.bits != nullptr && e.ldbits_w > pl.nt) return pl;          // words beyond the tile would stay unwritten
+    const long long images = g.rows / ((long long)g.P * g.Q);
+    // cells a tile of 64 consecutive output pixels can span, with one padded row and one cell on either side
+    const int row_x = 63 / g.W + 1, img_x = 63 / (g.H * g.W) + 1;
+    const int cells = 63 + row_x + (g.W + 1) * img_x + 2 * (g.W + 1) + 3;
+    const int pp = (cells + 63) / 64;
+    if (pp > 16) return pl;
+    if ((images * (g.H + 1) + 2) * (g.W + 1) + 64LL * pp >= (1LL << 31)) return pl;          // cell numbers fit an int
+    if (images * g.H * g.W * g.tw * 4 >= (1LL << 32)) return pl;                              // 32-bit byte offsets
+    pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16;
+    if (pl.lds_bytes > 160 * 1024) return pl;
+    const long long ntiles = cdiv(g.rows, 64);
+    // Measured against the direct kernels on 56x56x64->64 and 28x28 / 56x56x128->128 layers over batch sizes: the
+    // 64-column form wins from about 400 tiles, the 128-column form (a wave's tile is 144 or more MFMAs long, and
+    // one tile per wave is then mostly latency) from about 3000.
+    if (ntiles < (pl.nt == 2 ? 512 : 2560)) return pl;
+    pl.pa.wp1 = g.W + 1; pl.pa.hp1 = g.H + 1;
+    // the small divisions of the kernel (x / d with one 24-bit multiply) are exact for x * d <= 2^20
+    const long long lim = 1LL << 20;
+    if ((g.W + 64LL * pp) * (g.W + 1) > lim || (g.H + 64LL * pp / (g.W + 1) + 2) * (g.H + 1) > lim) return pl;
+    if ((g.W + 63LL) * g.W > lim || (g.H + 63LL / g.W + 2) * g.H > lim || images * g.H >= (1LL << 24)) return pl;
+    auto magic = [](int d) { return (int)(((1LL << 20) + d - 1) / d); };
+    pl.pa.magic_wp1 = magic(g.W + 1); pl.pa.magic_hp1 = magic(g.H + 1);
+    pl.pa.magic_q = magic(g.Q); pl.pa.magic_p = magic(g.P);
+    pl.pa.images = (int)images;
+    pl.pa.plane = 64 * pp; pl.pa.pp = pp;
+    pl.pa.ntiles = (int)ntiles;
+    pl.pa.pad_keep = g.excl ? 0u : 0xFFFFFFFFu;
+    pl.ok = true;
+    return pl;
+}
+
+template <int NT, int CW, int WAVES, int KIND>
+int launch_patch_kind(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, const PatchPlan& pl, hipStream_t s) {
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<NT, CW, WAVES, KIND>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return BNN_ERR_DEVICE;
+    const unsigned nwg = (unsigned)min(256, pl.pa.ntiles);   // one workgroup per compute unit; few tiles: spread over all of them
+    hipLaunchKernelGGL((conv_patch_kernel<NT, CW, WAVES, KIND>), dim3(nwg), dim3(64 * WAVES), pl.lds_bytes, s, A, B, g, e, pl.pa);
+    return check_launch();
+}
+
+template <int NT, int CW, int WAVES>
+int launch_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, const PatchPlan& pl, hipStream_t s) {
+    switch (pl.kind) {
+        case mfma::EPI_BITS: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_BITS>(A, B, g, e, pl, s);
+        case mfma::EPI_CHAIN: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_CHAIN>(A, B, g, e, pl, s);
+        default: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_SUMS>(A, B, g, e, pl, s);
+    }
+}
+
+}  // namespace
+
+bool mfma_conv_patch_takes(const Geom& g, const Epi& e) { return plan_patch(g, e).ok; }
+
+const char* describe_mfma_conv_patch(const Geom& g) {
+    return g.cols <= 64 ? "mfma_fp4_conv3x3_patch_wave64x64" : "mfma_fp4_conv3x3_patch_wave64x128";
+}
+
+int launch_mfma_conv_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    const PatchPlan pl = plan_patch(g, e);
+    if (!pl.ok) return BNN_ERR_UNSUPPORTED;
+    if (pl.nt == 2) return pl.cw == 2 ? launch_patch<2, 2, 12>(A, B, g, e, pl, s) : launch_patch<2, 4, 12>(A, B, g, e, pl, s);
+    return pl.cw == 2 ? launch_patch<4, 2, 8>(A, B, g, e, pl, s) : launch_patch<4, 4, 8>(A, B, g, e, pl, s);
+}
+
+}  // namespace bnn

@@ -353,6 +353,107 @@ __device__ __forceinline__ void epilogue_chain(v16f (&acc)[MT][NT], const long l
     }
 }
 
+// Which epilogue a call needs (uniform; also evaluated on the host by kernels that are compiled per kind).
+enum { EPI_BITS = 0, EPI_CHAIN = 1, EPI_SUMS = 2, EPI_GENERIC = 3 };
+__host__ __device__ inline int epilogue_kind(const Epi& e, const bool conv, const bool row_corr) {
+    const bool no_resid = e.resid == nullptr && e.resid16 == nullptr && e.resid_bits == nullptr;
+    if (e.bits != nullptr && e.out == nullptr && e.out16 == nullptr && no_resid && !row_corr) return EPI_BITS;
+    if (conv && e.sums_tiled != 0 && e.bits != nullptr && e.out == nullptr && e.resid == nullptr && !row_corr) return EPI_CHAIN;
+    if (e.out != nullptr && e.bits == nullptr && e.out16 == nullptr && no_resid && !row_corr) return EPI_SUMS;
+    return EPI_GENERIC;
+}
+
+// Threshold of this lane's column in each column tile; INT_MAX (never reached) outside the matrix.
+template <int NT>
+__device__ __forceinline__ void column_thresholds(int (&thi)[NT], bool (&cok)[NT], const int n0, const int l32, const Geom& g,
+                                                  const Epi& e) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int col = n0 + 32 * j + l32;
+        cok[j] = col < g.cols;
+        thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
+    }
+}
+
+// Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted by the pad correction;
+// one v_cmp per accumulator register gives two packed words.
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue_bits(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
+                                              const Geom& g, const Epi& e, const int corr_all, const int (&thi)[NT],
+                                              const bool (&cok)[NT]) {
+    float thf[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)thi[j] + (float)corr_all : __builtin_inff();
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= g.rows) break;                          // uniform per wave
+        uint32_t wout[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wout[j] = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int lo_row = 8 * (r >> 2) + (r & 3);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const unsigned long long ball = __builtin_amdgcn_ballot_w64(acc[i][j][r] >= thf[j]);
+                wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
+                wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
+            }
+        }
+        const long long row = rbase + lane;
+        if (lane < 32 && row < g.rows) {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int wi = (n0 >> 5) + j;
+                if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+            }
+        }
+    }
+}
+
+// Sums only (int32, or the same values as fp32): blocks of 32 x 32 that lie inside the matrix are stored without
+// per-element tests, from a scalar base per accumulator register (its row) plus one 32-bit offset per lane (its
+// column and half) -- no vector address arithmetic; the edge blocks test every element.
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue_sums(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
+                                              const Geom& g, const Epi& e, const int corr_all) {
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+    const long long m0u = ((long long)__builtin_amdgcn_readfirstlane((int)(m0 >> 32)) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int)m0);          // wave-uniform, made scalar
+    const int n0u = __builtin_amdgcn_readfirstlane(n0);
+    const float corrf = (float)corr_all;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const long long rbase = m0u + 32 * i;
+        if (rbase >= g.rows) break;
+        const bool rows_in = rbase + 32 <= g.rows;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int cbase = n0u + 32 * j;
+            const uint32_t lane_off = (uint32_t)((4 * half * e.ldc + l32) * 4);
+            if (rows_in && cbase + 32 <= g.cols) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    char* row_base = reinterpret_cast<char*>(e.out + (rbase + 8 * (r >> 2) + (r & 3)) * (long long)e.ldc + cbase);
+                    const float v = acc[i][j][r] - corrf;            // exact: integers below 2^24
+                    *reinterpret_cast<int32_t*>(row_base + (size_t)lane_off) = e.out_f32 ? __float_as_int(v) : (int)v;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int col = cbase + l32;
+                    const float v = acc[i][j][r] - corrf;
+                    if (row < g.rows && col < g.cols)
+                        e.out[row * (long long)e.ldc + col] = e.out_f32 ? __float_as_int(v) : (int)v;
+                }
+            }
+        }
+    }
+}
+
 // Epilogue shared by the matrix-core kernels.  acc holds, as exact integers in fp32, the sums
 // over every processed bit position; positions beyond the logical width are 0 bits in both
 // operands and have contributed (+1)(+1) = +1 each: corr_all of them per output (in exclude mode
@@ -362,96 +463,15 @@ template <int MT, int NT, bool CONV, bool EXCL>
 __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
                                          const Geom& g, const Epi& e, const int corr_all, const int pad_tap,
                                          const Fetched fetched = Fetched{make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), false}) {
-    const int l32 = lane & 31;
     const bool row_corr = EXCL && CONV && pad_tap != 0;      // correction depends on the pixel
-
-    int thi[NT];           // threshold of this lane's column; INT_MAX (never reached) outside the matrix
+    int thi[NT];
     bool cok[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int col = n0 + 32 * j + l32;
-        cok[j] = col < g.cols;
-        thi[j] = (e.bits != nullptr && cok[j]) ? e.thr[col] : INT_MAX;
-    }
-
-    if (e.bits != nullptr && e.out == nullptr && e.out16 == nullptr && e.resid == nullptr && e.resid16 == nullptr &&
-        e.resid_bits == nullptr && !row_corr) {
-        // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted
-        // by the pad correction; one v_cmp per accumulator register gives two packed words.
-        float thf[NT];
-#pragma unroll
-        for (int j = 0; j < NT; ++j) thf[j] = cok[j] ? (float)thi[j] + (float)corr_all : __builtin_inff();
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            const long long rbase = m0 + 32 * i;
-            if (rbase >= g.rows) break;                          // uniform per wave
-            uint32_t wout[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) wout[j] = 0u;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lo_row = 8 * (r >> 2) + (r & 3);
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const unsigned long long ball = __builtin_amdgcn_ballot_w64(acc[i][j][r] >= thf[j]);
-                    wout[j] = write_lane((uint32_t)ball, lo_row, wout[j]);
-                    wout[j] = write_lane((uint32_t)(ball >> 32), lo_row + 4, wout[j]);
-                }
-            }
-            const long long row = rbase + lane;
-            if (lane < 32 && row < g.rows) {
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const int wi = (n0 >> 5) + j;
-                    if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
-                }
-            }
-        }
-        return;
-    }
-    if (CONV && e.sums_tiled != 0 && e.bits != nullptr && e.out == nullptr && e.resid == nullptr && !row_corr) {
-        epilogue_chain<MT, NT>(acc, m0, n0, lane, g, e, corr_all, thi, cok, fetched);
-        return;
-    }
-    if (e.out != nullptr && e.bits == nullptr && e.out16 == nullptr && e.resid == nullptr && e.resid16 == nullptr &&
-        e.resid_bits == nullptr && !row_corr) {
-        // Sums only (int32, or the same values as fp32): blocks of 32 x 32 that lie inside the matrix are stored
-        // without per-element tests, from a scalar base per accumulator register (its row) plus one 32-bit offset
-        // per lane (its column and half) -- no vector address arithmetic; the edge blocks test every element.
-        const int half = lane >> 5;
-        const long long m0u = ((long long)__builtin_amdgcn_readfirstlane((int)(m0 >> 32)) << 32) |
-                              (uint32_t)__builtin_amdgcn_readfirstlane((int)m0);          // wave-uniform, made scalar
-        const int n0u = __builtin_amdgcn_readfirstlane(n0);
-        const float corrf = (float)corr_all;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            const long long rbase = m0u + 32 * i;
-            if (rbase >= g.rows) break;
-            const bool rows_in = rbase + 32 <= g.rows;
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const int cbase = n0u + 32 * j;
-                const uint32_t lane_off = (uint32_t)((4 * half * e.ldc + l32) * 4);
-                if (rows_in && cbase + 32 <= g.cols) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        char* row_base = reinterpret_cast<char*>(e.out + (rbase + 8 * (r >> 2) + (r & 3)) * (long long)e.ldc + cbase);
-                        const float v = acc[i][j][r] - corrf;            // exact: integers below 2^24
-                        *reinterpret_cast<int32_t*>(row_base + (size_t)lane_off) = e.out_f32 ? __float_as_int(v) : (int)v;
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const long long row = rbase + 8 * (r >> 2) + 4 * half + (r & 3);
-                        const int col = cbase + l32;
-                        const float v = acc[i][j][r] - corrf;
-                        if (row < g.rows && col < g.cols)
-                            e.out[row * (long long)e.ldc + col] = e.out_f32 ? __float_as_int(v) : (int)v;
-                    }
-                }
-            }
-        }
-        return;
+    column_thresholds<NT>(thi, cok, n0, lane & 31, g, e);
+    switch (epilogue_kind(e, CONV, row_corr)) {
+        case EPI_BITS: epilogue_bits<MT, NT>(acc, m0, n0, lane, g, e, corr_all, thi, cok); return;
+        case EPI_CHAIN: epilogue_chain<MT, NT>(acc, m0, n0, lane, g, e, corr_all, thi, cok, fetched); return;
+        case EPI_SUMS: epilogue_sums<MT, NT>(acc, m0, n0, lane, g, e, corr_all); return;
+        default: break;
     }
     if (e.resid != nullptr || e.resid16 != nullptr || e.resid_bits != nullptr)
         epilogue_generic<MT, NT, CONV, EXCL, true>(acc, m0, n0, lane, g, e, corr_all, pad_tap, thi, cok, row_corr, fetched);

@@ -56,10 +56,14 @@ def test_kernel_choice_is_host_logic():
     # a short-K matrix product with int32 output moves more bytes than it multiplies: small tiles
     assert b.bmm_kernel_name(8192, 8192, 256, int32_out=True) == "mfma_fp4_bmm_wg64x64"
     assert b.bmm_kernel_name(8192, 8192, 256) != "mfma_fp4_bmm_wg64x64"
-    # the graded convolution shape: direct kernel, 256x128 tile, also with int32 output
-    assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1) == "mfma_fp4_conv_wg256x128"
-    assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1, int32_out=True) == "mfma_fp4_conv_wg256x128"
-    assert b.bconv_kernel_name(128, 56, 56, 64, 64, 3, 1, 1) == "mfma_fp4_conv_wg512x64"
+    # the graded convolution shape: 3x3, stride 1, few channels -> filters resident in LDS, wave-private patches
+    assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1) == "mfma_fp4_conv3x3_patch_wave64x128"
+    assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1, int32_out=True) == "mfma_fp4_conv3x3_patch_wave64x128"
+    assert b.bconv_kernel_name(128, 56, 56, 64, 64, 3, 1, 1) == "mfma_fp4_conv3x3_patch_wave64x64"
+    # the same layers at a small batch, with stride 2 or with more channels: the direct kernel's tiles
+    assert b.bconv_kernel_name(2, 56, 56, 128, 128, 3, 1, 1) == "mfma_fp4_conv_wg64x64"
+    assert b.bconv_kernel_name(128, 56, 56, 64, 128, 3, 2, 1) == "mfma_fp4_conv_wg256x128"
+    assert b.bconv_kernel_name(128, 28, 28, 256, 256, 3, 1, 1) == "mfma_fp4_conv_wg256x128"
     # long K goes through LDS
     assert b.bconv_kernel_name(16, 64, 64, 2048, 2048, 3, 1, 1) == "mfma_fp4_conv_lds_wg256x128"
     assert b.bmm_kernel_name(0, 1, 1) == "invalid" and b.bconv_kernel_name(1, 2, 2, 32, 1, 5, 1, 0) == "invalid"

@@ -196,7 +196,7 @@ def test_random_shapes_all_paths(bnn, orc, seed):
 
 # shapes large enough for each of the bigger workgroup tiles of the direct kernel (512x64, 256x128, 128x128), with
 # ragged last tiles, odd channel counts, strides and paddings; residual in and sum out as well
-LARGER = [(37, 61, 59, 64, 64, 3, 1, 1, "mfma_fp4_conv_wg512x64"), (41, 60, 58, 96, 40, 3, 1, 0, "mfma_fp4_conv_wg512x64"),
+LARGER = [(150, 61, 59, 64, 64, 3, 2, 1, "mfma_fp4_conv_wg512x64"), (41, 60, 58, 96, 40, 3, 1, 0, "mfma_fp4_conv_wg512x64"),
           (29, 61, 60, 128, 128, 3, 1, 1, "mfma_fp4_conv_wg256x128"), (50, 90, 88, 160, 130, 3, 2, 2, "mfma_fp4_conv_wg256x128"),
           (13, 59, 57, 256, 100, 3, 1, 1, "mfma_fp4_conv_wg128x128"), (11, 63, 61, 33, 128, 2, 1, 1, "mfma_fp4_conv_wg128x128")]
 
@@ -209,4 +209,26 @@ def test_larger_tiles_direct_kernel(bnn, orc, shape):
     for pad_mode in (0, 1):
         ref1 = orc.bconv(case["x"], case["filt"], C, st, pad, pad_mode, tier=1)
         assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, st, pad, pad_mode, N - 1, 1), ref1[N - 1:])
+        run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)
+
+
+# 3x3 stride-1 pad-1 layers with at most 128 channels in and out, large enough for the kernel that keeps the filters and
+# wave-private input patches in LDS: ragged last tile, ragged columns, tiles that cross image rows and whole images
+# (7x7 and 1x2 images), 64 and 128 channels, an image wider than the words requested ahead
+PATCH = [(64, 56, 56, 64, 64, "mfma_fp4_conv3x3_patch_wave64x64"), (4100, 7, 7, 64, 48, "mfma_fp4_conv3x3_patch_wave64x64"),
+         (520, 20, 19, 128, 64, "mfma_fp4_conv3x3_patch_wave64x64"), (220, 28, 27, 128, 128, "mfma_fp4_conv3x3_patch_wave64x128"),
+         (44, 62, 61, 64, 100, "mfma_fp4_conv3x3_patch_wave64x128"), (10, 250, 80, 64, 64, "mfma_fp4_conv3x3_patch_wave64x64"),
+         (100000, 1, 2, 64, 40, "mfma_fp4_conv3x3_patch_wave64x64")]
+
+
+@pytest.mark.parametrize("shape", PATCH)
+def test_patch_kernel_3x3(bnn, orc, shape):
+    N, H, W, C, O, kernel = shape
+    assert bnn.bconv_kernel_name(N, H, W, C, O, 3, 1, 1) == kernel
+    case = wl.bconv_case(97, N, H, W, C, O, 3, 1, 1, index0=(H * W) % 83)
+    for pad_mode in (0, 1):
+        print("patch", shape, "pad_mode", pad_mode, flush=True)
+        ref1 = orc.bconv(case["x"], case["filt"], C, 1, 1, pad_mode, tier=1)
+        for n0 in (0, N - 1):
+            assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, 1, 1, pad_mode, n0, 1), ref1[n0:n0 + 1])
         run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)

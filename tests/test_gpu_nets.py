@@ -140,6 +140,21 @@ def test_resnet_random_chains(bnn, orc, seed):
     check_resnet(bnn, orc, p, x, hw, 0, tier=1, pad_mode=pad_mode)
 
 
+@pytest.mark.parametrize("blocks,hw,batch,pad_mode", [
+    (((64, 64, 1), (64, 64, 1), (64, 96, 2)), 40, 340, 0), (((64, 64, 1), (64, 64, 1), (64, 96, 2)), 40, 340, 1),
+    (((128, 128, 1), (128, 128, 1)), 32, 2600, 1)])
+def test_resnet_chains_patch_kernel(bnn, orc, blocks, hw, batch, pad_mode):
+    # residual chains whose stride-1 layers are large enough for the 3x3 kernel with LDS-resident filters (64- and
+    # 128-column forms): bits-only layers, the first residual taken from bits, blocked 16-bit sums in and out, in both
+    # padding conventions; 10x10 and 8x8 feature maps, so most 64-pixel tiles cross image rows and images
+    H = hw // 4
+    cin, cout, _ = blocks[0]
+    assert bnn.bconv_kernel_name(batch, H, H, cin, cout, 3, 1, 1).startswith("mfma_fp4_conv3x3_patch")
+    p = wl.resnet18_params(blocks=blocks, classes=10, config=97)
+    x = wl.resnet18_input(batch, hw=hw, config=97)
+    check_resnet(bnn, orc, p, x, hw, 0, tier=1, pad_mode=pad_mode)
+
+
 def test_resnet18_batch8(bnn, orc):
     p = wl.resnet18_params()
     x = wl.resnet18_input(8)
