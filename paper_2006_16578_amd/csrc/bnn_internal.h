@@ -74,7 +74,11 @@ struct Epi {
     // 1: resid16 / out16 are stored in blocks of 32 rows x 32 columns (ldc a multiple of 32, rows padded to 32),
     // each block in the order the matrix cores hand out a 32x32 accumulator (sums16_index): a lane's 16 values
     // are 32 contiguous bytes, so the residual moves as two 16-byte accesses per lane instead of sixteen
-    // 2-byte ones.  The tensor is private to the layer chain, which produces and consumes it with these kernels.
+    // 2-byte ones.  The tensor is private to the layer chain, which produces and consumes it with these kernels;
+    // which element a lane's register holds is private to the kernel that writes a block (the 3x3 patch kernel keeps
+    // 16 channels of one pixel per lane, the others one channel of 16 pixels).  That is safe because a block's sums
+    // are only ever read by the second convolution of the next identity block: the same geometry and epilogue kind,
+    // hence the same kernel choice.
     int sums_tiled;
     int ldc;               // elements between rows of out / resid
     int out_f32;           // 1: `out` receives the sums converted to fp32 (exact: |v| < 2^24) instead of int32

@@ -55,6 +55,103 @@ __device__ __forceinline__ v8i as_operand(const uint4& u) {
     return r;
 }
 
+// 16 sign bits of a lane's registers (bit r = register r = channel 8a + 4 half + b, r = 4a + b) -> that lane pair's
+// packed word of 32 channels with a 1 where the value is NOT negative; both half-waves end up with the whole word.
+__device__ __forceinline__ uint32_t word_from_signs(uint32_t m, int half) {
+    m = (m | (m << 8)) & 0x00FF00FFu;                // nibble a -> byte a
+    m = (m | (m << 4)) & 0x0F0F0F0Fu;
+    m <<= 4 * half;                                  // this half-wave's channels of each byte
+    const auto both = __builtin_amdgcn_permlane32_swap(m, m, false, false);      // meet the other half-wave
+    return ~(both[0] | both[1]);
+}
+
+// Epilogue of a residual layer inside a layer chain with swapped operand roles: a lane holds 16 channels of one pixel,
+// accumulators started at 0.5 - threshold (`start`: LDS, [column tile][half-wave][register]).  Blocked 16-bit sums in
+// and / or out (a lane's 16 values are 32 contiguous bytes of the block, in this kernel's own order), or the +1/-1 of
+// packed bits as the residual: each lane reads the word of its own pixel, and a register's channel is a compile-time
+// bit position once the word is shifted by the half-wave's 4.  corr: what the second source added beyond its logical
+// width.  fp32 throughout: half-integers below 2^23, exact.
+template <int MT>
+__device__ __forceinline__ void epilogue_chain_swapped(v16f (&acc)[MT][2], const long long m0, const int n0, const int lane,
+                                                       const Geom& g, const Epi& e, const float* start, const int corr) {
+    const int l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const long long rbase = m0 + 32 * i;
+        if (rbase >= g.rows) break;                              // uniform per wave
+        uint32_t wout[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const bool cblk = n0 + 32 * j < g.cols;              // uniform: whole blocks (cols is a multiple of 32)
+            const long long blk = ((rbase >> 5) * (long long)(e.ldc >> 5) + ((n0 >> 5) + j)) * 1024 + lane * 16;
+            float rv[16];
+            if (e.resid16 != nullptr) {
+                uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
+                if (cblk) {
+                    const uint4* src = reinterpret_cast<const uint4*>(e.resid16 + blk);
+                    lo = src[0]; hi = src[1];
+                }
+                const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    rv[r] = (float)((r & 1) ? ((int)w[r >> 1] >> 16) : (int)(short)(w[r >> 1] & 0xffffu));
+            } else if (e.resid_bits != nullptr) {
+                const long long rrow = min(rbase + l32, g.rows - 1);
+                const int wi = min((n0 >> 5) + j, e.ld_resid_bits_w - 1);
+                const uint32_t y = ~e.resid_bits[rrow * (long long)e.ld_resid_bits_w + wi] >> (4 * half);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {                   // bit 1 -> +1.0, bit 0 -> -1.0
+                    const int c = 8 * (r >> 2) + (r & 3);
+                    rv[r] = __uint_as_float(((y << (31 - c)) & 0x80000000u) | 0x3f800000u);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) rv[r] = 0.f;
+            }
+            if (corr != 0) {                                     // uniform: bit positions past the second source's width
+                const float corrf = (float)corr;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) rv[r] -= corrf;
+            }
+            const float4* sv = reinterpret_cast<const float4*>(start + ((((n0 >> 5) + j) * 2 + half) * 16));
+            float st[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = sv[q];
+                st[4 * q] = v.x; st[4 * q + 1] = v.y; st[4 * q + 2] = v.z; st[4 * q + 3] = v.w;
+            }
+            uint32_t m = 0u;
+            int vs[16];
+#pragma unroll
+            for (int r = 15; r >= 0; --r) {
+                const float sum = acc[i][j][r] + rv[r];
+                m = __builtin_amdgcn_alignbit(m, __float_as_uint(sum), 31);
+                vs[r] = (int)(sum - st[r]);                      // the integer sum itself
+            }
+            if (e.out16 != nullptr && cblk) {
+                uint32_t pk[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const mfma::v2s two = __builtin_amdgcn_cvt_pk_i16(vs[2 * q], vs[2 * q + 1]);
+                    pk[q] = (uint32_t)(uint16_t)two[0] | ((uint32_t)(uint16_t)two[1] << 16);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(e.out16 + blk);
+                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            }
+            wout[j] = word_from_signs(m, half);
+        }
+        const long long row = rbase + lane;
+        if (lane < 32 && row < g.rows) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int wi = (n0 >> 5) + j;
+                if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+            }
+        }
+    }
+}
+
 // NT: 32-column accumulator tiles per wave (all output channels); CW: packed words per pixel (C / 32); KIND: the
 // epilogue the call needs (mfma::epilogue_kind), compiled in alone to keep the register count of the tile loop low.
 template <int NT, int CW, int WAVES, int KIND>
@@ -72,6 +169,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
 
     uint4* const filt = lds;                                         // [tap][word][column]
     uint4* const patch = lds + 9 * CW * COLSP + wave * 2 * pa.plane; // [half of the slab][cell]
+    // bits kind: start values of the accumulators, [column tile][half-wave][register] (see SWAPPED below)
+    float* const start = reinterpret_cast<float*>(lds + 9 * CW * COLSP + WAVES * 2 * pa.plane);
     const char* const Ab = reinterpret_cast<const char*>(A);
 
     // A tile's first output pixel (wave-uniform; scalar arithmetic).  Everything a lane needs is then a small
@@ -175,6 +274,23 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
             }
         }
     }
+    // Bits kind: the operand roles are swapped (filters as the MFMA's row operand), so that a lane ends up with 16
+    // output channels of ONE pixel and can pack its own bits: every accumulator starts at 0.5 - threshold of its
+    // channel (exact: thresholds are clamped to +-2^20, beyond every reachable sum, and partial sums stay half-integers
+    // below 2^23), the output bit is then "not the sign bit", and 16 v_alignbit collect a lane's 16 signs -- against
+    // a compare, a wait state and two lane writes per register when a lane holds one channel of 16 pixels.  Channels
+    // past the last start at -infinity: their bits stay 0.
+    constexpr bool SWAPPED = KIND != mfma::EPI_SUMS;
+    if (SWAPPED && tid < COLSP) {
+        const int col = tid, jt = col >> 5, c = col & 31;
+        const int reg = 4 * (c >> 3) + (c & 3), hf = (c >> 2) & 1;     // channel 8a + 4 hf + b of a tile: register 4a + b
+        float v = -__builtin_inff();
+        if (col < g.cols) {
+            const int lim = 1 << 20;                 // beyond every reachable sum (K <= 1152 here, residual sums are 16-bit)
+            v = 0.5f - (float)max(-lim, min(lim, e.thr[col]));
+        }
+        start[(jt * 2 + hf) * 16 + reg] = v;
+    }
     __syncthreads();
 
     // this lane's thresholds, read once for all tiles (a load inside the tile loop would make every epilogue start
@@ -206,9 +322,20 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j) {
+                    if constexpr (SWAPPED) {         // 0.5 - threshold of the register's channel, straight from LDS
+                        const float4* sv = reinterpret_cast<const float4*>(start + ((2 * h + j) * 2 + half) * 16);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[h][i][j][r] = 0.f;
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 v = sv[q];
+                            acc[h][i][j][4 * q] = v.x; acc[h][i][j][4 * q + 1] = v.y;
+                            acc[h][i][j][4 * q + 2] = v.z; acc[h][i][j][4 * q + 3] = v.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[h][i][j][r] = 0.f;
+                    }
+                }
 
         // K loop: nine taps per 64-channel slab.  The fragments of tap t + 1 are requested before the MFMAs of tap
         // t (two register sets), and the scheduler is told to spread those reads between the MFMAs, so that the
@@ -234,9 +361,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
                 for (int i = 0; i < MT; ++i)
 #pragma unroll
                     for (int j = 0; j < NT; ++j)
-                        acc[j / 2][i][j % 2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            as_operand(fa[t & 1][i]), as_operand(fb[t & 1][j]), acc[j / 2][i][j % 2],
-                            4 /*A: E2M1*/, 4 /*B: E2M1*/, 0, 0, 0, 0);
+                        acc[j / 2][i][j % 2] = SWAPPED
+                            ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(fb[t & 1][j]), as_operand(fa[t & 1][i]),
+                                                                             acc[j / 2][i][j % 2], 4, 4, 0, 0, 0, 0)
+                            : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(fa[t & 1][i]), as_operand(fb[t & 1][j]),
+                                                                             acc[j / 2][i][j % 2], 4 /*A: E2M1*/, 4 /*B: E2M1*/, 0, 0, 0, 0);
                 if (t + 1 < 9) {
 #pragma unroll
                     for (int q = 0; q < MT * NT; ++q) {
@@ -251,17 +380,36 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
 #pragma unroll
         for (int h = 0; h < NT / 2; ++h) {
             int corr2 = 0;                           // no bit position beyond the logical width was multiplied here
-            if (g.A2 != nullptr) corr2 = mfma::extra_source<MT, 2>(acc[h], g, m0, 64 * h, lane, c2) - g.bits2;
-            if constexpr (KIND == mfma::EPI_BITS)
-                mfma::epilogue_bits<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2, thi[h], cok[h]);
-            else if constexpr (KIND == mfma::EPI_CHAIN)
-                mfma::epilogue_chain<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2, thi[h], cok[h],
-                                            mfma::Fetched{make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u), false});
-            else
+            if (g.A2 != nullptr) corr2 = mfma::extra_source<MT, 2, SWAPPED>(acc[h], g, m0, 64 * h, lane, c2) - g.bits2;
+            if constexpr (KIND == mfma::EPI_BITS) {
+                // lane (pixel l32, half): register r = 4a + b holds channel 8a + 4 half + b of column tile 2h + j
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    uint32_t wout[2];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        uint32_t m = 0u;             // bit r: sign of register r
+#pragma unroll
+                        for (int r = 15; r >= 0; --r) m = __builtin_amdgcn_alignbit(m, __float_as_uint(acc[h][i][j][r]), 31);
+                        wout[j] = word_from_signs(m, half);
+                    }
+                    const long long row = m0 + 32 * i + lane;
+                    if (lane < 32 && row < g.rows) {
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            if (2 * h + j < e.ldbits_w) e.bits[row * e.ldbits_w + 2 * h + j] = wout[j];
+                    }
+                }
+            } else if constexpr (KIND == mfma::EPI_CHAIN) {
+                epilogue_chain_swapped<MT>(acc[h], m0, 64 * h, lane, g, e, start, corr2);
+            } else
                 mfma::epilogue_sums<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2);
         }
     }
 }
+
+// Waves per workgroup: what the registers allow (three per SIMD with 64-column tiles, two with 128-column tiles).
+constexpr int waves_for(int nt, int kind) { (void)kind; return nt == 2 ? 12 : 8; }
 
 struct PatchPlan {
     bool ok;
@@ -277,9 +425,10 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     if (g.cols > 128 || g.P != g.H || g.Q != g.W) return pl;
     pl.kind = mfma::epilogue_kind(e, true, false);
     if (pl.kind == mfma::EPI_GENERIC) return pl;                     // (row-major residuals: the direct kernels)
+    if (pl.kind == mfma::EPI_BITS && g.A2 != nullptr) return pl;     // (the bits-only form has no second source)
     pl.nt = g.cols <= 64 ? 2 : 4;
     pl.cw = g.tw;
-    pl.waves = pl.nt == 2 ? 12 : 8;                 // three / two waves per SIMD: what the registers allow
+    pl.waves = waves_for(pl.nt, pl.kind);
     if (e.bits != nullptr && e.ldbits_w > pl.nt) return pl;          // words beyond the tile would stay unwritten
     const long long images = g.rows / ((long long)g.P * g.Q);
     // cells a tile of 64 consecutive output pixels can span, with one padded row and one cell on either side
@@ -289,7 +438,7 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     if (pp > 16) return pl;
     if ((images * (g.H + 1) + 2) * (g.W + 1) + 64LL * pp >= (1LL << 31)) return pl;          // cell numbers fit an int
     if (images * g.H * g.W * g.tw * 4 >= (1LL << 32)) return pl;                              // 32-bit byte offsets
-    pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16;
+    pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16 + (size_t)pl.nt * 2 * 16 * 4;
     if (pl.lds_bytes > 160 * 1024) return pl;
     const long long ntiles = cdiv(g.rows, 64);
     // Measured against the direct kernels on 56x56x64->64 and 28x28 / 56x56x128->128 layers over batch sizes: the
@@ -322,12 +471,15 @@ int launch_patch_kind(const uint32_t* A, const uint32_t* B, const Geom& g, const
     return check_launch();
 }
 
-template <int NT, int CW, int WAVES>
+template <int NT, int CW>
 int launch_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, const PatchPlan& pl, hipStream_t s) {
     switch (pl.kind) {
-        case mfma::EPI_BITS: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_BITS>(A, B, g, e, pl, s);
-        case mfma::EPI_CHAIN: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_CHAIN>(A, B, g, e, pl, s);
-        default: return launch_patch_kind<NT, CW, WAVES, mfma::EPI_SUMS>(A, B, g, e, pl, s);
+        case mfma::EPI_BITS:
+            return launch_patch_kind<NT, CW, waves_for(NT, mfma::EPI_BITS), mfma::EPI_BITS>(A, B, g, e, pl, s);
+        case mfma::EPI_CHAIN:
+            return launch_patch_kind<NT, CW, waves_for(NT, mfma::EPI_CHAIN), mfma::EPI_CHAIN>(A, B, g, e, pl, s);
+        default:
+            return launch_patch_kind<NT, CW, waves_for(NT, mfma::EPI_SUMS), mfma::EPI_SUMS>(A, B, g, e, pl, s);
     }
 }
 
@@ -342,8 +494,8 @@ const char* describe_mfma_conv_patch(const Geom& g) {
 int launch_mfma_conv_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
     const PatchPlan pl = plan_patch(g, e);
     if (!pl.ok) return BNN_ERR_UNSUPPORTED;
-    if (pl.nt == 2) return pl.cw == 2 ? launch_patch<2, 2, 12>(A, B, g, e, pl, s) : launch_patch<2, 4, 12>(A, B, g, e, pl, s);
-    return pl.cw == 2 ? launch_patch<4, 2, 8>(A, B, g, e, pl, s) : launch_patch<4, 4, 8>(A, B, g, e, pl, s);
+    if (pl.nt == 2) return pl.cw == 2 ? launch_patch<2, 2>(A, B, g, e, pl, s) : launch_patch<2, 4>(A, B, g, e, pl, s);
+    return pl.cw == 2 ? launch_patch<4, 2>(A, B, g, e, pl, s) : launch_patch<4, 4>(A, B, g, e, pl, s);
 }
 
 }  // namespace bnn

@@ -480,8 +480,9 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[MT][NT], const long long m0
 }
 
 // The optional second source of a Geom (fused 1x1 downsample shortcut): a handful of K-steps read
-// straight from global memory.  Returns the number of bit positions it multiplied.
-template <int MT, int NT>
+// straight from global memory.  Returns the number of bit positions it multiplied.  SWAP: the filters are the MFMA's
+// row operand (accumulators hold 16 channels of one pixel per lane instead of one channel of 16 pixels).
+template <int MT, int NT, bool SWAP = false>
 __device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, const long long m0, const int n0,
                                             const int lane, const uint32_t c2) {
     const int l32 = lane & 31;
@@ -512,7 +513,8 @@ __device__ __forceinline__ int extra_source(v16f (&acc)[MT][NT], const Geom& g, 
         for (int i = 0; i < MT; ++i)
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 0, 0, 0);
+                acc[i][j] = SWAP ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(eb[j], ea[i], acc[i][j], 4, 4, 0, 0, 0, 0)
+                                 : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 0, 0, 0);
     }
     return steps * 64;
 }
