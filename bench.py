@@ -475,6 +475,16 @@ def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 
             if batch == 8:
                 tg = _time_graph(torch, lambda: rnet.forward(x, out=o), 30)
                 res["batch8"]["hip_graph_replay_ms"] = round(tg, 4)
+                # Sec. 6.2 / Table 10 for a residual network: all 16 block convolutions as ONE persistent kernel
+                # (stem and head stay ordinary launches), against one launch per layer; the same kernel with its
+                # barriers switched off prices the synchronisation (results undefined, timing only)
+                pers = {}
+                for cap in (32, 64, 128, 256):
+                    tp = _time_gpu(torch, lambda: rnet.forward_persistent(x, out=o, grid_cap=cap), 30)
+                    tn = _time_gpu(torch, lambda: rnet.forward_persistent(x, out=o, grid_cap=cap, no_sync=True), 30)
+                    pers["grid_%d" % cap] = {"ms": round(tp, 4), "without_barriers_ms": round(tn, 4),
+                                             "barrier_share": round(max(tp - tn, 0.0) / tp, 3)}
+                res["batch8"]["persistent_blocks_kernel"] = pers
             if batch == 256:
                 xs, w, th = x, to_dev(p["stem_w"]), to_dev(p["stem_thr"])
                 ts = _time_gpu(torch, lambda: bnn.conv_f32_split_thr(xs, w, th, 4, 3, products=6), 5)
@@ -499,9 +509,16 @@ def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 
             r = {}
             for batch in (big, 8):
                 x = to_dev(wl.cnn_input(name, batch))
+                persistent_ok = batch == 8 and name in ("cifar_vgg", "cifar_resnet14")
                 o = torch.empty((batch, spec["classes"]), dtype=torch.int32, device=dev)
                 t = _time_gpu(torch, lambda: net5.forward(x, out=o), 5 if batch == big else 20)
                 r["batch%d" % batch] = {"ms": round(t, 4), "images_per_s": round(batch / t * 1e3, 1)}
+                if persistent_ok:       # runs of layers between pools as persistent kernels (Sec. 6.2), as for ResNet-18
+                    tp = _time_gpu(torch, lambda: net5.forward_persistent(x, out=o), 20)
+                    tn = _time_gpu(torch, lambda: net5.forward_persistent(x, out=o, no_sync=True), 20)
+                    r["batch8"]["persistent_runs_ms"] = round(tp, 4)
+                    r["batch8"]["persistent_without_barriers_ms"] = round(tn, 4)
+                    r["batch8"]["barrier_share_of_persistent"] = round(max(tp - tn, 0.0) / tp, 3)
                 if batch == big:
                     # the first layer alone: binarized weights on the bf16 matrix cores (what the network uses, Sec. 6.1),
                     # and the same shape with real-valued weights on the fp32 matrix cores

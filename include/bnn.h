@@ -310,21 +310,29 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch,
 #define BNN_STATIC_WORKSPACE_BYTES (32u << 20)
 int bnn_static_workspace_init(void);
 int bnn_net_forward_static(bnn_net* net, const void* input, void* output, int batch, int path, void* stream);
-/* The same forward as ONE kernel launch (Sec. 6.2: every layer a device function of one kernel, a device-wide
- * barrier between layers).  Supported: an input layer (u8 or bits) followed by fully-connected layers only, at
- * most 8 of them; anything else returns BNN_ERR_UNSUPPORTED (use bnn_net_forward).  Same arguments, workspace
- * and results as bnn_net_forward.  The grid never exceeds what the device holds at once; a barrier
- * that is not reached by all workgroups within a few tenths of a second (other work holding the compute units)
- * makes every workgroup leave the kernel: the output is then undefined and bnn_net_persistent_status reports
- * it.  Calls that overlap on one device must use different workspaces.
+/* The same forward with every unbroken run of fully-connected layers, 3x3 convolutions and residual blocks as ONE
+ * kernel launch (Sec. 6.2: every layer a device function of one kernel, a device-wide barrier between layers).
+ * An MLP (u8 or bits input, FC layers) is one launch in all; a ResNet-shaped net runs its first layer and its head
+ * as the ordinary kernels and all blocks in one launch between them; a pooling layer ends a run.  Supported inside
+ * a run: FC layers, and 3x3 convolutions (also those of residual blocks, any stride, both paddings) of 64, 128, 256
+ * or 512 input channels; at most 48 such layers per forward; anything else returns BNN_ERR_UNSUPPORTED (use
+ * bnn_net_forward).  Same arguments, workspace and results as bnn_net_forward.  The layer table of a run travels
+ * through the workspace: the first forward of a net at a given batch and workspace uploads it and WAITS for the
+ * stream once; later forwards with the same arguments enqueue only.  The grid never exceeds what the device holds at
+ * once; a barrier that is not reached by all workgroups within a few tenths of a second (other work holding the
+ * compute units) makes every workgroup leave the kernel: the output is then undefined and
+ * bnn_net_persistent_status reports it.  Calls that overlap on one device must use different workspaces.
  * flags: 0, or a combination of
  *   BNN_PERSIST_NO_SYNC          skip the barriers -- the results are then UNDEFINED; it exists only to measure
  *                                what the barriers cost;
  *   BNN_PERSIST_GIVE_UP_AT_ONCE  a workgroup that finds a barrier not yet complete gives up at its first poll
  *                                (every workgroup still leaves the kernel normally) -- results UNDEFINED; it
- *                                exists to exercise the time-out path and its status report. */
+ *                                exists to exercise the time-out path and its status report;
+ *   BNN_PERSIST_GRID_CAP(n)      at most n workgroups (1 .. 65535; a barrier costs more the more workgroups meet at
+ *                                it).  Default: 128 for nets with convolutions, the device's capacity otherwise. */
 #define BNN_PERSIST_NO_SYNC 1
 #define BNN_PERSIST_GIVE_UP_AT_ONCE 2
+#define BNN_PERSIST_GRID_CAP(n) (((n) & 0xFFFF) << 8)
 int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch,
                                void* workspace, size_t workspace_bytes, int flags, void* stream);
 /* Whether the LAST bnn_net_forward_persistent of this net gave up at a barrier: *aborted = 1 (its output is

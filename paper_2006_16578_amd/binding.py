@@ -602,10 +602,11 @@ class Net:
                    "bnn_net_persistent_status")
         return aborted.value != 0
 
-    def forward_persistent(self, x, out=None, no_sync: bool = False, give_up_at_once: bool = False):
-        """Same forward in one kernel launch (FC chains only).  no_sync skips the device-wide barriers (results
-        undefined, for timing the barriers only); give_up_at_once makes every barrier wait time out at its first
-        poll (results undefined, for testing the time-out report)."""
+    def forward_persistent(self, x, out=None, no_sync: bool = False, give_up_at_once: bool = False, grid_cap: int = 0):
+        """Same forward with every run of FC / 3x3 convolution / residual-block layers as one kernel launch.  no_sync
+        skips the device-wide barriers (results undefined, for timing the barriers only); give_up_at_once makes every
+        barrier wait time out at its first poll (results undefined, for testing the time-out report); grid_cap > 0
+        bounds the number of workgroups."""
         _dev(x, self._in_dtype, None, "input")
         batch = x.shape[0]
         need = self.workspace_bytes(batch)
@@ -616,7 +617,8 @@ class Net:
         with torch.cuda.device(x.device):
             _check(load().bnn_net_forward_persistent(self._h, _ptr(x), _ptr(out), batch, _ptr(self._ws),
                                                      ctypes.c_size_t(self._ws.numel()),
-                                                     (1 if no_sync else 0) | (2 if give_up_at_once else 0), _stream(x)),
+                                                     (1 if no_sync else 0) | (2 if give_up_at_once else 0) | ((int(grid_cap) & 0xFFFF) << 8),
+                                                     _stream(x)),
                    "bnn_net_forward_persistent")
         return out
 

@@ -1,4 +1,7 @@
 // C ABI of libbnn: argument validation, shape bookkeeping and kernel dispatch.
+#include <string.h>
+
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -13,7 +16,27 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int words(int nbits) { return (nbits + 31) / 32; }
 inline int round4(int v) { return (v + 3) / 4 * 4; }
 
+// While a persistent forward collects a chain, a layer's contraction is recorded here instead of launched.
+thread_local std::vector<PersistLayer>* capture_sink = nullptr;
+
 int dispatch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, int path, hipStream_t s) {
+    if (capture_sink != nullptr) {
+        if (capture_sink->size() >= (size_t)PERSIST_MAX_LAYERS || g.b_tiled) return BNN_ERR_UNSUPPORTED;
+        PersistLayer P = {};
+        P.A = A; P.B = B; P.g = g; P.e = e;
+        if (g.conv) {
+            const int v = persist_conv_variant(g);
+            if (v < 0) return BNN_ERR_UNSUPPORTED;
+            P.variant = 1 + v;
+        } else {
+            if (g.lda_w >= (1 << 20) || g.ldb_w >= (1 << 21)) return BNN_ERR_UNSUPPORTED;
+            P.variant = 0;
+        }
+        const int col_span = (e.bits != nullptr) ? std::max(g.cols, e.ldbits_w * 32) : g.cols;   // pad words are written too
+        P.gx = (int)cdiv(g.rows, 64); P.gy = (int)cdiv(col_span, 64);
+        capture_sink->push_back(P);
+        return BNN_OK;
+    }
     switch (path) {
         case BNN_PATH_VALU: return launch_valu(A, B, g, e, s);
         case BNN_PATH_MFMA: return launch_mfma(A, B, g, e, s);
@@ -127,6 +150,9 @@ struct bnn_net {
     // results of the last forward, for bnn_net_layer_bits
     const char* last_ws = nullptr; int last_batch = 0;
     const unsigned* last_persist_sync = nullptr;   // barrier counter and abort flag of the last persistent forward
+    // layer table of the last persistent forward as uploaded, and where: an identical table is not uploaded again
+    std::vector<PersistLayer> persist_uploaded;
+    const void* persist_uploaded_at = nullptr;
 };
 
 namespace {
@@ -143,6 +169,7 @@ struct Plan {
     size_t resid_bytes = 0;
     size_t bwn_off = 0, bwn_bytes = 0;   // expanded first-layer weights (first layer with binarized weights only)
     size_t sync_off = 0;                 // barrier counter and abort flag of the persistent kernel
+    size_t table_off = 0;                // layer table of the persistent kernel
     size_t pool_off = 0;                 // pooled sums [batch][C] int32 of a HEAD layer
     int rc = BNN_OK;
 };
@@ -228,6 +255,7 @@ Plan plan(bnn_net* net, int batch) {
         off += align256(pl.bwn_bytes);
     }
     pl.sync_off = off; off += 256;
+    pl.table_off = off; off += align256(sizeof(PersistLayer) * PERSIST_MAX_LAYERS);
     pl.pool_off = off; off += head_pool_bytes;
     pl.total = off;
     return pl;
@@ -570,16 +598,51 @@ int bnn_net_workspace_bytes(const bnn_net* net, int batch, size_t* bytes) {
     return BNN_OK;
 }
 
-int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, void* workspace, size_t workspace_bytes,
-                    int path, void* stream) {
-    if (!net || !input || batch < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
-    Plan pl = plan(net, batch);
-    if (pl.rc != BNN_OK) return pl.rc;
-    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BNN_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BNN_ERR_ALIGNMENT;
-    char* ws = static_cast<char*>(workspace);
-    net->last_ws = ws; net->last_batch = batch;
+namespace {
 
+// State of a persistent forward: the run of layers collected so far and how to launch it.
+struct PersistCtx {
+    bnn_net* net;
+    char* ws;
+    const Plan* pl;
+    int sync, spin_limit, max_grid;
+    hipStream_t stream;
+    PersistNet pn = {};
+    std::vector<PersistLayer> segment;
+    size_t table_used = 0;          // entries of the table region already taken by earlier runs of this forward
+    std::vector<PersistLayer> table; // what the table region holds after this forward
+
+    int flush() {
+        if (segment.empty() && pn.in_u8 == nullptr) return BNN_OK;
+        if (table_used + segment.size() > (size_t)PERSIST_MAX_LAYERS) return BNN_ERR_UNSUPPORTED;
+        PersistLayer* dev = reinterpret_cast<PersistLayer*>(ws + pl->table_off) + table_used;
+        // upload the run's layer table unless the same bytes are already there (repeated forwards of one net)
+        const bool same = net->persist_uploaded_at == ws + pl->table_off &&
+                          net->persist_uploaded.size() >= table_used + segment.size() &&
+                          (segment.empty() || memcmp(net->persist_uploaded.data() + table_used, segment.data(),
+                                                     segment.size() * sizeof(PersistLayer)) == 0);
+        if (!same && !segment.empty()) {
+            if (hipMemcpyAsync(dev, segment.data(), segment.size() * sizeof(PersistLayer), hipMemcpyHostToDevice, stream) !=
+                hipSuccess)
+                return BNN_ERR_DEVICE;
+            if (hipStreamSynchronize(stream) != hipSuccess) return BNN_ERR_DEVICE;   // the host copy may go away
+        }
+        int max_tiles = 1;
+        for (const PersistLayer& P : segment) max_tiles = std::max(max_tiles, P.gx * P.gy);
+        pn.nlayers = (int)segment.size();
+        pn.layers = dev;
+        const int rc = launch_persist_chain(pn, max_tiles, max_grid, reinterpret_cast<unsigned*>(ws + pl->sync_off), sync,
+                                            spin_limit, stream);
+        table.insert(table.end(), segment.begin(), segment.end());
+        table_used += segment.size();
+        segment.clear();
+        pn = PersistNet{};
+        return rc;
+    }
+};
+
+int forward_impl(bnn_net* net, const void* input, void* output, int batch, char* ws, const Plan& pl, int path, void* stream,
+                 PersistCtx* pc) {
     const uint32_t* cur = nullptr;      // bits of the current activation
     int curH = 1, curW = 1, curC = 0, cur_ld = 0;
     int32_t* R = nullptr;               // running int32 residual (same shape as cur), or null
@@ -588,8 +651,23 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
         const bnn_net::Layer& L = net->layers[i];
         uint32_t* obits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
         int rc = BNN_OK;
+        // persistent forward: contractions are collected (dispatch() records them while capture_sink is set) and run
+        // as one kernel per unbroken run of FC / CONV / BLOCK layers; every other layer first lets that kernel go
+        const bool contraction = L.kind == bnn_net::FC || L.kind == bnn_net::CONV || L.kind == bnn_net::BLOCK;
+        if (pc != nullptr) {
+            if (!contraction && !(i == 0 && L.kind == bnn_net::IN_U8)) {
+                rc = pc->flush();
+                if (rc != BNN_OK) return rc;
+            }
+            capture_sink = contraction ? &pc->segment : nullptr;
+        }
         switch (L.kind) {
             case bnn_net::IN_U8:
+                if (pc != nullptr) {                 // done inside the persistent kernel, ahead of its first layer
+                    pc->pn.in_u8 = static_cast<const uint8_t*>(input); pc->pn.in_bits = obits;
+                    pc->pn.in_rows = batch; pc->pn.in_cols = L.a; pc->pn.in_thr = L.thr_u8; pc->pn.in_ldw = L.words_per_row;
+                    break;
+                }
                 rc = bnn_pack_u8(static_cast<const uint8_t*>(input), L.thr_u8, obits, batch, L.a, L.words_per_row, stream);
                 break;
             case bnn_net::IN_BITS:
@@ -654,7 +732,7 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                 rc = bnn_bconv_thr_ex(cur, static_cast<const uint32_t*>(L.w0), nullptr, nullptr,
                                       static_cast<const int32_t*>(L.t0), hbits, batch, curH, curW, curC, L.b, 3,
                                       L.stride, 1, L.pad_mode, path, stream);
-                if (rc != BNN_OK) return rc;
+                if (rc != BNN_OK) { capture_sink = nullptr; return rc; }
                 rc = bconv_common(hbits, static_cast<const uint32_t*>(L.w1), keep_sum ? Rnew : nullptr, shortcut,
                                   static_cast<const int32_t*>(L.t1), ybits, batch, L.H, L.W, L.b, L.b, 3, 1, 1,
                                   L.pad_mode, path, stream, shortcut_bits, x2, static_cast<const uint32_t*>(L.w2), curH, curW,
@@ -670,22 +748,40 @@ int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, vo
                                   curH * curW, curC, L.a, stream);
                 break;
         }
+        capture_sink = nullptr;
         if (rc != BNN_OK) return rc;
         cur = obits; curH = L.H; curW = L.W; curC = L.C; cur_ld = L.words_per_row;
     }
+    if (pc != nullptr) return pc->flush();
     return BNN_OK;
+}
+
+}  // namespace
+
+int bnn_net_forward(bnn_net* net, const void* input, void* output, int batch, void* workspace, size_t workspace_bytes,
+                    int path, void* stream) {
+    if (!net || !input || batch < 1 || net->layers.empty()) return BNN_ERR_INVALID_ARG;
+    Plan pl = plan(net, batch);
+    if (pl.rc != BNN_OK) return pl.rc;
+    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BNN_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BNN_ERR_ALIGNMENT;
+    char* ws = static_cast<char*>(workspace);
+    net->last_ws = ws; net->last_batch = batch;
+    return forward_impl(net, input, output, batch, ws, pl, path, stream, nullptr);
 }
 
 int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, int batch, void* workspace,
                                size_t workspace_bytes, int flags, void* stream) {
     if (!net || !input || !output || batch < 1 || net->layers.size() < 2) return BNN_ERR_INVALID_ARG;
-    if (flags & ~(BNN_PERSIST_NO_SYNC | BNN_PERSIST_GIVE_UP_AT_ONCE)) return BNN_ERR_INVALID_ARG;
+    const int grid_cap = (flags >> 8) & 0xFFFF;
+    if (flags & ~(BNN_PERSIST_NO_SYNC | BNN_PERSIST_GIVE_UP_AT_ONCE | (0xFFFF << 8))) return BNN_ERR_INVALID_ARG;
+    bool any_contraction = false, any_conv = false;
     for (size_t i = 0; i < net->layers.size(); ++i) {
         const bnn_net::Kind kd = net->layers[i].kind;
-        const bool ok = (i == 0) ? (kd == bnn_net::IN_U8 || kd == bnn_net::IN_BITS) : (kd == bnn_net::FC);
-        if (!ok) return BNN_ERR_UNSUPPORTED;           // fully-connected chains only
+        if (kd == bnn_net::FC || kd == bnn_net::CONV || kd == bnn_net::BLOCK) any_contraction = true;
+        if (kd == bnn_net::CONV || kd == bnn_net::BLOCK) any_conv = true;
     }
-    if (net->layers.size() - 1 > (size_t)PERSIST_MAX_LAYERS) return BNN_ERR_UNSUPPORTED;
+    if (!any_contraction) return BNN_ERR_UNSUPPORTED;
     Plan pl = plan(net, batch);
     if (pl.rc != BNN_OK) return pl.rc;
     if (!workspace || workspace_bytes < pl.total) return BNN_ERR_WORKSPACE;
@@ -693,44 +789,27 @@ int bnn_net_forward_persistent(bnn_net* net, const void* input, void* output, in
     char* ws = static_cast<char*>(workspace);
     net->last_ws = ws; net->last_batch = batch;
 
-    PersistNet pn = {};
-    const bnn_net::Layer& L0 = net->layers[0];
-    const uint32_t* cur;
-    if (L0.kind == bnn_net::IN_U8) {
-        pn.in_u8 = static_cast<const uint8_t*>(input);
-        pn.in_bits = reinterpret_cast<uint32_t*>(ws + L0.bits_off);
-        pn.in_rows = batch; pn.in_cols = L0.a; pn.in_thr = L0.thr_u8; pn.in_ldw = L0.words_per_row;
-        cur = pn.in_bits;
-    } else {
-        if (!aligned16(input)) return BNN_ERR_ALIGNMENT;
-        cur = static_cast<const uint32_t*>(input);
-    }
-    int cur_ld = L0.words_per_row;
-    for (size_t i = 1; i < net->layers.size(); ++i) {
-        const bnn_net::Layer& L = net->layers[i];
-        PersistLayer& P = pn.layer[pn.nlayers++];
-        const int K = L.a, Nn = L.b;
-        if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
-        P.A = cur; P.B = static_cast<const uint32_t*>(L.w0);
-        P.g = bmm_geom(batch, Nn, K, cur_ld, round4(words(K)));
-        P.e = Epi{};
-        int col_span = Nn;
-        if (L.t0) {
-            P.e.thr = static_cast<const int32_t*>(L.t0);
-            P.e.bits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
-            P.e.ldbits_w = L.words_per_row;
-            col_span = max(Nn, L.words_per_row * 32);   // pad words of the output rows are written (as zeros) too
-            cur = P.e.bits; cur_ld = L.words_per_row;
-        } else {
-            P.e.out = static_cast<int32_t*>(output); P.e.ldc = Nn;
-        }
-        P.gx = (int)cdiv(batch, 64); P.gy = (int)cdiv(col_span, 64);
-    }
-    net->last_persist_sync = reinterpret_cast<const unsigned*>(ws + pl.sync_off);
+    PersistCtx pc;
+    pc.net = net; pc.ws = ws; pc.pl = &pl;
+    pc.sync = (flags & BNN_PERSIST_NO_SYNC) ? 0 : 1;
     // a waiter polls about once a microsecond: 2^17 polls are a few tenths of a second
-    const int spin_limit = (flags & BNN_PERSIST_GIVE_UP_AT_ONCE) ? 0 : (1 << 17);
-    return launch_persist_fc(pn, reinterpret_cast<unsigned*>(ws + pl.sync_off), (flags & BNN_PERSIST_NO_SYNC) ? 0 : 1,
-                             spin_limit, static_cast<hipStream_t>(stream));
+    pc.spin_limit = (flags & BNN_PERSIST_GIVE_UP_AT_ONCE) ? 0 : (1 << 17);
+    // a device-wide barrier costs more the more workgroups meet at it (measured: about 2 us with 16, 18 us with
+    // 256); a convolution chain has many layers with few tiles each, so its grid is kept small unless the caller
+    // asks otherwise
+    pc.max_grid = grid_cap > 0 ? grid_cap : (any_conv ? 128 : (1 << 20));
+    pc.stream = static_cast<hipStream_t>(stream);
+    net->last_persist_sync = reinterpret_cast<const unsigned*>(ws + pl.sync_off);
+    const int rc = forward_impl(net, input, output, batch, ws, pl, BNN_PATH_MFMA, stream, &pc);
+    capture_sink = nullptr;
+    if (rc == BNN_OK) {
+        net->persist_uploaded = pc.table;
+        net->persist_uploaded_at = ws + pl.table_off;
+    } else {
+        net->persist_uploaded.clear();
+        net->persist_uploaded_at = nullptr;
+    }
+    return rc;
 }
 
 int bnn_net_persistent_status(bnn_net* net, int* aborted, void* stream) {

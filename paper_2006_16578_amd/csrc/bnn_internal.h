@@ -97,24 +97,32 @@ __host__ __device__ inline long long sums16_index(long long row, int col, int ld
     return ((row >> 5) * (long long)(ldc >> 5) + (col >> 5)) * 1024 + lane * 16 + r;
 }
 
-// A chain of binarized FC layers for the whole-network persistent kernel (passed by value as a kernel argument).
-constexpr int PERSIST_MAX_LAYERS = 8;
+// A chain of binarized layers for the whole-network persistent kernel.  The layer table lives in device memory
+// (a ResNet-18-shaped chain has 16 layers of 256 bytes: more than a kernel argument block holds).
+constexpr int PERSIST_MAX_LAYERS = 48;
 struct PersistLayer {
     const uint32_t* A;
     const uint32_t* B;
     Geom g;
     Epi e;
     int gx, gy;            // 64 x 64 output tiles
+    int variant;           // 0: matrix product; 1 + persist_conv_variant(): 3x3 convolution, see bnn_persistent.hip
 };
 struct PersistNet {
     int nlayers;
+    const PersistLayer* layers;    // device memory, nlayers entries
     const uint8_t* in_u8;  // optional input layer: [in_rows][in_cols] 8-bit values -> in_bits [in_rows][in_ldw], bit = (x >= in_thr)
     uint32_t* in_bits;
     long long in_rows;
     int in_cols, in_thr, in_ldw;
-    PersistLayer layer[PERSIST_MAX_LAYERS];
 };
-int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, int spin_limit, hipStream_t s);
+// Index of the kernel's convolution form for this geometry, or -1 if the persistent kernel has none (it carries the
+// fully unrolled 3x3 forms for 64, 128, 256 and 512 channels only).
+int persist_conv_variant(const Geom& g);
+// max_tiles: the largest tile count of the chain's layers (sizes the grid); max_grid: upper bound for the grid (the cost
+// of a device-wide barrier grows with the number of workgroups).
+int launch_persist_chain(const PersistNet& net, int max_tiles, int max_grid, unsigned* ctr, int sync, int spin_limit,
+                         hipStream_t s);
 
 int launch_valu(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 int launch_mfma(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);

@@ -1,5 +1,6 @@
-// Whole-network persistent kernel for chains of binarized fully-connected layers (paper Sec. 6.2: every
-// layer is a device function inside one kernel, a device-wide barrier separates consecutive layers).
+// Whole-network persistent kernel for chains of binarized layers -- fully-connected layers, 3x3 convolutions and the
+// two convolutions of residual blocks (paper Sec. 6.2: every layer is a device function inside one kernel, a
+// device-wide barrier separates consecutive layers).
 //
 // One launch; the grid is at most what the chip holds at once (occupancy x compute units), so on an otherwise
 // idle device every workgroup is resident for the whole kernel, and if other work holds compute units the
@@ -43,7 +44,13 @@ __device__ __forceinline__ bool grid_barrier(unsigned* ctr, unsigned* abort_flag
     return ok_sh != 0;
 }
 
-__global__ __launch_bounds__(256, PTile::MINB) void persist_fc_kernel(PersistNet net, unsigned* ctr, int spin_limit, int sync) {
+template <int V, bool EXCL, int CPT3>
+__device__ __forceinline__ void conv_tile(const PersistLayer& L, int bx, int by) {
+    mfma::mfma_tile<PTile, V, true, EXCL, false, CPT3>(L.A, L.B, L.g, L.e, bx, by);
+}
+
+__global__ __launch_bounds__(256, PTile::MINB) void persist_chain_kernel(PersistNet net, const PersistLayer* __restrict__ layers,
+                                                                         unsigned* ctr, int spin_limit, int sync) {
     const unsigned nwg = gridDim.x;
     unsigned phase = 0;
     if (net.in_u8 != nullptr) {                        // input layer: 8-bit pixels -> bits, one wave per row
@@ -64,11 +71,21 @@ __global__ __launch_bounds__(256, PTile::MINB) void persist_fc_kernel(PersistNet
         if (sync && !grid_barrier(ctr, ctr + 1, phase * nwg, spin_limit)) return;
     }
     for (int l = 0; l < net.nlayers; ++l) {
-        const PersistLayer& L = net.layer[l];
+        const PersistLayer& L = layers[l];
         const int total = L.gx * L.gy;
         for (int t = (int)blockIdx.x; t < total; t += (int)nwg) {
             const int by = t / L.gx, bx = t - by * L.gx;
-            mfma::mfma_tile<PTile, 4, false, false, true>(L.A, L.B, L.g, L.e, bx, by);
+            switch (L.variant) {                       // uniform
+                case 0: mfma::mfma_tile<PTile, 4, false, false, true>(L.A, L.B, L.g, L.e, bx, by); break;
+                case 1: conv_tile<1, false, 1>(L, bx, by); break;     // 64 channels
+                case 2: conv_tile<1, true, 1>(L, bx, by); break;
+                case 3: conv_tile<2, false, 1>(L, bx, by); break;     // 128
+                case 4: conv_tile<2, true, 1>(L, bx, by); break;
+                case 5: conv_tile<4, false, 1>(L, bx, by); break;     // 256
+                case 6: conv_tile<4, true, 1>(L, bx, by); break;
+                case 7: conv_tile<4, false, 2>(L, bx, by); break;     // 512
+                default: conv_tile<4, true, 2>(L, bx, by); break;
+            }
         }
         if (l + 1 < net.nlayers) {
             ++phase;
@@ -83,28 +100,41 @@ __global__ void persist_clear_kernel(unsigned* ctr) {
 
 }  // namespace
 
+int persist_conv_variant(const Geom& g) {
+    if (!g.conv || g.k != 3 || g.taps != 9 || g.bits_tap != g.tw * 32 || g.lda_w != g.tw || !mfma::offsets_fit(g)) return -1;
+    int form;
+    switch (g.tw) {
+        case 2: form = 0; break;
+        case 4: form = 1; break;
+        case 8: form = 2; break;
+        case 16: form = 3; break;
+        default: return -1;
+    }
+    return 2 * form + (g.excl ? 1 : 0);
+}
+
 // ctr: two words of device memory (barrier counter, abort flag).  sync == 0 skips the barriers: the results
 // are then undefined; it exists to time the cost of the barriers alone.  spin_limit: polls (each an s_sleep and
 // one device-scope load, about a microsecond) before a waiter gives up.
-int launch_persist_fc(const PersistNet& net, unsigned* ctr, int sync, int spin_limit, hipStream_t s) {
+int launch_persist_chain(const PersistNet& net, int max_tiles, int max_grid, unsigned* ctr, int sync, int spin_limit,
+                         hipStream_t s) {
     // workgroups the current device holds at once (queried per call: the property belongs to the device)
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return BNN_ERR_DEVICE;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return BNN_ERR_DEVICE;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&persist_fc_kernel), 256, 0) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&persist_chain_kernel), 256, 0) !=
         hipSuccess)
         return BNN_ERR_DEVICE;
     if (cus < 1 || per_cu < 1) return BNN_ERR_DEVICE;
     const int max_wg = cus * per_cu;
-    int want = 1;
-    for (int l = 0; l < net.nlayers; ++l) want = max(want, net.layer[l].gx * net.layer[l].gy);
+    int want = max(1, max_tiles);
     if (net.in_u8 != nullptr) {
         const long long row_groups = cdiv(net.in_rows, 4);
         want = max(want, row_groups < (1 << 20) ? (int)row_groups : (1 << 20));
     }
-    const int grid = min(want, max_wg);
+    const int grid = min(min(want, max_wg), max(1, max_grid));
     hipLaunchKernelGGL(persist_clear_kernel, dim3(1), dim3(64), 0, s, ctr);
-    hipLaunchKernelGGL(persist_fc_kernel, dim3((unsigned)grid), dim3(256), 0, s, net, ctr, spin_limit, sync);
+    hipLaunchKernelGGL(persist_chain_kernel, dim3((unsigned)grid), dim3(256), 0, s, net, net.layers, ctr, spin_limit, sync);
     return check_launch();
 }
 

@@ -323,6 +323,43 @@ def test_mlp_persistent(bnn, orc, batch):
     assert np.array_equal(host(net.forward(x)), ref)       # and the per-layer path still agrees
 
 
+@pytest.mark.parametrize("blocks,hw,batch,pad_mode", [
+    (((64, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2)), 32, 3, 0),
+    (((64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 256, 2), (256, 512, 2), (512, 512, 1)), 64, 2, 1),
+    (((128, 128, 1), (128, 128, 1)), 40, 9, 0)])
+def test_resnet_persistent(bnn, orc, blocks, hw, batch, pad_mode):
+    # residual chains as one persistent kernel (stem and head stay ordinary launches): every block's bits and the
+    # logits must equal the per-layer forward's exactly -- the same integer arithmetic, another launch structure --
+    # and the per-layer forward is checked against the oracle; repeated calls re-use the uploaded layer table
+    p = wl.resnet18_params(blocks=blocks, classes=11, config=98)
+    x = wl.resnet18_input(batch, hw=hw, config=98)
+    check_resnet(bnn, orc, p, x, hw, 0, tier=1, pad_mode=pad_mode)
+    xd = to_dev(x)
+    net = build_resnet(bnn, p, hw, pad_mode)
+    ref = host(net.forward(xd))
+    ref_bits = [words(net.layer_bits(b)) for b in range(len(blocks) + 1)]
+    for rep, cap in enumerate((0, 0, 16, 1000)):
+        got = host(net.forward_persistent(xd, grid_cap=cap))
+        assert not net.persistent_status(), "a barrier gave up in call %d" % rep
+        assert np.array_equal(got, ref), "logits, call %d" % rep
+        for b in range(len(blocks) + 1):
+            assert np.array_equal(words(net.layer_bits(b)), ref_bits[b]), "layer %d, call %d" % (b, rep)
+    # another batch through the same net: the table is rebuilt
+    x2 = to_dev(wl.resnet18_input(batch + 1, hw=hw, config=99))
+    assert np.array_equal(host(net.forward_persistent(x2)), host(net.forward(x2)))
+
+
+def test_persistent_refuses_what_it_cannot_run(bnn):
+    # 96 input channels have no unrolled 3x3 form in the persistent kernel
+    p = wl.resnet18_params(blocks=((64, 96, 2), (96, 96, 1)), classes=5, config=98)
+    net = build_resnet(bnn, p, 32)
+    x = to_dev(wl.resnet18_input(2, hw=32, config=98))
+    with pytest.raises(bnn.BnnError) as ei:
+        net.forward_persistent(x)
+    assert ei.value.status == -3
+    assert host(net.forward(x)).shape == (2, 5)            # the per-layer path takes it
+
+
 def test_persistent_timeout_is_reported(bnn, orc):
     # the time-out path, forced from the host: with a poll limit of zero the first workgroup that finds a barrier
     # incomplete raises the abort flag, every workgroup leaves the kernel normally, and the status call says so;
@@ -367,11 +404,16 @@ def test_persistent_bits_input_and_limits(bnn, orc):
         h = orc.threshold_pack(orc.bmm(h, W[i], dims[i]), thr[i], ldb_w=wl.round_up(wl.nwords(dims[i + 1]), 4))
     ref = orc.bmm(h, W[2], dims[2])
     assert np.array_equal(host(net.forward_persistent(to_dev(x))), ref)
-    # a convolutional network is refused, not mis-run
-    spec = wl.cnn_layers("cifar_vgg")
-    cnn = bnn.Net.from_layers(spec["layers"], spec["in_hw"])
-    with pytest.raises(bnn.BnnError):
-        cnn.forward_persistent(to_dev(wl.cnn_input("cifar_vgg", 2)))
+    # a convolutional network with pooling layers: every run of layers between the pools is one persistent launch,
+    # the result is that of the per-layer forward (Cifar-VGG and Cifar-ResNet-14: convolutions, blocks, then FC layers)
+    for name in ("cifar_vgg", "cifar_resnet14"):
+        spec = wl.cnn_layers(name)
+        cnn = bnn.Net.from_layers(spec["layers"], spec["in_hw"])
+        xi = to_dev(wl.cnn_input(name, 3))
+        want = host(cnn.forward(xi))
+        for rep in range(2):
+            assert np.array_equal(host(cnn.forward_persistent(xi)), want), (name, rep)
+            assert not cnn.persistent_status()
 
 
 @pytest.mark.parametrize("shape", [(2, 21, 19, 3, 5, 7, 4, 3), (1, 9, 9, 1, 1, 3, 1, 1), (3, 16, 12, 4, 70, 5, 2, 2),
