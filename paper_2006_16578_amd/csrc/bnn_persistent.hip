@@ -49,7 +49,7 @@ __device__ __forceinline__ void conv_tile(const PersistLayer& L, int bx, int by)
     mfma::mfma_tile<PTile, V, true, EXCL, false, CPT3>(L.A, L.B, L.g, L.e, bx, by);
 }
 
-__global__ __launch_bounds__(256, PTile::MINB) void persist_chain_kernel(PersistNet net, const PersistLayer* __restrict__ layers,
+__global__ __launch_bounds__(256, 3) void persist_chain_kernel(PersistNet net, const PersistLayer* __restrict__ layers,
                                                                          unsigned* ctr, int spin_limit, int sync) {
     const unsigned nwg = gridDim.x;
     unsigned phase = 0;
