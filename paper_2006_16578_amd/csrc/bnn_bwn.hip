@@ -760,12 +760,11 @@ struct WaveArgs {
     int N, H, W, O, pad, P, Q;
     int tiles_p, tiles_q;
     int ntiles;              // N * tiles_p * tiles_q
-    int ws_plane_units;      // 16-byte units per weight plane and channel tile in the workspace (2 * nsteps * 64)
     FastDiv div_tiles, div_tq;
 };
 
 template <class G, int TERMS, bool WANT_Y>
-__global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const float* __restrict__ x, const uint4* __restrict__ wexp,
+__global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                                         const float* __restrict__ thr, float* __restrict__ y,
                                                                         uint32_t* __restrict__ bits, WaveArgs g) {
     constexpr int NT = 2, COLS = 64;
@@ -776,15 +775,6 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: everything derived from the rectangle index stays scalar
     char* patch = reinterpret_cast<char*>(smem) + 3 * G::WUNITS * 16 + wave * (3 * G::PLANE);     // this wave's three planes
     const int n0 = (int)blockIdx.y * COLS;
-
-    {   // weights of this channel tile -> LDS (the first NRUNS run slots of each plane hold data)
-        const uint4* src = wexp + (long long)blockIdx.y * 3 * g.ws_plane_units;
-        for (int u = tid; u < 3 * G::WUNITS; u += G::WAVES * 64) {
-            const int pl = u / G::WUNITS, v = u - pl * G::WUNITS;
-            wlds[u] = src[pl * g.ws_plane_units + v];
-        }
-    }
-    __syncthreads();                                                   // the only barrier
 
     float th[NT];
     bool cok[NT];
@@ -859,12 +849,61 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
         }
     };
 
+    // Rectangle of this wave in round r: whole rounds give a workgroup eight consecutive rectangles; the last, partial
+    // round is dealt across the workgroups (wave 0 of each first), so that no compute unit runs a full extra round.
     const int step = (int)gridDim.x * G::WAVES;
-    int t = (int)blockIdx.x * G::WAVES + wave;
-    if (t < g.ntiles) { request(t); stage(t); }
-    for (; t < g.ntiles; t += step) {
-        const bool more = t + step < g.ntiles;
-        if (more) request(t + step);
+    const int whole = g.ntiles / step;
+    auto tile_of = [&](int r) {
+        if (r < whole) return r * step + (int)blockIdx.x * G::WAVES + wave;
+        return r == whole ? whole * step + wave * (int)gridDim.x + (int)blockIdx.x : g.ntiles;   // past the last round: no rectangle
+    };
+    int t = tile_of(0);
+    if (t < g.ntiles) request(t);              // the first patch is on its way while the weights are staged
+    {   // weights of this channel tile -> LDS, split on the way (w [O][k][k][C]; a run is 8 consecutive values of one filter
+        // row, zero past the row's end; column = output channel): unit (plane, run, column) of wlds.  Every load is issued
+        // before the first split; pairs past the end repeat the last one and store nothing.
+        constexpr int PER = (G::WUNITS + G::WAVES * 64 - 1) / (G::WAVES * 64);
+        float xs[PER][8];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int p = min(tid + i * G::WAVES * 64, G::WUNITS - 1);
+            const int rho = p >> 6, o = min(n0 + (p & 63), g.O - 1);
+            const int r = rho / G::RPR, j = rho - r * G::RPR;
+            const float* wrow = w + ((long long)o * G::KS + r) * G::SEG;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xs[i][e] = wrow[min(8 * j + e, G::SEG - 1)];
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int p = tid + i * G::WAVES * 64;
+            const int rho = min(p, G::WUNITS - 1) >> 6;
+            const int j = rho % G::RPR;
+            const bool col_ok = n0 + (p & 63) < g.O;
+            uint32_t hi[4] = {0u, 0u, 0u, 0u}, mid[4] = {0u, 0u, 0u, 0u}, lo[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x0 = (col_ok && 8 * j + e < G::SEG) ? xs[i][e] : 0.f;
+                const uint32_t a = __float_as_uint(x0);
+                const float r1 = x0 - __uint_as_float(a & 0xffff0000u);
+                const uint32_t b = __float_as_uint(r1);
+                const float r2 = r1 - __uint_as_float(b & 0xffff0000u);
+                hi[e >> 1] |= (a >> 16) << (16 * (e & 1));
+                mid[e >> 1] |= (b >> 16) << (16 * (e & 1));
+                lo[e >> 1] |= (__float_as_uint(r2) >> 16) << (16 * (e & 1));
+            }
+            if (p < G::WUNITS) {
+                wlds[p] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                wlds[G::WUNITS + p] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+                wlds[2 * G::WUNITS + p] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            }
+        }
+    }
+    if (t < g.ntiles) stage(t);
+    __syncthreads();                                                   // the only barrier: the weights are in place
+    for (int r = 0; t < g.ntiles; ++r) {
+        const int t_next = tile_of(r + 1);
+        const bool more = t_next < g.ntiles;
+        if (more) request(t_next);
 
         // ---- K loop, unrolled in full: run index of this lane = 2 * step + half; every offset is a compile-time constant
         v16f_bwn acc[NT];
@@ -914,10 +953,20 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
                 }
         };
         fetch(std::integral_constant<int, 0>{});
+        __builtin_amdgcn_sched_barrier(0);
         static_for<G::NSTEPS>([&](auto st_tag) {
             constexpr int st = decltype(st_tag)::value;
             if constexpr (st + 1 < G::NSTEPS) fetch(std::integral_constant<int, st + 1>{});
             multiply(st_tag);
+            // Left alone, the compiler sinks every LDS read to just before the MFMA that uses it (fewer live registers) and
+            // the wave then waits out the LDS latency a dozen times per step: keep the reads of the next step between this
+            // step's MFMAs, one each, and let nothing cross a step boundary.
+#pragma unroll
+            for (int q = 0; q < (TERMS == 9 ? 9 : 6) * NT; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         });
 
         // ---- epilogue: threshold -> packed bits (and / or the fp32 sums)
@@ -954,7 +1003,8 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
                 if (wi < ow) bits[pix * ow + wi] = wout[j];
             }
         }
-        if (more) stage(t + step);             // every read of this rectangle's patch has been consumed by its MFMAs
+        if (more) stage(t_next);               // every read of this rectangle's patch has been consumed by its MFMAs
+        t = t_next;
     }
 }
 
@@ -966,23 +1016,21 @@ int launch_conv_f32_wave_v(const float* x, const float* w, const float* thr, flo
     g.N = N; g.H = H; g.W = W; g.O = O; g.pad = pad; g.P = P; g.Q = Q;
     g.tiles_p = (int)cdiv(P, G::FP); g.tiles_q = (int)cdiv(Q, G::FQ);
     g.ntiles = N * g.tiles_p * g.tiles_q;
-    g.ws_plane_units = 2 * G::NSTEPS * 64;
     g.div_tiles = make_fastdiv((uint32_t)(g.tiles_p * g.tiles_q));
     g.div_tq = make_fastdiv((uint32_t)g.tiles_q);
-    const size_t per_tile_units = (size_t)3 * g.ws_plane_units;
-    if (workspace_bytes < per_tile_units * 16 * col_tiles) return BNN_ERR_WORKSPACE;
+    // This kernel splits the weights itself while it stages them; the workspace the entry point asks for (the other
+    // first-layer kernels keep their expanded weights there) is checked all the same, so that the call's contract does
+    // not depend on which kernel serves a shape.
+    if (workspace == nullptr || workspace_bytes < (size_t)3 * 2 * G::NSTEPS * 64 * 16 * col_tiles) return BNN_ERR_WORKSPACE;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_f32_wave_kernel<G, TERMS, WANT_Y>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
     if (attr != hipSuccess) return BNN_ERR_DEVICE;
-    uint4* wexp = static_cast<uint4*>(workspace);
-    const int nunits = (int)(per_tile_units * col_tiles);
-    hipLaunchKernelGGL(conv_f32_expand_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, w, wexp, G::CIN, O, G::KS, 64, G::NSTEPS, nunits, 0);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return BNN_ERR_DEVICE;
     const long long wgs = min(cdiv(g.ntiles, G::WAVES), (long long)max(1, cus / col_tiles));
     hipLaunchKernelGGL((conv_f32_wave_kernel<G, TERMS, WANT_Y>), dim3((unsigned)wgs, (unsigned)col_tiles), dim3(G::WAVES * 64), G::LDS, s, x,
-                       wexp, thr, y, bits, g);
+                       w, thr, y, bits, g);
     return check_launch();
 }
 
