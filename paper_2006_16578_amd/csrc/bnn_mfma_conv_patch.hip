@@ -1,6 +1,6 @@
-// Matrix-core path for 3x3 "same" convolutions (stride 1, pad 1) with few channels on both sides: the filters stay
-// in LDS as finished E2M1 operands for the whole launch, and every wave keeps the input patch of its 64 output
-// pixels there, expanded once for all nine taps.
+// Matrix-core path for 3x3 convolutions with pad 1 (stride 1; stride 2 for 64 -> 128 channels) with few channels on
+// both sides: the filters stay in LDS as finished E2M1 operands for the whole launch, and every wave keeps the input
+// patch of its 64 output pixels there, expanded once for all nine taps.
 //
 // Why.  The short-K layers of a network (Sec. 6: C = O = 64 or 128) give each accumulator 9 or 18 MFMAs.  In the
 // direct kernel a wave expands its own fragments for every tap (7 vector instructions per packed word, each
@@ -31,7 +31,8 @@ using mfma::v16f;
 using mfma::v8i;
 
 constexpr int MT = 2;            // a wave tile is 64 output pixels x all output channels
-constexpr int PRE = 4;           // patch positions per lane whose words are requested one tile ahead
+// patch positions per lane whose words are requested one tile ahead (a stride-2 tile spans twice the cells)
+constexpr int pre_positions(int stride) { return stride == 2 ? 8 : 4; }
 
 struct PatchArgs {
     int wp1, hp1;                // W + 1, H + 1
@@ -154,13 +155,16 @@ __device__ __forceinline__ void epilogue_chain_swapped(v16f (&acc)[MT][2], const
 
 // NT: 32-column accumulator tiles per wave (all output channels); CW: packed words per pixel (C / 32); KIND: the
 // epilogue the call needs (mfma::epilogue_kind), compiled in alone to keep the register count of the tile loop low.
-template <int NT, int CW, int WAVES, int KIND>
+// S: stride (1 or 2).  With stride 2 the output pixel (p, q) is centred on the input pixel (2p, 2q): the same padded
+// coordinates, a lane's base twice as far from the tile's first pixel, the same nine offsets.
+template <int NT, int CW, int WAVES, int KIND, int S = 1>
 __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_t* __restrict__ A,
                                                                    const uint32_t* __restrict__ B, Geom g, Epi e,
                                                                    PatchArgs pa) {
     extern __shared__ uint4 lds[];
     constexpr int COLSP = NT * 32;
     constexpr int CG = CW / 2;                       // 64-channel slabs
+    constexpr int PRE = pre_positions(S);
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -188,11 +192,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
     };
     auto small_div = [](int x, int magic) { return (int)(__umul24((uint32_t)x, (uint32_t)magic) >> 20); };
     // byte offset of the input pixel at the patch's cell j (0 and in = false for a padding cell).  The patch starts
-    // one padded row and one cell before the first pixel's cell: at padded row f.p of image f.n, column f.q.
+    // one padded row and one cell before the first pixel's centre: at padded row S f.p of image f.n, column S f.q.
     auto locate = [&](const First& f, int j, bool& in) {
-        const int x = f.q + j;
+        const int x = S * f.q + j;
         const int drow = small_div(x, pa.magic_wp1), xp = x - __mul24(drow, pa.wp1);
-        const int yl = f.p + drow;
+        const int yl = S * f.p + drow;
         const int dimg = small_div(yl, pa.magic_hp1), yp = yl - __mul24(dimg, pa.hp1);
         const int n = f.n + dimg;
         in = xp > 0 && yp > 0 && n < pa.images;
@@ -313,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
             const int lp = f.p + dp;
             const int dn = small_div(lp, pa.magic_p), p = lp - __mul24(dn, g.P);
             // cells between this pixel and the tile's first: whole padded rows, then columns
-            abase[i] = half * pa.plane + __mul24(__mul24(dn, pa.hp1) + p - f.p, pa.wp1) + q - f.q;
+            abase[i] = half * pa.plane + __mul24(__mul24(dn, pa.hp1) + S * (p - f.p), pa.wp1) + S * (q - f.q);
         }
 
         v16f acc[NT / 2][MT][2];                     // [64-column half][row tile][column tile]: the epilogue runs per half
@@ -410,6 +414,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
 
 // Waves per workgroup: what the registers allow (three per SIMD with 64-column tiles, two with 128-column tiles).
 constexpr int waves_for(int nt, int kind) { (void)kind; return nt == 2 ? 12 : 8; }
+// stride 2, 64 -> 128 channels: a patch is twice as long, seven of them fit beside the filters
+constexpr int WAVES_STRIDE2 = 7;
 
 struct PatchPlan {
     bool ok;
@@ -420,20 +426,27 @@ struct PatchPlan {
 
 PatchPlan plan_patch(const Geom& g, const Epi& e) {
     PatchPlan pl = {};
-    if (!g.conv || g.b_tiled || g.k != 3 || g.stride != 1 || g.pad != 1 || g.taps != 9) return pl;
+    if (!g.conv || g.b_tiled || g.k != 3 || (g.stride != 1 && g.stride != 2) || g.pad != 1 || g.taps != 9) return pl;
     if ((g.tw != 2 && g.tw != 4) || g.bits_tap != g.tw * 32 || g.lda_w != g.tw) return pl;
-    if (g.cols > 128 || g.P != g.H || g.Q != g.W) return pl;
+    const int S = g.stride;
+    if (g.cols > 128 || g.P != (g.H - 1) / S + 1 || g.Q != (g.W - 1) / S + 1) return pl;
     pl.kind = mfma::epilogue_kind(e, true, false);
     if (pl.kind == mfma::EPI_GENERIC) return pl;                     // (row-major residuals: the direct kernels)
     if (pl.kind == mfma::EPI_BITS && g.A2 != nullptr) return pl;     // (the bits-only form has no second source)
     pl.nt = g.cols <= 64 ? 2 : 4;
     pl.cw = g.tw;
-    pl.waves = waves_for(pl.nt, pl.kind);
+    // stride 2: built for 64 -> 128 channels, bits out (the first convolution of a block that halves the image)
+    if (S == 2 && (pl.nt != 4 || pl.cw != 2 || pl.kind != mfma::EPI_BITS)) return pl;
+    pl.waves = S == 2 ? WAVES_STRIDE2 : waves_for(pl.nt, pl.kind);
     if (e.bits != nullptr && e.ldbits_w > pl.nt) return pl;          // words beyond the tile would stay unwritten
     const long long images = g.rows / ((long long)g.P * g.Q);
-    // cells a tile of 64 consecutive output pixels can span, with one padded row and one cell on either side
-    const int row_x = 63 / g.W + 1, img_x = 63 / (g.H * g.W) + 1;
-    const int cells = 63 + row_x + (g.W + 1) * img_x + 2 * (g.W + 1) + 3;
+    // Cells a tile of 64 consecutive output pixels can span.  From one output pixel to the next the centre moves S cells;
+    // a row change adds S (W + 1 - Q) cells to that, an image change the padded rows between the last window row of one
+    // image and the first of the next; then two padded rows and three cells for the last pixel's window.
+    const int row_x = 63 / g.Q + 1, img_x = 63 / (g.P * g.Q) + 1;
+    const int row_extra = S * (g.W + 1 - g.Q);
+    const int img_extra = max(0, (g.H + 1 - S * (g.P - 1)) * (g.W + 1) - S * g.Q - row_extra);
+    const int cells = 63 * S + row_x * row_extra + img_x * img_extra + 2 * (g.W + 1) + 3;
     const int pp = (cells + 63) / 64;
     if (pp > 16) return pl;
     if ((images * (g.H + 1) + 2) * (g.W + 1) + 64LL * pp >= (1LL << 31)) return pl;          // cell numbers fit an int
@@ -444,12 +457,12 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     // Measured against the direct kernels on 56x56x64->64 and 28x28 / 56x56x128->128 layers over batch sizes: the
     // 64-column form wins from about 400 tiles, the 128-column form (a wave's tile is 144 or more MFMAs long, and
     // one tile per wave is then mostly latency) from about 3000.
-    if (ntiles < (pl.nt == 2 ? 512 : 2560)) return pl;
+    if (ntiles < (S == 2 ? 1024 : pl.nt == 2 ? 512 : 2560)) return pl;
     pl.pa.wp1 = g.W + 1; pl.pa.hp1 = g.H + 1;
     // the small divisions of the kernel (x / d with one 24-bit multiply) are exact for x * d <= 2^20
     const long long lim = 1LL << 20;
-    if ((g.W + 64LL * pp) * (g.W + 1) > lim || (g.H + 64LL * pp / (g.W + 1) + 2) * (g.H + 1) > lim) return pl;
-    if ((g.W + 63LL) * g.W > lim || (g.H + 63LL / g.W + 2) * g.H > lim || images * g.H >= (1LL << 24)) return pl;
+    if ((S * g.Q + 64LL * pp) * (g.W + 1) > lim || (S * g.P + 64LL * pp / (g.W + 1) + 2) * (g.H + 1) > lim) return pl;
+    if ((g.Q + 63LL) * g.Q > lim || (g.P + 63LL / g.Q + 2) * g.P > lim || images * g.H >= (1LL << 24)) return pl;
     auto magic = [](int d) { return (int)(((1LL << 20) + d - 1) / d); };
     pl.pa.magic_wp1 = magic(g.W + 1); pl.pa.magic_hp1 = magic(g.H + 1);
     pl.pa.magic_q = magic(g.Q); pl.pa.magic_p = magic(g.P);
@@ -461,13 +474,13 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     return pl;
 }
 
-template <int NT, int CW, int WAVES, int KIND>
+template <int NT, int CW, int WAVES, int KIND, int S = 1>
 int launch_patch_kind(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, const PatchPlan& pl, hipStream_t s) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<NT, CW, WAVES, KIND>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<NT, CW, WAVES, KIND, S>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return BNN_ERR_DEVICE;
     const unsigned nwg = (unsigned)min(256, pl.pa.ntiles);   // one workgroup per compute unit; few tiles: spread over all of them
-    hipLaunchKernelGGL((conv_patch_kernel<NT, CW, WAVES, KIND>), dim3(nwg), dim3(64 * WAVES), pl.lds_bytes, s, A, B, g, e, pl.pa);
+    hipLaunchKernelGGL((conv_patch_kernel<NT, CW, WAVES, KIND, S>), dim3(nwg), dim3(64 * WAVES), pl.lds_bytes, s, A, B, g, e, pl.pa);
     return check_launch();
 }
 
@@ -488,12 +501,14 @@ int launch_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi&
 bool mfma_conv_patch_takes(const Geom& g, const Epi& e) { return plan_patch(g, e).ok; }
 
 const char* describe_mfma_conv_patch(const Geom& g) {
+    if (g.stride == 2) return "mfma_fp4_conv3x3s2_patch_wave64x128";
     return g.cols <= 64 ? "mfma_fp4_conv3x3_patch_wave64x64" : "mfma_fp4_conv3x3_patch_wave64x128";
 }
 
 int launch_mfma_conv_patch(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
     const PatchPlan pl = plan_patch(g, e);
     if (!pl.ok) return BNN_ERR_UNSUPPORTED;
+    if (g.stride == 2) return launch_patch_kind<4, 2, WAVES_STRIDE2, mfma::EPI_BITS, 2>(A, B, g, e, pl, s);
     if (pl.nt == 2) return pl.cw == 2 ? launch_patch<2, 2>(A, B, g, e, pl, s) : launch_patch<2, 4>(A, B, g, e, pl, s);
     return pl.cw == 2 ? launch_patch<4, 2>(A, B, g, e, pl, s) : launch_patch<4, 4>(A, B, g, e, pl, s);
 }

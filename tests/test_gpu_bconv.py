@@ -221,6 +221,25 @@ PATCH = [(64, 56, 56, 64, 64, "mfma_fp4_conv3x3_patch_wave64x64"), (4100, 7, 7, 
          (100000, 1, 2, 64, 40, "mfma_fp4_conv3x3_patch_wave64x64")]
 
 
+# the same kernel with stride 2 (64 -> at most 128 channels, bits out): even and odd image sizes, images smaller than a
+# tile, ragged columns, ragged last tile
+PATCH_STRIDE2 = [(90, 56, 56, 64, 128), (760, 19, 17, 64, 128), (16500, 3, 4, 64, 100), (4200, 7, 7, 64, 128),
+                 (63, 70, 60, 64, 96)]
+
+
+@pytest.mark.parametrize("shape", PATCH_STRIDE2)
+def test_patch_kernel_3x3_stride2(bnn, orc, shape):
+    N, H, W, C, O = shape
+    assert bnn.bconv_kernel_name(N, H, W, C, O, 3, 2, 1) == "mfma_fp4_conv3x3s2_patch_wave64x128"
+    case = wl.bconv_case(98, N, H, W, C, O, 3, 2, 1, index0=(H * W) % 83)
+    for pad_mode in (0, 1):
+        print("patch stride 2", shape, "pad_mode", pad_mode, flush=True)
+        ref1 = orc.bconv(case["x"], case["filt"], C, 2, 1, pad_mode, tier=1)
+        for n0 in (0, N - 1):
+            assert np.array_equal(orc.bconv_images(case["x"], case["filt"], C, 2, 1, pad_mode, n0, 1), ref1[n0:n0 + 1])
+        run_conv(bnn, orc, case, 0, pad_mode, ref=ref1)
+
+
 @pytest.mark.parametrize("shape", PATCH)
 def test_patch_kernel_3x3(bnn, orc, shape):
     N, H, W, C, O, kernel = shape
