@@ -60,9 +60,12 @@ def test_kernel_choice_is_host_logic():
     assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1) == "mfma_fp4_conv3x3_patch_wave64x128"
     assert b.bconv_kernel_name(128, 56, 56, 128, 128, 3, 1, 1, int32_out=True) == "mfma_fp4_conv3x3_patch_wave64x128"
     assert b.bconv_kernel_name(128, 56, 56, 64, 64, 3, 1, 1) == "mfma_fp4_conv3x3_patch_wave64x64"
-    # the same layers at a small batch, with stride 2 or with more channels: the direct kernel's tiles
+    # stride 2, 64 -> 128 channels, bits out: the same kernel with the lane bases twice as far apart
+    assert b.bconv_kernel_name(128, 56, 56, 64, 128, 3, 2, 1) == "mfma_fp4_conv3x3s2_patch_wave64x128"
+    # the same layers at a small batch, with int32 sums at stride 2, or with more channels: the direct kernel's tiles
     assert b.bconv_kernel_name(2, 56, 56, 128, 128, 3, 1, 1) == "mfma_fp4_conv_wg64x64"
-    assert b.bconv_kernel_name(128, 56, 56, 64, 128, 3, 2, 1) == "mfma_fp4_conv_wg256x128"
+    assert b.bconv_kernel_name(128, 56, 56, 64, 128, 3, 2, 1, int32_out=True) == "mfma_fp4_conv_wg256x128"
+    assert not b.bconv_kernel_name(16, 56, 56, 64, 128, 3, 2, 1).startswith("mfma_fp4_conv3x3")     # too few tiles for it
     assert b.bconv_kernel_name(128, 28, 28, 256, 256, 3, 1, 1) == "mfma_fp4_conv_wg256x128"
     # long K goes through LDS
     assert b.bconv_kernel_name(16, 64, 64, 2048, 2048, 3, 1, 1) == "mfma_fp4_conv_lds_wg256x128"
