@@ -405,7 +405,33 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
                     }
                 }
             } else if constexpr (KIND == mfma::EPI_CHAIN) {
-                epilogue_chain_swapped<MT>(acc[h], m0, 64 * h, lane, g, e, start, corr2);
+                if (e.resid16 == nullptr && e.resid_bits != nullptr) {
+                    // A first residual taken from packed bits (+1 / -1 per pixel and channel) goes through the matrix
+                    // pipe: one more K-step whose "filter" is the identity -- -1.0 where the K slot is the column's own
+                    // channel (a 1 bit expands to -1.0, so the product is +1), 0.0 elsewhere -- against the expanded word
+                    // of the pixel.  Two MFMAs per row tile instead of three vector instructions per accumulator register.
+                    v8i ident[2], px[MT];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const uint4 u = expand_unit(j == half ? 1u << l32 : 0u, 0u);       // 0x8 in the one nibble of bit l32
+                        ident[j] = as_operand(make_uint4(u.x | (u.x >> 2), u.y | (u.y >> 2), u.z | (u.z >> 2), u.w | (u.w >> 2)));
+                    }
+#pragma unroll
+                    for (int i = 0; i < MT; ++i) {
+                        const long long rrow = min(m0 + 32 * i + l32, g.rows - 1);
+                        const int wi = min(2 * h + half, e.ld_resid_bits_w - 1);
+                        px[i] = mfma::expand_fp4(e.resid_bits[rrow * (long long)e.ld_resid_bits_w + wi], c2);
+                    }
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[h][i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ident[j], px[i], acc[h][i][j], 4, 4, 0, 0, 0, 0);
+                    Epi e2 = e;
+                    e2.resid_bits = nullptr;
+                    epilogue_chain_swapped<MT>(acc[h], m0, 64 * h, lane, g, e2, start, corr2);
+                } else
+                    epilogue_chain_swapped<MT>(acc[h], m0, 64 * h, lane, g, e, start, corr2);
             } else
                 mfma::epilogue_sums<MT, 2>(acc[h], m0, 64 * h, lane, g, e, corr2);
         }
