@@ -700,9 +700,15 @@ size_t bwn_workspace_bytes(int C, int O, int k) {
     return (size_t)(cdiv(O, 128) * 128 * 2 * nsteps * 16);
 }
 
+bool try_bwn_wave(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int C, int O,
+                  int k, int stride, int pad, int P, int Q, void* workspace, size_t workspace_bytes, hipStream_t s, int* rc);
+
 int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W,
                         int C, int O, int k, int stride, int pad, void* workspace, size_t workspace_bytes, hipStream_t s) {
     const int P = (H + 2 * pad - k) / stride + 1, Q = (W + 2 * pad - k) / stride + 1;
+    int wave_rc = BNN_OK;
+    if (try_bwn_wave(x, wbits, thr, y, bits, N, H, W, C, O, k, stride, pad, P, Q, workspace, workspace_bytes, s, &wave_rc))
+        return wave_rc;                        // wave-private patches in LDS for the filter geometries that kernel is built for
     BwnTile g;
     size_t lds = 0;
     // LDS-staged kernel with small workgroups while several of them fit a CU side by side (one loads its
@@ -729,9 +735,11 @@ int launch_bwn_conv_thr(const float* x, const uint32_t* wbits, const float* thr,
 // epilogue, so the only memory wait a wave sees is one it has had a whole rectangle of MFMA work to cover; the eight
 // waves of a workgroup share nothing but the weights (copied to LDS once: the workgroups are persistent) and drift
 // apart, so that on every SIMD one wave stages while the other multiplies.  No barrier after the weights are in.
-template <int KS_, int STRIDE_, int CIN_, int FP_, int FQ_>
+// WAVES_: waves per workgroup (what fits LDS beside the weights); WPL_: weight planes -- 3 for real-valued weights (split
+// like the inputs), 1 for binarized weights (+1.0 / -1.0 are exact in bf16).
+template <int KS_, int STRIDE_, int CIN_, int FP_, int FQ_, int WAVES_ = 8, int WPL_ = 3>
 struct WaveGeom {
-    static constexpr int KS = KS_, STRIDE = STRIDE_, CIN = CIN_, FP = FP_, FQ = FQ_;
+    static constexpr int KS = KS_, STRIDE = STRIDE_, CIN = CIN_, FP = FP_, FQ = FQ_, WPL = WPL_;
     static constexpr int PR = (FP - 1) * STRIDE + KS;                        // patch rows
     static constexpr int ROW_ELEMS = ((FQ - 1) * STRIDE + KS) * CIN;         // input values of a patch row
     static constexpr int SEG = KS * CIN;                                     // values of one filter row
@@ -743,8 +751,8 @@ struct WaveGeom {
     static constexpr int PAIRS = PITCH / 4;                                  // 2-element units written per patch row (data + zeroed slack)
     static constexpr int PLANE = PR * PITCH;                                 // bytes of one bf16 plane of a patch
     static constexpr int WUNITS = NRUNS * 64;                                // 16-byte units of one weight plane in LDS
-    static constexpr int WAVES = 8;
-    static constexpr size_t LDS = (size_t)3 * WUNITS * 16 + (size_t)WAVES * 3 * PLANE;
+    static constexpr int WAVES = WAVES_;
+    static constexpr size_t LDS = (size_t)WPL * WUNITS * 16 + (size_t)WAVES * 3 * PLANE;
     static_assert(FP * FQ == 32 && PAIRS <= 64 && (STRIDE * CIN * 2) % 8 == 0, "one lane per pair; 8-byte aligned runs");
 };
 
@@ -764,16 +772,18 @@ struct WaveArgs {
 };
 
 template <class G, int TERMS, bool WANT_Y>
-__global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const float* __restrict__ x, const float* __restrict__ w,
+__global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const float* __restrict__ x, const void* __restrict__ wv,
                                                                         const float* __restrict__ thr, float* __restrict__ y,
                                                                         uint32_t* __restrict__ bits, WaveArgs g) {
     constexpr int NT = 2, COLS = 64;
+    constexpr bool BWN = G::WPL == 1;                                  // wv: weight bits [O][k][k][1 word] instead of floats [O][k][k][C]
+    static_assert(G::WPL == 3 || (G::WPL == 1 && G::CIN <= 32 && TERMS == 3), "three planes of real weights or one of +-1");
     extern __shared__ uint4 smem[];
-    uint4* wlds = smem;                                                // [3 planes][NRUNS][64 columns] units of 8 bf16
+    uint4* wlds = smem;                                                // [weight planes][NRUNS][64 columns] units of 8 bf16
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // scalar: everything derived from the rectangle index stays scalar
-    char* patch = reinterpret_cast<char*>(smem) + 3 * G::WUNITS * 16 + wave * (3 * G::PLANE);     // this wave's three planes
+    char* patch = reinterpret_cast<char*>(smem) + G::WPL * G::WUNITS * 16 + wave * (3 * G::PLANE);     // this wave's three planes
     const int n0 = (int)blockIdx.y * COLS;
 
     float th[NT];
@@ -849,7 +859,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
         }
     };
 
-    // Rectangle of this wave in round r: whole rounds give a workgroup eight consecutive rectangles; the last, partial
+    // Rectangle of this wave in round r: whole rounds give a workgroup's waves consecutive rectangles; the last, partial
     // round is dealt across the workgroups (wave 0 of each first), so that no compute unit runs a full extra round.
     const int step = (int)gridDim.x * G::WAVES;
     const int whole = g.ntiles / step;
@@ -859,7 +869,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
     };
     int t = tile_of(0);
     if (t < g.ntiles) request(t);              // the first patch is on its way while the weights are staged
-    {   // weights of this channel tile -> LDS, split on the way (w [O][k][k][C]; a run is 8 consecutive values of one filter
+    if constexpr (!BWN) {   // weights of this channel tile -> LDS, split on the way (w [O][k][k][C]; a run is 8 consecutive values of one filter
         // row, zero past the row's end; column = output channel): unit (plane, run, column) of wlds.  Every load is issued
         // before the first split; pairs past the end repeat the last one and store nothing.
         constexpr int PER = (G::WUNITS + G::WAVES * 64 - 1) / (G::WAVES * 64);
@@ -869,7 +879,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
             const int p = min(tid + i * G::WAVES * 64, G::WUNITS - 1);
             const int rho = p >> 6, o = min(n0 + (p & 63), g.O - 1);
             const int r = rho / G::RPR, j = rho - r * G::RPR;
-            const float* wrow = w + ((long long)o * G::KS + r) * G::SEG;
+            const float* wrow = static_cast<const float*>(wv) + ((long long)o * G::KS + r) * G::SEG;
 #pragma unroll
             for (int e = 0; e < 8; ++e) xs[i][e] = wrow[min(8 * j + e, G::SEG - 1)];
         }
@@ -898,6 +908,41 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
             }
         }
     }
+    if constexpr (BWN) {    // weight bits of this channel tile -> LDS as bf16 +1.0 / -1.0 (0 past a filter row's end and past
+        // the last channel): a run of 8 values lies in at most 8 / C + 2 tap words, all of them requested before the first is used
+        const uint32_t* wbits = static_cast<const uint32_t*>(wv);
+        constexpr int PER = (G::WUNITS + G::WAVES * 64 - 1) / (G::WAVES * 64), TW = 8 / G::CIN + 2;
+        uint32_t tw[PER][TW];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int p = min(tid + i * G::WAVES * 64, G::WUNITS - 1);
+            const int rho = p >> 6, o = min(n0 + (p & 63), g.O - 1);
+            const int r = rho / G::RPR, j = rho - r * G::RPR;
+            const uint32_t* wrow = wbits + ((long long)o * G::KS + r) * G::KS;          // one word per tap
+            const int t0 = (8 * j) / G::CIN;
+#pragma unroll
+            for (int q = 0; q < TW; ++q) tw[i][q] = wrow[min(t0 + q, G::KS - 1)];
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int p = tid + i * G::WAVES * 64;
+            const int rho = min(p, G::WUNITS - 1) >> 6;
+            const int j = rho % G::RPR;
+            const bool col_ok = n0 + (p & 63) < g.O;
+            const int t0 = (8 * j) / G::CIN;
+            uint32_t pk[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int el = 8 * j + e, t = el / G::CIN, c = el - t * G::CIN;
+                uint32_t word = 0u;
+#pragma unroll
+                for (int q = 0; q < TW; ++q) word = (t - t0 == q) ? tw[i][q] : word;
+                const uint32_t val = !(col_ok && el < G::SEG) ? 0u : ((word >> c) & 1u) ? 0x3F80u : 0xBF80u;
+                pk[e >> 1] |= val << (16 * (e & 1));
+            }
+            if (p < G::WUNITS) wlds[p] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+    }
     if (t < g.ntiles) stage(t);
     __syncthreads();                                                   // the only barrier: the weights are in place
     for (int r = 0; t < g.ntiles; ++r) {
@@ -912,7 +957,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
         // two operand sets: the LDS reads of step st + 1 are issued before the MFMAs of step st
-        uint4 oa[2][3], ob[2][3][NT];
+        uint4 oa[2][3], ob[2][G::WPL][NT];
         auto fetch = [&](auto st_tag) {
             constexpr int st = decltype(st_tag)::value;
             constexpr int rho0 = 2 * st, rho1 = 2 * st + 1;
@@ -928,9 +973,10 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
                 const uint2 lo = *reinterpret_cast<const uint2*>(asrc + pl * G::PLANE);
                 const uint2 hi = *reinterpret_cast<const uint2*>(asrc + pl * G::PLANE + 8);
                 oa[st & 1][pl] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                if (pl < G::WPL)
 #pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    ob[st & 1][pl][j] = *reinterpret_cast<const uint4*>(bsrc + pl * (G::WUNITS * 16) + j * (32 * 16));
+                    for (int j = 0; j < NT; ++j)
+                        ob[st & 1][pl][j] = *reinterpret_cast<const uint4*>(bsrc + pl * (G::WUNITS * 16) + j * (32 * 16));
             }
         };
         auto multiply = [&](auto st_tag) {
@@ -945,7 +991,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
 #pragma unroll
                 for (int px = 2; px >= 0; --px) {
                     const int pw = sum - px;
-                    if (pw < 0 || pw > 2) continue;
+                    if (pw < 0 || pw >= G::WPL) continue;
 #pragma unroll
                     for (int j = 0; j < NT; ++j)
                         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_bwn, oa[st & 1][px]),
@@ -962,7 +1008,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
             // the wave then waits out the LDS latency a dozen times per step: keep the reads of the next step between this
             // step's MFMAs, one each, and let nothing cross a step boundary.
 #pragma unroll
-            for (int q = 0; q < (TERMS == 9 ? 9 : 6) * NT; ++q) {
+            for (int q = 0; q < TERMS * NT; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
@@ -1009,7 +1055,7 @@ __global__ __launch_bounds__(G::WAVES * 64, 1) void conv_f32_wave_kernel(const f
 }
 
 template <class G, int TERMS, bool WANT_Y>
-int launch_conv_f32_wave_v(const float* x, const float* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int O,
+int launch_conv_f32_wave_v(const float* x, const void* w, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int O,
                            int pad, int P, int Q, void* workspace, size_t workspace_bytes, hipStream_t s) {
     const int col_tiles = (int)cdiv(O, 64);
     WaveArgs g;
@@ -1021,7 +1067,7 @@ int launch_conv_f32_wave_v(const float* x, const float* w, const float* thr, flo
     // This kernel splits the weights itself while it stages them; the workspace the entry point asks for (the other
     // first-layer kernels keep their expanded weights there) is checked all the same, so that the call's contract does
     // not depend on which kernel serves a shape.
-    if (workspace == nullptr || workspace_bytes < (size_t)3 * 2 * G::NSTEPS * 64 * 16 * col_tiles) return BNN_ERR_WORKSPACE;
+    if (workspace == nullptr || workspace_bytes < (size_t)G::WPL * 2 * G::NSTEPS * 64 * 16 * col_tiles) return BNN_ERR_WORKSPACE;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_f32_wave_kernel<G, TERMS, WANT_Y>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
     if (attr != hipSuccess) return BNN_ERR_DEVICE;
@@ -1050,6 +1096,23 @@ bool try_conv_f32_wave(const float* x, const float* w, const float* thr, float* 
     else
         *rc = products == 6 ? launch_conv_f32_wave_v<G, 6, false>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s)
                             : launch_conv_f32_wave_v<G, 9, false>(x, w, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s);
+    return true;
+}
+
+// Binarized weights on the wave-private kernel: the 11x11 stride-4 first layer of 3-channel images (one weight plane,
+// three term products; six waves: a patch is 23 rows).  true: launched (rc receives the status).
+bool try_bwn_wave(const float* x, const uint32_t* wbits, const float* thr, float* y, uint32_t* bits, int N, int H, int W, int C, int O,
+                  int k, int stride, int pad, int P, int Q, void* workspace, size_t workspace_bytes, hipStream_t s, int* rc) {
+    if (!(k == 11 && stride == 4 && C == 3)) return false;
+    if ((long long)W * C < 2 || (long long)H * W * C >= (1LL << 31)) return false;
+    constexpr int FP = 4, FQ = 8;
+    typedef WaveGeom<11, 4, 3, FP, FQ, 6, 1> G;
+    static_assert(G::LDS <= LDS_MAX, "weights and six patches fit LDS");
+    const long long tiles = (long long)N * cdiv(P, FP) * cdiv(Q, FQ);
+    if (tiles >= (1LL << 31) - 65536) return false;
+    if (tiles < 4096) return false;            // small batches: the LDS-staged and direct kernels (more workgroups, shorter prologue)
+    *rc = y != nullptr ? launch_conv_f32_wave_v<G, 3, true>(x, wbits, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s)
+                       : launch_conv_f32_wave_v<G, 3, false>(x, wbits, thr, y, bits, N, H, W, O, pad, P, Q, workspace, workspace_bytes, s);
     return true;
 }
 

@@ -284,6 +284,35 @@ def test_bwn_first_layer_shapes(bnn, orc, shape):
     assert np.array_equal(words(bnn.bwn_conv_thr(to_dev(x), to_dev(wb), to_dev(thr), C, st, pad)), words(bits))
 
 
+# 11x11 stride-4 first layers of 3-channel images with at least 4096 rectangles of 4 x 8 output pixels: the kernel with
+# wave-private patches (binarized weights: one weight plane); ragged rectangles, ragged and several 64-column tiles,
+# images of a single rectangle, odd padding
+@pytest.mark.parametrize("shape", [(300, 92, 76, 3, 36, 2), (230, 100, 90, 3, 100, 2), (4200, 11, 13, 3, 64, 2),
+                                   (330, 83, 79, 3, 130, 5)])
+def test_bwn_first_layer_11x11_wave_kernel(bnn, orc, shape):
+    N, H, W, C, O, pad = shape
+    k, st = 11, 4
+    P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    assert N * ((P + 3) // 4) * ((Q + 7) // 8) >= 4096
+    rng = np.random.default_rng(sum(shape) + 3)
+    x = rng.uniform(-1, 1, size=(N, H, W, C)).astype(np.float32)
+    wb = wl.random_bits(rng, (O, k, k), C)
+    thr = rng.normal(0, 3.0, size=O).astype(np.float32)
+    bits, y = bnn.bwn_conv_thr(to_dev(x), to_dev(wb), to_dev(thr), C, st, pad, want_f32=True)
+    ref = orc.bwn_conv_f32(x, wb, C, st, pad)
+    err = np.abs(host(y) - ref)
+    print("bwn 11x11", shape, "max error", float(err.max()), "of rms", float(np.sqrt((ref.astype(np.float64) ** 2).mean())), flush=True)
+    assert host(y).shape == ref.shape
+    assert (err <= 1e-4 * np.maximum(np.abs(ref), np.sqrt((ref.astype(np.float64) ** 2).mean()))).all()
+    assert err.max() <= 2e-6 * max(1.0, np.abs(ref).max()) * np.sqrt(k * k * C)
+    assert np.array_equal(words(bits), orc.pack_f32(host(y), thr))
+    assert np.array_equal(words(bnn.bwn_conv_thr(to_dev(x), to_dev(wb), to_dev(thr), C, st, pad)), words(bits))
+    # integer inputs: every product and every partial sum is exact, so the result equals the oracle's bit for bit
+    xi = rng.integers(-2000, 2001, size=(N, H, W, C)).astype(np.float32)
+    _, yi = bnn.bwn_conv_thr(to_dev(xi), to_dev(wb), to_dev(thr), C, st, pad, want_f32=True)
+    assert np.array_equal(host(yi), orc.bwn_conv_f32(xi, wb, C, st, pad))
+
+
 def test_bwn_exact_cases(bnn, orc):
     # (a) integer inputs: the three-way bf16 split is exact and sums below 2^24 never round, so the fp32
     # result equals the oracle's bit for bit; (b) isolated values with all 24 significand bits set (at most
