@@ -174,7 +174,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
     uint4* const filt = lds;                                         // [tap][word][column]
     uint4* const patch = lds + 9 * CW * COLSP + wave * 2 * pa.plane; // [half of the slab][cell]
     // bits kind: start values of the accumulators, [column tile][half-wave][register] (see SWAPPED below)
-    float* const start = reinterpret_cast<float*>(lds + 9 * CW * COLSP + WAVES * 2 * pa.plane);
+    // (eight copies, one unit more than a copy apart: the eight lanes LDS serves together read eight different units --
+    // sixteen lanes reading ONE 16-byte unit are not a broadcast but a conflict)
+    constexpr int START_PITCH = NT * 2 * 16 + 4;
+    float* const start_all = reinterpret_cast<float*>(lds + 9 * CW * COLSP + WAVES * 2 * pa.plane);
+    const float* const start = start_all + (l32 & 7) * START_PITCH;
     const char* const Ab = reinterpret_cast<const char*>(A);
 
     // A tile's first output pixel (wave-uniform; scalar arithmetic).  Everything a lane needs is then a small
@@ -293,7 +297,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
             const int lim = 1 << 20;                 // beyond every reachable sum (K <= 1152 here, residual sums are 16-bit)
             v = 0.5f - (float)max(-lim, min(lim, e.thr[col]));
         }
-        start[(jt * 2 + hf) * 16 + reg] = v;
+#pragma unroll
+        for (int cp = 0; cp < 8; ++cp) start_all[cp * START_PITCH + (jt * 2 + hf) * 16 + reg] = v;
     }
     __syncthreads();
 
@@ -477,7 +482,7 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     if (pp > 16) return pl;
     if ((images * (g.H + 1) + 2) * (g.W + 1) + 64LL * pp >= (1LL << 31)) return pl;          // cell numbers fit an int
     if (images * g.H * g.W * g.tw * 4 >= (1LL << 32)) return pl;                              // 32-bit byte offsets
-    pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16 + (size_t)pl.nt * 2 * 16 * 4;
+    pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16 + (size_t)8 * (pl.nt * 2 * 16 + 4) * 4;
     if (pl.lds_bytes > 160 * 1024) return pl;
     const long long ntiles = cdiv(g.rows, 64);
     // Measured against the direct kernels on 56x56x64->64 and 28x28 / 56x56x128->128 layers over batch sizes: the

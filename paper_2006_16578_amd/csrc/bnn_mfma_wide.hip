@@ -134,9 +134,12 @@ __global__ __launch_bounds__(WIDE_THREADS, 1) void mfma_wide_kernel(const uint32
                                                                             acc[i][j], 4, 4, 0, 0, 0, 0);
     };
 
-    // One slab (as in the kernel above): A fragments and the expansion of this wave's B fragments run one K-step ahead;
-    // the next slab is stored during K-steps 1 and 2, the barrier follows K-step 2, and K-step 3 fetches the next slab's
-    // packed B words and first A fragments.
+    // One slab: four K-steps from buffer s & 1.  A fragments and the expansion of this wave's B fragments run one K-step
+    // ahead.  MORE: the next slab (held in ga / gb) is stored into the other buffer during K-steps 1 and 2 and the registers
+    // are refilled from global memory with the slab after it right behind (clamped to the last slab: a redundant load, no
+    // branch); the ONE barrier of the slab follows K-step 2 -- by then every wave has read all of this slab's LDS data
+    // (its last fragments were requested before K-step 2's MFMAs and the barrier waits for them) and has written its
+    // share of the next -- and K-step 3 fetches the next slab's packed B words and first A fragments.
     auto slab = [&](int s, auto more, auto masked) {
         constexpr bool MORE = decltype(more)::value;
         const int buf = s & 1;
@@ -145,7 +148,9 @@ __global__ __launch_bounds__(WIDE_THREADS, 1) void mfma_wide_kernel(const uint32
         for (int v = 0; v < 4; ++v) {
             if (v < 3) { read_a(buf, v + 1, (v + 1) & 1); expand_b(v + 1, (v + 1) & 1); }
             if (MORE && v == 3) { read_a(buf ^ 1, 0, 0); read_bq(buf ^ 1); expand_b(0, 0); }
-            if (v == 0 && s > 0) read_bq(buf); // (again: carrying the four words over the loop edge costs hundreds of spilled registers)
+            // the packed B words again rather than carried over the loop edge: with them live across the edge (or with this
+            // read unconditional) the compiler spills 400-600 registers in this loop
+            if (v == 0 && s > 0) read_bq(buf);
             if (MORE && v == 1) { store_a(buf ^ 1, s + 1, masked); load_a(s2); }
             if (MORE && v == 2) { store_b(buf ^ 1, s + 1, masked); load_b(s2); }
             multiply(v & 1);
