@@ -31,7 +31,7 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
-TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.416e+08}
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.406e+08}
 
 
 # Table 6 of the paper, BTC-FMT row (RTX 2080; trained weights, real data): context only
