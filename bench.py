@@ -32,6 +32,7 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
 TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.406e+08}
+WIDE_KERNEL = "mfma_fp4_bmm_xlds_wg256x256"
 
 
 # Table 6 of the paper, BTC-FMT row (RTX 2080; trained weights, real data): context only
@@ -51,6 +52,9 @@ def main() -> int:
     ap.add_argument("--path", choices=["auto", "valu", "mfma"], default="auto", help="arithmetic path (profiling runs)")
     ap.add_argument("--shapes", default="", help="comma-separated subset of the sweep, e.g. sq8192 (profiling runs)")
     ap.add_argument("--variant", choices=["both", "bits", "int32"], default="both", help="epilogues to run (profiling runs)")
+    ap.add_argument("--layout", choices=["rows", "panels"], default="rows",
+                    help="panels: the shapes that take the 256x256-tile kernel get both operands (and write the packed "
+                         "output) in the K-panel layout of bnn.h; the default line is measured on row-major operands")
     ap.add_argument("--only", default="", help="run only these extra sections (comma-separated: bconv, bconv_sweep, general, "
                                                "layout, mlp, resnet18, table5, cfg1; or roofline alone) and print them; the BMM sweep is skipped (profiling runs)")
     ap.add_argument("--resnet-batches", default="256,8", help="batch sizes of the ResNet-18 section (profiling runs)")
@@ -105,117 +109,160 @@ def main() -> int:
     path = {"auto": bnn.PATH_AUTO, "valu": bnn.PATH_VALU, "mfma": bnn.PATH_MFMA}[args.path]
     only = [t for t in args.shapes.split(",") if t]
     do_bits, do_i32 = args.variant in ("both", "bits"), args.variant in ("both", "int32")
-    shapes = []
-    for name, M, N, K, _ in wl.cfg2_shapes():
-        if only and name not in only:
-            continue
-        case = wl.cfg2_case(name)
-        A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
-        Cb = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
-        C = torch.empty((M, N), dtype=torch.int32, device=dev)
-        shapes.append({"name": name, "M": M, "N": N, "K": K, "A": A, "B": B, "tau": tau, "Cb": Cb, "C": C,
-                       "kernel": bnn.bmm_kernel_name(M, N, K, path),
-                       "kernel_i32": bnn.bmm_kernel_name(M, N, K, path, int32_out=True)})
-    macs_step = sum((do_bits + do_i32) * float(s["M"]) * s["N"] * s["K"] for s in shapes)
+    def sweep(layout, steps, warmup, trains):
+        """One timed run of the sweep: warmup untimed steps, then `steps` timed ones; per-shape figures and the roofline
+        of the kernel variant with the most time in a step."""
+        shapes = []
+        for name, M, N, K, _ in wl.cfg2_shapes():
+            if only and name not in only:
+                continue
+            case = wl.cfg2_case(name)
+            A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+            Cb = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
+            C = torch.empty((M, N), dtype=torch.int32, device=dev)
+            sh = {"name": name, "M": M, "N": N, "K": K, "A": A, "B": B, "tau": tau, "Cb": Cb, "C": C, "panels": False,
+                  "kernel": bnn.bmm_kernel_name(M, N, K, path),
+                  "kernel_i32": bnn.bmm_kernel_name(M, N, K, path, int32_out=True)}
+            if layout == "panels" and sh["kernel"] == WIDE_KERNEL and sh["kernel_i32"] == WIDE_KERNEL:
+                sh.update({"panels": True, "A": bnn.panels_from_rows(A, K), "B": bnn.panels_from_rows(B, K),
+                           "Cb": torch.empty(((N + 255) // 256, M, 8), dtype=torch.int32, device=dev),
+                           "kernel": WIDE_KERNEL + "_kpanels", "kernel_i32": WIDE_KERNEL + "_kpanels"})
+                del A, B
+            shapes.append(sh)
+        macs_step = sum((do_bits + do_i32) * float(s["M"]) * s["N"] * s["K"] for s in shapes)
 
-    def one_step(record: bool):
-        for s in shapes:
-            if record:
-                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-                e0.record()
-            if do_bits:
+        def run_bits(s):
+            if s["panels"]:
+                bnn.bmm_thr_panels(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"])
+            else:
                 bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path)
-            if record:
-                e1.record()
-            if do_i32:
+
+        def run_i32(s):
+            if s["panels"]:
+                bnn.bmm_panels(s["A"], s["B"], s["K"], out=s["C"])
+            else:
                 bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path)
-            if record:
-                e2.record()
-                s["ev"].append((e0, e1, e2))
 
-    for s in shapes:
-        s["ev"] = []
-    for _ in range(args.warmup):
-        one_step(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value_tops = macs_step * 2.0 / (ms_per_step * 1e-3) / 1e12
+        def one_step(record: bool):
+            for s in shapes:
+                if record:
+                    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                    e0.record()
+                if do_bits:
+                    run_bits(s)
+                if record:
+                    e1.record()
+                if do_i32:
+                    run_i32(s)
+                if record:
+                    e2.record()
+                    s["ev"].append((e0, e1, e2))
 
-    # Per-shape figures.  A lone launch between two events reads no less than the launch gap of the stream, and a
-    # Python loop of launches no less than the host's 10 us per call, so every shape is ALSO timed as a train of
-    # launches queued behind a long-running kernel (_Train): `*_ms` is the GPU time per launch inside the train,
-    # `*_single_launch_ms` the in-step figure (what one isolated call costs, launch gap included).
-    per_shape = []
-    train = None if args.skip_trains else _Train(bnn, torch, dev)
-    for s in shapes:
-        thr_1 = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9) if do_bits else None
-        i32_1 = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9) if do_i32 else None
-        reps = lambda one_ms: int(min(200, max(5, 2.0 / max(one_ms, 1e-3))))
-        thr_ms = (thr_1 if args.skip_trains else
-                  train.time(lambda: bnn.bmm_thr(s["A"], s["B"], s["tau"], s["K"], out=s["Cb"], path=path), reps(thr_1))) if do_bits else None
-        i32_ms = (i32_1 if args.skip_trains else
-                  train.time(lambda: bnn.bmm(s["A"], s["B"], s["K"], out=s["C"], path=path), reps(i32_1))) if do_i32 else None
-        ops = 2.0 * s["M"] * s["N"] * s["K"]
-        kw = wl.nwords(s["K"]) * 4
-        bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
-        bytes_i32 = s["M"] * kw + s["N"] * kw + s["M"] * s["N"] * 4
-        row = {"shape": s["name"], "M": s["M"], "N": s["N"], "K": s["K"]}
-        if do_bits:
-            row.update({"kernel": s["kernel"], "bits_out_ms": round(thr_ms, 5), "bits_out_single_launch_ms": round(thr_1, 5),
-                        "bits_out_tops": round(ops / thr_ms / 1e9, 2),
-                        "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
-                        "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
-                        "bits_out_frac_hbm_peak": round(bytes_thr / thr_ms / 1e6 / PEAK_HBM_GBS, 4)})
-        if do_i32:
-            row.update({"int32_out_kernel": s["kernel_i32"], "int32_out_ms": round(i32_ms, 5),
-                        "int32_out_single_launch_ms": round(i32_1, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
-                        "int32_out_frac_fp4_mfma_peak": round(ops / i32_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
-                        "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1),
-                        "int32_out_frac_hbm_peak": round(bytes_i32 / i32_ms / 1e6 / PEAK_HBM_GBS, 4)})
-        row["in_step_ms"] = {"bits": round(thr_1, 5) if do_bits else None, "int32": round(i32_1, 5) if do_i32 else None}
-        per_shape.append(row)
+        for s in shapes:
+            s["ev"] = []
+        for _ in range(warmup):
+            one_step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_step(True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / steps
+        value_tops = macs_step * 2.0 / (ms_per_step * 1e-3) / 1e12
 
-    # roofline of the dominant kernel: the launches (both epilogues) of the kernel variant that
-    # takes the most time in a step
-    by_kernel = {}
-    for s, ps in zip(shapes, per_shape):
-        kw = (s["M"] + s["N"]) * wl.nwords(s["K"]) * 4
-        # launch durations measured inside the timed region (events on the launch stream around every launch)
-        for on, kern, ms, out_bytes in ((do_bits, s["kernel"], ps["in_step_ms"]["bits"], s["M"] * wl.nwords(s["N"]) * 4),
-                                        (do_i32, s["kernel_i32"], ps["in_step_ms"]["int32"], 4 * s["M"] * s["N"])):
-            if on:
-                d = by_kernel.setdefault(kern, {"ms": 0.0, "flop": 0.0, "launches": 0, "bytes": 0})
-                d["ms"] += ms
-                d["flop"] += 2.0 * s["M"] * s["N"] * s["K"]
-                d["launches"] += 1
-                d["bytes"] += kw + out_bytes
-    dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
-    dk = by_kernel[dom]
-    achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
-    probe_buf = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
-    measured_peak = bnn.probe_pipeline("mfma_fp4", probe_buf, iters=4000)[0] / 1e12
-    measured_loop = bnn.probe_pipeline("mfma_fp4_expand", probe_buf, iters=4000)[0] / 1e12
-    del probe_buf
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_FP4_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4),
-                "measured_peak": round(measured_peak, 1), "frac_of_measured_peak": round(achieved / measured_peak, 4),
-                "measured_expand_plus_mfma_loop": round(measured_loop, 1),
-                "frac_of_measured_loop": round(achieved / measured_loop, 4),
-                "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
-                            else None),
-                "algorithmic_bytes_per_launch": round(dk["bytes"] / max(dk["launches"], 1)),
-                "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
-                "flop_per_launch": dk["flop"] / dk["launches"],
-                "note": "peak: published fp4 (E2M1) dense matrix-core rate; measured_peak: the same MFMA alone, register-"
-                        "resident, in this run; measured_expand_plus_mfma_loop: the kernel's inner loop without memory "
-                        "(bnn_probe_pipeline); 1 MAC on +1/-1 = 2 flop = 2 binary ops"}
+        # Per-shape figures.  A lone launch between two events reads no less than the launch gap of the stream, and a
+        # Python loop of launches no less than the host's 10 us per call, so every shape is ALSO timed as a train of
+        # launches queued behind a long-running kernel (_Train): `*_ms` is the GPU time per launch inside the train,
+        # `*_single_launch_ms` the in-step figure (what one isolated call costs, launch gap included).
+        per_shape = []
+        train = None if not trains else _Train(bnn, torch, dev)
+        for s in shapes:
+            thr_1 = max(float(np.mean([a.elapsed_time(b) for a, b, _ in s["ev"]])), 1e-9) if do_bits else None
+            i32_1 = max(float(np.mean([b.elapsed_time(c) for _, b, c in s["ev"]])), 1e-9) if do_i32 else None
+            reps = lambda one_ms: int(min(200, max(5, 2.0 / max(one_ms, 1e-3))))
+            thr_ms = (thr_1 if not trains else
+                      train.time(lambda: run_bits(s), reps(thr_1))) if do_bits else None
+            i32_ms = (i32_1 if not trains else
+                      train.time(lambda: run_i32(s), reps(i32_1))) if do_i32 else None
+            ops = 2.0 * s["M"] * s["N"] * s["K"]
+            kw = wl.nwords(s["K"]) * 4
+            bytes_thr = s["M"] * kw + s["N"] * kw + s["M"] * wl.nwords(s["N"]) * 4 + s["N"] * 4
+            bytes_i32 = s["M"] * kw + s["N"] * kw + s["M"] * s["N"] * 4
+            row = {"shape": s["name"], "M": s["M"], "N": s["N"], "K": s["K"]}
+            if do_bits:
+                row.update({"kernel": s["kernel"], "bits_out_ms": round(thr_ms, 5), "bits_out_single_launch_ms": round(thr_1, 5),
+                            "bits_out_tops": round(ops / thr_ms / 1e9, 2),
+                            "bits_out_frac_fp4_mfma_peak": round(ops / thr_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                            "bits_out_hbm_gbs": round(bytes_thr / thr_ms / 1e6, 1),
+                            "bits_out_frac_hbm_peak": round(bytes_thr / thr_ms / 1e6 / PEAK_HBM_GBS, 4)})
+            if do_i32:
+                row.update({"int32_out_kernel": s["kernel_i32"], "int32_out_ms": round(i32_ms, 5),
+                            "int32_out_single_launch_ms": round(i32_1, 5), "int32_out_tops": round(ops / i32_ms / 1e9, 2),
+                            "int32_out_frac_fp4_mfma_peak": round(ops / i32_ms / 1e9 / PEAK_FP4_MFMA_TFLOPS, 4),
+                            "int32_out_hbm_gbs": round(bytes_i32 / i32_ms / 1e6, 1),
+                            "int32_out_frac_hbm_peak": round(bytes_i32 / i32_ms / 1e6 / PEAK_HBM_GBS, 4)})
+            row["in_step_ms"] = {"bits": round(thr_1, 5) if do_bits else None, "int32": round(i32_1, 5) if do_i32 else None}
+            per_shape.append(row)
+
+        # roofline of the dominant kernel: the launches (both epilogues) of the kernel variant that
+        # takes the most time in a step
+        by_kernel = {}
+        for s, ps in zip(shapes, per_shape):
+            kw = (s["M"] + s["N"]) * wl.nwords(s["K"]) * 4
+            # launch durations measured inside the timed region (events on the launch stream around every launch)
+            for on, kern, ms, out_bytes in ((do_bits, s["kernel"], ps["in_step_ms"]["bits"], s["M"] * wl.nwords(s["N"]) * 4),
+                                            (do_i32, s["kernel_i32"], ps["in_step_ms"]["int32"], 4 * s["M"] * s["N"])):
+                if on:
+                    d = by_kernel.setdefault(kern, {"ms": 0.0, "flop": 0.0, "launches": 0, "bytes": 0})
+                    d["ms"] += ms
+                    d["flop"] += 2.0 * s["M"] * s["N"] * s["K"]
+                    d["launches"] += 1
+                    d["bytes"] += kw + out_bytes
+        dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
+        dk = by_kernel[dom]
+        achieved = dk["flop"] / (dk["ms"] * 1e-3) / 1e12
+        probe_buf = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+        measured_peak = bnn.probe_pipeline("mfma_fp4", probe_buf, iters=4000)[0] / 1e12
+        measured_loop = bnn.probe_pipeline("mfma_fp4_expand", probe_buf, iters=4000)[0] / 1e12
+        del probe_buf
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_FP4_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_MFMA_TFLOPS, 4),
+                    "measured_peak": round(measured_peak, 1), "frac_of_measured_peak": round(achieved / measured_peak, 4),
+                    "measured_expand_plus_mfma_loop": round(measured_loop, 1),
+                    "frac_of_measured_loop": round(achieved / measured_loop, 4),
+                    "traffic": (TRAFFIC_DEFAULT_SWEEP.get(dom) if (args.path == "auto" and not only and args.variant == "both")
+                                else None),   # keyed by kernel AND layout (the panel runs carry the _kpanels name)
+                    "algorithmic_bytes_per_launch": round(dk["bytes"] / max(dk["launches"], 1)),
+                    "avg_launch_ms": round(dk["ms"] / dk["launches"], 5), "launches_per_step": dk["launches"],
+                    "flop_per_launch": dk["flop"] / dk["launches"],
+                    "note": "peak: published fp4 (E2M1) dense matrix-core rate; measured_peak: the same MFMA alone, register-"
+                            "resident, in this run; measured_expand_plus_mfma_loop: the kernel's inner loop without memory "
+                            "(bnn_probe_pipeline); 1 MAC on +1/-1 = 2 flop = 2 binary ops"}
+
+        return value_tops, ms_per_step, per_shape, roofline
+
+    value_tops, ms_per_step, per_shape, roofline = sweep(args.layout, args.steps, args.warmup, not args.skip_trains)
 
     extras = {}
+    if args.layout == "rows" and not args.skip_extras and args.path == "auto":
+        # the same sweep once more with the large squares in the K-panel layout (Sec. 5.1: the paper reports its
+        # products on its own fixed-stride format beside the general one); not the `value` of this line
+        v2, ms2, ps2, rf2 = sweep("panels", args.steps, args.warmup, False)
+        conv = []
+        for n in (4096, 16384):
+            X = torch.randint(-2**31, 2**31 - 1, (n, n // 32), dtype=torch.int32, device=dev)
+            Xp = bnn.panels_from_rows(X, n)
+            t_to = _time_gpu(torch, lambda: bnn.panels_from_rows(X, n), 10)
+            t_back = _time_gpu(torch, lambda: bnn.rows_from_panels(Xp, n), 10)
+            conv.append({"rows": n, "K": n, "panels_from_rows_ms": round(t_to, 5), "rows_from_panels_ms": round(t_back, 5)})
+            del X, Xp
+        extras["bmm_sweep_k_panels"] = {
+            "value": round(v2, 2), "unit": "binary TOPS", "ms_per_step": round(ms2, 4), "roofline": rf2,
+            "shapes_in_panels": [r for r in ps2 if r.get("kernel", r.get("int32_out_kernel", "")).endswith("_kpanels")],
+            "conversion": conv,
+            "note": "operands resident in HBM in the K-panel layout (bnn_panels_from_rows, done once and not timed, as "
+                    "for weights and for activations produced by bnn_bmm_thr_panels); the other shapes row-major as above"}
     if not args.skip_extras:
         extras = run_extras(bnn, wl, np, torch, to_dev, dev, None, rb, t5)
     cpu = None
@@ -232,7 +279,9 @@ def main() -> int:
         "config": {"workload": "BMM sweep (config 2): square n in {2048,4096,8192,16384} + FC M in {8,128,1024} x "
                                "K=4096 x N=4096; each shape with fused threshold->bits and with int32 output; "
                                "uniform random bits, seeded", "path": args.path,
-                   "shapes": args.shapes or "all", "variant": args.variant},
+                   "shapes": args.shapes or "all", "variant": args.variant,
+                   "layout": "row-major packed words" if args.layout == "rows" else
+                             "K panels of 256 bits for the shapes of the 256x256-tile kernel, row-major for the others"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "bmm_shapes": per_shape,

@@ -116,6 +116,21 @@ def tile_b(B) -> np.ndarray:
     return np.ascontiguousarray(padded.reshape(groups, 32, upr, 4).transpose(0, 2, 1, 3)).reshape(groups * 32, ldw)
 
 
+def panels(X, K: int) -> np.ndarray:
+    """The K-panel layout as its definition: K cut into panels of 256 bits, panel p holding words 8p .. 8p+7 of every
+    row back to back, [ceil(K/256)][rows][8]; bits past K are 0.  A pure permutation, no arithmetic."""
+    X = _words(X, 2)
+    rows, ldw = X.shape
+    kw = (K + 31) // 32
+    assert ldw >= kw
+    npan = (K + 255) // 256
+    padded = np.zeros((rows, npan * 8), dtype=np.uint32)
+    padded[:, :kw] = X[:, :kw]
+    if K % 32:
+        padded[:, kw - 1] &= np.uint32((1 << (K % 32)) - 1)
+    return np.ascontiguousarray(padded.reshape(rows, npan, 8).transpose(1, 0, 2))
+
+
 # ----------------------------------------------------------------------------- O3
 def conv_out_size(H: int, k: int, stride: int, pad: int) -> int:
     return (H + 2 * pad - k) // stride + 1

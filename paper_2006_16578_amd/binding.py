@@ -14,7 +14,7 @@ import torch
 
 __all__ = ["BnnError", "lib_path", "load", "PAD_MINUS_ONE", "PAD_EXCLUDE", "PATH_AUTO", "PATH_VALU", "PATH_MFMA",
            "nwords", "round_up", "bmm", "bmm_thr", "bconv", "bconv_thr", "threshold_pack", "pack_u8", "pack_f32",
-           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "probe_load_stride", "probe_pipeline", "probe_pipeline_enqueue", "PROBES", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "conv_f32_split_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
+           "unpack_i32", "tile_b", "bmm_tiled", "bmm_thr_tiled", "panels_from_rows", "rows_from_panels", "bmm_panels", "bmm_thr_panels", "probe_load_stride", "probe_pipeline", "probe_pipeline_enqueue", "PROBES", "sign_pack_f32", "bmm_general_f32", "bconv_general_f32", "maxpool_or", "conv_f32_thr", "conv_f32_split_thr", "bwn_conv_thr", "head_f32", "Net", "EXPORTS", "bmm_kernel_name", "bconv_kernel_name"]
 
 PAD_MINUS_ONE, PAD_EXCLUDE = 0, 1
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # every symbol include/bnn.h declares
 EXPORTS = ["bnn_status_string", "bnn_version", "bnn_bmm_kernel_name", "bnn_bconv_kernel_name", "bnn_bmm_kernel_name_out", "bnn_bconv_kernel_name_out", "bnn_bmm", "bnn_bmm_ex", "bnn_bmm_thr", "bnn_bmm_thr_ex",
            "bnn_bconv", "bnn_bconv_ex", "bnn_bconv_thr", "bnn_bconv_thr_ex", "bnn_threshold_pack", "bnn_pack_u8",
-           "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_probe_load_stride", "bnn_probe_pipeline", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
+           "bnn_pack_f32", "bnn_tile_b", "bnn_bmm_tiled", "bnn_bmm_thr_tiled", "bnn_panels_from_rows", "bnn_rows_from_panels", "bnn_bmm_panels", "bnn_bmm_thr_panels", "bnn_probe_load_stride", "bnn_probe_pipeline", "bnn_sign_pack_f32", "bnn_bmm_general_workspace_bytes", "bnn_bmm_general_f32",
            "bnn_bconv_general_workspace_bytes", "bnn_bconv_general_f32", "bnn_unpack_i32", "bnn_maxpool_or", "bnn_conv_f32_thr", "bnn_conv_f32_split_workspace_bytes", "bnn_conv_f32_split_thr", "bnn_conv_f32_split_thr_ex", "bnn_bwn_workspace_bytes", "bnn_bwn_conv_thr", "bnn_head_f32", "bnn_net_create",
            "bnn_net_destroy", "bnn_net_input_u8", "bnn_net_input_bits", "bnn_net_input_conv_f32", "bnn_net_input_bwn_f32", "bnn_net_add_fc",
            "bnn_net_add_conv", "bnn_net_add_pool", "bnn_net_add_block", "bnn_net_add_head_f32", "bnn_net_workspace_bytes",
@@ -252,6 +252,49 @@ def bmm_thr_tiled(A, Bt, thr, N: int, K: int, ldcb_w: int | None = None, out=Non
     with torch.cuda.device(A.device):
         _check(load().bnn_bmm_thr_tiled(_ptr(A), _ptr(Bt), _ptr(thr), _ptr(out), M, int(N), int(K), A.shape[1], Bt.shape[1],
                                         out.shape[1], _stream(A)), "bnn_bmm_thr_tiled")
+    return out
+
+
+def panels_from_rows(X, K: int):
+    """Packed [rows][ldx_w] -> the K-panel layout ([ceil(K/256)][rows][8] words) that bmm_panels / bmm_thr_panels read."""
+    _dev(X, _BITS, 2, "X")
+    rows, ldx = X.shape
+    out = torch.empty(((int(K) + 255) // 256, rows, 8), dtype=_BITS, device=X.device)
+    with torch.cuda.device(X.device):
+        _check(load().bnn_panels_from_rows(_ptr(X), _ptr(out), ctypes.c_int64(rows), int(K), ldx, _stream(X)), "bnn_panels_from_rows")
+    return out
+
+
+def rows_from_panels(Xp, K: int, ldx_w: int | None = None):
+    """The K-panel layout back to packed rows [rows][ldx_w]."""
+    _dev(Xp, _BITS, 3, "Xp")
+    rows = Xp.shape[1]
+    ldx_w = round_up(nwords(K), 4) if ldx_w is None else int(ldx_w)
+    out = torch.empty((rows, ldx_w), dtype=_BITS, device=Xp.device)
+    with torch.cuda.device(Xp.device):
+        _check(load().bnn_rows_from_panels(_ptr(Xp), _ptr(out), ctypes.c_int64(rows), int(K), ldx_w, _stream(Xp)), "bnn_rows_from_panels")
+    return out
+
+
+def bmm_panels(Ap, Bp, K: int, out=None):
+    """int32 [M][N] = A x B^T with both operands in K panels ([panels][rows][8])."""
+    _dev(Ap, _BITS, 3, "Ap"); _dev(Bp, _BITS, 3, "Bp")
+    M, N = Ap.shape[1], Bp.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Ap.device)
+    with torch.cuda.device(Ap.device):
+        _check(load().bnn_bmm_panels(_ptr(Ap), _ptr(Bp), _ptr(out), M, N, int(K), out.shape[1], _stream(Ap)), "bnn_bmm_panels")
+    return out
+
+
+def bmm_thr_panels(Ap, Bp, thr, K: int, out=None):
+    """Fused threshold; the output bits come in K panels ([ceil(N/256)][M][8]), the next product's A."""
+    _dev(Ap, _BITS, 3, "Ap"); _dev(Bp, _BITS, 3, "Bp"); _dev(thr, torch.int32, 1, "thr")
+    M, N = Ap.shape[1], Bp.shape[1]
+    if out is None:
+        out = torch.empty(((N + 255) // 256, M, 8), dtype=_BITS, device=Ap.device)
+    with torch.cuda.device(Ap.device):
+        _check(load().bnn_bmm_thr_panels(_ptr(Ap), _ptr(Bp), _ptr(thr), _ptr(out), M, N, int(K), _stream(Ap)), "bnn_bmm_thr_panels")
     return out
 
 

@@ -375,6 +375,41 @@ int bnn_bmm_thr_tiled(const uint32_t* A, const uint32_t* B_tiled, const int32_t*
     if (!Cbits || !thr) return BNN_ERR_INVALID_ARG;
     return bmm_common(A, B_tiled, nullptr, thr, Cbits, M, N, K, lda_w, ldb_w, 0, ldcb_w, BNN_PATH_MFMA, stream, false, true);
 }
+int bnn_panels_from_rows(const uint32_t* X, uint32_t* Xp, int64_t rows, int K, int ldx_w, void* stream) {
+    if (!X || !Xp || rows < 1 || K < 1 || ldx_w < words(K)) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K || rows >= (1LL << 31)) return BNN_ERR_UNSUPPORTED;
+    if (!aligned16(Xp)) return BNN_ERR_ALIGNMENT;
+    return launch_panels_from_rows(X, Xp, rows, K, ldx_w, static_cast<hipStream_t>(stream));
+}
+int bnn_rows_from_panels(const uint32_t* Xp, uint32_t* X, int64_t rows, int K, int ldx_w, void* stream) {
+    if (!X || !Xp || rows < 1 || K < 1 || ldx_w < words(K)) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K || rows >= (1LL << 31)) return BNN_ERR_UNSUPPORTED;
+    if ((ldx_w & 3) || !aligned16(Xp) || !aligned16(X)) return BNN_ERR_ALIGNMENT;
+    return launch_rows_from_panels(Xp, X, rows, K, ldx_w, static_cast<hipStream_t>(stream));
+}
+static int bmm_panels_common(const uint32_t* Ap, const uint32_t* Bp, int32_t* C, const int32_t* thr, uint32_t* Cbits_p, int M, int N,
+                             int K, int ldc, void* stream) {
+    if (!Ap || !Bp || M < 1 || N < 1 || K < 1) return BNN_ERR_INVALID_ARG;
+    if (K > BNN_MAX_K) return BNN_ERR_UNSUPPORTED;
+    if (!aligned16(Ap) || !aligned16(Bp)) return BNN_ERR_ALIGNMENT;
+    if (C && (ldc < N || !aligned16(C))) return ldc < N ? BNN_ERR_INVALID_ARG : BNN_ERR_ALIGNMENT;
+    if (Cbits_p && (!aligned16(Cbits_p) || !aligned16(thr))) return BNN_ERR_ALIGNMENT;
+    const int kw8 = (words(K) + 7) / 8 * 8;
+    Geom g = bmm_geom(M, N, K, kw8, kw8);
+    g.tw = kw8;
+    Epi e = {};
+    e.out = C; e.ldc = ldc; e.thr = thr; e.bits = Cbits_p; e.ldbits_w = (words(N) + 7) / 8 * 8;
+    return launch_mfma_wide_panels(Ap, Bp, g, e, static_cast<hipStream_t>(stream));
+}
+int bnn_bmm_panels(const uint32_t* Ap, const uint32_t* Bp, int32_t* C, int M, int N, int K, int ldc, void* stream) {
+    if (!C) return BNN_ERR_INVALID_ARG;
+    return bmm_panels_common(Ap, Bp, C, nullptr, nullptr, M, N, K, ldc, stream);
+}
+int bnn_bmm_thr_panels(const uint32_t* Ap, const uint32_t* Bp, const int32_t* thr, uint32_t* Cbits_p, int M, int N, int K,
+                       void* stream) {
+    if (!Cbits_p || !thr) return BNN_ERR_INVALID_ARG;
+    return bmm_panels_common(Ap, Bp, nullptr, thr, Cbits_p, M, N, K, 0, stream);
+}
 int bnn_probe_load_stride(const uint32_t* zeros, int64_t* cycles, int stride_bytes, int rows, int iters, int dependent,
                           void* stream) {
     if (!zeros || !cycles || stride_bytes < 32 || (stride_bytes & 15) || rows < 32 || iters < 1) return BNN_ERR_INVALID_ARG;

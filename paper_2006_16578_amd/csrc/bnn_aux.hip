@@ -59,6 +59,36 @@ __global__ __launch_bounds__(256) void tile_b_kernel(const uint4* __restrict__ B
     Bt[d] = row < N ? B[row * upr + u] : make_uint4(0u, 0u, 0u, 0u);
 }
 
+// K-panel layout (the fixed-stride idea of Sec. 5.1 with this chip's sizes): K is cut into panels of 256 bits and panel p
+// stores its 32 bytes of every row back to back, so 16-byte unit u of row r sits at unit ((u / 2) * rows + r) * 2 + u % 2.
+// The last panel is filled up with 0 bits.  One thread per destination unit, both directions.
+__global__ __launch_bounds__(256) void panels_from_rows_kernel(const uint32_t* __restrict__ X, uint4* __restrict__ Xp, long long rows,
+                                                               int K, int ldx_w, long long nunits) {
+    const long long d = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (d >= nunits) return;
+    const long long t = d >> 1;
+    const long long panel = t / rows;
+    const long long r = t - panel * rows;
+    const int w0 = (int)(panel * 8 + 4 * (d & 1));
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int left = K - 32 * (w0 + i);          // logical bits from this word on
+        const uint32_t v = left > 0 ? X[r * ldx_w + w0 + i] : 0u;
+        w[i] = left >= 32 ? v : left > 0 ? v & (0xFFFFFFFFu >> (32 - left)) : 0u;
+    }
+    Xp[d] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__global__ __launch_bounds__(256) void rows_from_panels_kernel(const uint4* __restrict__ Xp, uint4* __restrict__ X, long long rows,
+                                                               int npanels, int upr, long long nunits) {
+    const long long d = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (d >= nunits) return;
+    const long long r = d / upr;
+    const int u = (int)(d - r * upr);
+    X[d] = (u >> 1) < npanels ? Xp[((long long)(u >> 1) * rows + r) * 2 + (u & 1)] : make_uint4(0u, 0u, 0u, 0u);
+}
+
 // Load-latency probe in the manner of the paper's Sec. 4.1 (latency of a tile load against the row stride):
 // one wave repeatedly loads the operand fragment of one MFMA -- lane l reads 16 bytes of row l % 32 at byte
 // offset 16 * (l / 32) -- from rows `stride` bytes apart, walking along K.  dependent = 1 chains each address
@@ -539,6 +569,21 @@ int launch_tile_b(const uint32_t* B, uint32_t* Bt, int N, int ldb_w, hipStream_t
     const long long nunits = cdiv(N, 32) * 32 * (long long)upr;
     hipLaunchKernelGGL(tile_b_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, reinterpret_cast<const uint4*>(B),
                        reinterpret_cast<uint4*>(Bt), N, upr, nunits);
+    return check_launch();
+}
+
+int launch_panels_from_rows(const uint32_t* X, uint32_t* Xp, long long rows, int K, int ldx_w, hipStream_t s) {
+    const long long nunits = cdiv(K, 256) * rows * 2;
+    hipLaunchKernelGGL(panels_from_rows_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s, X, reinterpret_cast<uint4*>(Xp),
+                       rows, K, ldx_w, nunits);
+    return check_launch();
+}
+
+int launch_rows_from_panels(const uint32_t* Xp, uint32_t* X, long long rows, int K, int ldx_w, hipStream_t s) {
+    const int upr = ldx_w / 4;
+    const long long nunits = rows * upr;
+    hipLaunchKernelGGL(rows_from_panels_kernel, dim3((unsigned)cdiv(nunits, 256)), dim3(256), 0, s,
+                       reinterpret_cast<const uint4*>(Xp), reinterpret_cast<uint4*>(X), rows, (int)cdiv(K, 256), upr, nunits);
     return check_launch();
 }
 

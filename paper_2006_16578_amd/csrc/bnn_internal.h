@@ -133,6 +133,7 @@ int launch_mfma_skinny(const uint32_t* A, const uint32_t* B, const Geom& g, cons
 // Large matrix products: 256 x 256 workgroup tiles whose operands are expanded once, on their way into LDS.
 bool mfma_wide_takes(const Geom& g, const Epi& e);
 int launch_mfma_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
+int launch_mfma_wide_panels(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s);
 // 3x3 stride-1 pad-1 convolutions with at most 128 channels in and out: filters resident in LDS, wave-private input patches.
 bool mfma_conv_patch_takes(const Geom& g, const Epi& e);
 const char* describe_mfma_conv_patch(const Geom& g);
@@ -150,6 +151,8 @@ int launch_threshold_pack(const int32_t* X, const int32_t* thr, uint32_t* bits, 
 int launch_pack_u8(const uint8_t* x, int thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);
 int launch_sign_pack_f32(const float* x, uint32_t* bits, long long rows, int cols, int ldx, int ldb_w, hipStream_t s);
 int launch_tile_b(const uint32_t* B, uint32_t* Bt, int N, int ldb_w, hipStream_t s);
+int launch_panels_from_rows(const uint32_t* X, uint32_t* Xp, long long rows, int K, int ldx_w, hipStream_t s);
+int launch_rows_from_panels(const uint32_t* Xp, uint32_t* X, long long rows, int K, int ldx_w, hipStream_t s);
 int launch_probe_stride(const uint32_t* buf, long long* cycles, int stride_bytes, int rows, int iters, int dependent, hipStream_t s);
 int launch_probe_pipeline(int which, void* buf, size_t buf_bytes, int iters, double* work, hipStream_t s);
 int launch_pack_f32(const float* x, const float* thr, uint32_t* bits, long long rows, int cols, int ldb_w, hipStream_t s);

@@ -377,7 +377,8 @@ __device__ __forceinline__ void column_thresholds(int (&thi)[NT], bool (&cok)[NT
 
 // Bits only: compare the fp32 accumulators (exact integers) against the threshold shifted by the pad correction;
 // one v_cmp per accumulator register gives two packed words.
-template <int MT, int NT>
+// PANELS: the packed output is laid out in panels of 8 words (word wi of row `row` at ((wi / 8) * rows + row) * 8 + wi % 8).
+template <int MT, int NT, bool PANELS = false>
 __device__ __forceinline__ void epilogue_bits(v16f (&acc)[MT][NT], const long long m0, const int n0, const int lane,
                                               const Geom& g, const Epi& e, const int corr_all, const int (&thi)[NT],
                                               const bool (&cok)[NT]) {
@@ -406,7 +407,7 @@ __device__ __forceinline__ void epilogue_bits(v16f (&acc)[MT][NT], const long lo
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 const int wi = (n0 >> 5) + j;
-                if (wi < e.ldbits_w) e.bits[row * e.ldbits_w + wi] = wout[j];
+                if (wi < e.ldbits_w) e.bits[PANELS ? ((wi >> 3) * g.rows + row) * 8 + (wi & 7) : row * e.ldbits_w + wi] = wout[j];
             }
         }
     }

@@ -60,6 +60,10 @@ constexpr int BP = TILE + 4;                        // units between the two pla
 constexpr int A_UNITS = 8 * WS;
 constexpr int BUF_UNITS = A_UNITS + 2 * BP;         // A expanded: 8 words x 257 units; B packed: 2 planes of 4 words per row
 
+// PANELS: both operands (and the packed output, if there is one) are in the K-panel layout of bnn.h -- panel p holds
+// words 8p .. 8p+7 of every row back to back -- so that a loader wave's 16-byte loads of one slab cover 1 KB of
+// contiguous memory (8 lines of 128 bytes) instead of 32 bytes in each of 32 lines.
+template <bool PANELS>
 __global__ __launch_bounds__(WIDE_THREADS, 1) void mfma_wide_kernel(const uint32_t* __restrict__ A, const uint32_t* __restrict__ B,
                                                                          Geom g, Epi e, int gx, int gy) {
     extern __shared__ uint4 lds[];                  // 2 * BUF_UNITS
@@ -78,15 +82,18 @@ __global__ __launch_bounds__(WIDE_THREADS, 1) void mfma_wide_kernel(const uint32
     // loader: thread -> row tid / 2 of A and of B, words 4 * (tid % 2) .. + 3 of every slab.  K-step v of a slab multiplies
     // word v of the lower half-wave's four words and word v of the upper one's: word v + 4 * half, in both operands.
     const int lrow = tid >> 1, lpart = tid & 1;
-    const uint32_t* ap = A + min(m_base + lrow, g.rows - 1) * (long long)g.lda_w + 4 * lpart;
-    const uint32_t* bp = B + (long long)min(n_base + lrow, g.cols - 1) * g.ldb_w + 4 * lpart;
-    const int kwords = g.tw;
+    const uint32_t* ap = A + min(m_base + lrow, g.rows - 1) * (long long)(PANELS ? 8 : g.lda_w) + 4 * lpart;
+    const uint32_t* bp = B + (long long)min(n_base + lrow, g.cols - 1) * (PANELS ? 8 : g.ldb_w) + 4 * lpart;
+    const int kwords = g.tw;                        // PANELS: a multiple of 8 (whole panels, pad bits 0)
     const int nslabs = (kwords + 7) / 8;
+    const long long a_slab = PANELS ? g.rows * 8 : 8, b_slab = PANELS ? (long long)g.cols * 8 : 8;   // words from slab to slab
 
     uint4 ga, gb;
-    auto slab_offset = [&](int s) { return s * 8 + 4 * lpart < kwords ? s * 8 : -4 * lpart; };
-    auto load_a = [&](int s) { ga = *reinterpret_cast<const uint4*>(ap + slab_offset(s)); };
-    auto load_b = [&](int s) { gb = *reinterpret_cast<const uint4*>(bp + slab_offset(s)); };
+    // a slab part past the end of K (row-major operands only) reads the start of the row instead: a valid address,
+    // and the store masks it
+    auto slab_offset = [&](int s, long long step) { return (PANELS || s * 8 + 4 * lpart < kwords) ? s * step : (long long)(-4 * lpart); };
+    auto load_a = [&](int s) { ga = *reinterpret_cast<const uint4*>(ap + slab_offset(s, a_slab)); };
+    auto load_b = [&](int s) { gb = *reinterpret_cast<const uint4*>(bp + slab_offset(s, b_slab)); };
     auto store_a = [&](int buf, int s, auto masked) {
         const uint32_t keep = (!decltype(masked)::value || s * 8 + 4 * lpart < kwords) ? 0xFFFFFFFFu : 0u;
         uint4* base = lds + buf * BUF_UNITS + (4 * lpart) * WS + lrow;
@@ -178,7 +185,17 @@ __global__ __launch_bounds__(WIDE_THREADS, 1) void mfma_wide_kernel(const uint32
 
     const long long m0 = m_base + (long long)wm * (MT * 32);
     const int n0 = n_base + wn * (NT * 32);
-    mfma::epilogue<MT, NT, false, false>(acc, m0, n0, lane, g, e, nslabs * 256 - g.bits_tap, 0);
+    const int corr_all = nslabs * 256 - g.bits_tap;
+    if constexpr (PANELS) {
+        if (e.bits != nullptr) {                    // uniform
+            int thi[NT];
+            bool cok[NT];
+            mfma::column_thresholds<NT>(thi, cok, n0, l32, g, e);
+            mfma::epilogue_bits<MT, NT, true>(acc, m0, n0, lane, g, e, corr_all, thi, cok);
+            return;
+        }
+    }
+    mfma::epilogue<MT, NT, false, false>(acc, m0, n0, lane, g, e, corr_all, 0);
 }
 
 
@@ -192,16 +209,31 @@ bool mfma_wide_takes(const Geom& g, const Epi& e) {
     return cdiv(g.rows, TILE) * cdiv(col_span, TILE) >= 240;
 }
 
-int launch_mfma_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+template <bool PANELS>
+static int launch_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
     const int col_span = (e.bits != nullptr) ? max(g.cols, e.ldbits_w * 32) : g.cols;
     const int gx = (int)cdiv(g.rows, TILE), gy = (int)cdiv(col_span, TILE);
     const unsigned nwg = (unsigned)(cdiv((long long)gx * gy, 8) * 8);
     constexpr size_t lds_bytes = (size_t)2 * BUF_UNITS * 16;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_wide_kernel),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_wide_kernel<PANELS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return BNN_ERR_DEVICE;
-    hipLaunchKernelGGL(mfma_wide_kernel, dim3(nwg), dim3(WIDE_THREADS), lds_bytes, s, A, B, g, e, gx, gy);
+    hipLaunchKernelGGL(mfma_wide_kernel<PANELS>, dim3(nwg), dim3(WIDE_THREADS), lds_bytes, s, A, B, g, e, gx, gy);
     return check_launch();
+}
+
+int launch_mfma_wide(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    return launch_wide<false>(A, B, g, e, s);
+}
+
+// Operands in K panels (g.tw a multiple of 8, lda_w / ldb_w unused); e.bits, if set, receives panels too
+// (e.ldbits_w = 8 * number of output panels).  Any shape; the tile is sized for large ones.
+int launch_mfma_wide_panels(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
+    if (g.conv || g.b_tiled || (g.tw & 7) || g.rows >= (1LL << 31)) return BNN_ERR_UNSUPPORTED;
+    if (e.bits != nullptr && (e.out != nullptr || e.out16 != nullptr || e.resid != nullptr || e.resid16 != nullptr ||
+                              e.resid_bits != nullptr || (e.ldbits_w & 7)))
+        return BNN_ERR_UNSUPPORTED;
+    return launch_wide<true>(A, B, g, e, s);
 }
 
 }  // namespace bnn

@@ -239,6 +239,31 @@ def test_bmm_pretiled_weights(bnn, orc, shape):
     assert np.array_equal(bits, orc.threshold_pack(ref, case["tau"], ldb_w=wl.round_up(wl.nwords(N), 4)))
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 1), (300, 70, 1234), (257, 513, 256), (256, 256, 8192), (1000, 1500, 700), (2304, 2100, 2048),
+                                   (4096, 4096, 4096), (40, 5000, 31)])
+def test_bmm_k_panel_layout(bnn, orc, shape):
+    # both operands in K panels, the packed output in panels too; conversions both ways against the layout's definition
+    M, N, K = shape
+    case = wl.bmm_case(97, M, N, K, index0=M % 83)
+    Ap, Bp = bnn.panels_from_rows(to_dev(case["A"]), K), bnn.panels_from_rows(to_dev(case["B"]), K)
+    assert np.array_equal(words(Ap), orc.panels(case["A"], K)) and np.array_equal(words(Bp), orc.panels(case["B"], K))
+    back = words(bnn.rows_from_panels(Ap, K, ldx_w=case["A"].shape[1] + 4))
+    assert np.array_equal(back[:, :case["A"].shape[1]], case["A"]) and not back[:, case["A"].shape[1]:].any()
+    ref = orc.bmm(case["A"], case["B"], K, tier=1)
+    assert np.array_equal(host(bnn.bmm_panels(Ap, Bp, K)), ref)
+    tau = case["tau"].copy()
+    edge = np.array([K, -K, K + 1, -K - 1, np.iinfo(np.int32).max, np.iinfo(np.int32).min], dtype=np.int64)
+    tau[: min(N, 6)] = edge[: min(N, 6)].astype(np.int32)          # thresholds at and beyond the range of a sum
+    bits_p = words(bnn.bmm_thr_panels(Ap, Bp, to_dev(tau), K))
+    ref_bits = orc.threshold_pack(ref, tau, ldb_w=wl.nwords(N))
+    assert np.array_equal(bits_p, orc.panels(ref_bits, N))
+    # the output is the next product's row operand as it stands
+    if M >= 256:
+        nxt = wl.bmm_case(98, 8, 40, N)
+        Wp = bnn.panels_from_rows(to_dev(nxt["B"]), N)
+        assert np.array_equal(host(bnn.bmm_panels(to_dev(bits_p), Wp, N)), orc.bmm(ref_bits, nxt["B"], N, tier=1))
+
+
 def test_probe_load_stride_runs(bnn):
     t = bnn.probe_load_stride(128, rows=256, iters=512)
     assert 1.0 < t < 1e5

@@ -220,3 +220,26 @@ def test_tile_b_layout_definition(orc):
                 assert (T[4 * d:4 * d + 4] == B[r, 4 * u:4 * u + 4]).all()
                 seen[4 * d:4 * d + 4] = True
         assert (T[~seen] == 0).all()
+
+
+def test_panels_layout_definition(orc):
+    # element-by-element against the index formula of the header, written with explicit loops; bits past K are dropped
+    rng = np.random.default_rng(12)
+    for (rows, K, ldw) in ((70, 256, 8), (3, 300, 12), (33, 1000, 32), (5, 31, 4)):
+        X = wl.random_bits(rng, rows, K, ldw)
+        dirty = X.copy()
+        if K % 32:
+            dirty[:, K // 32] |= np.uint32(0xFFFFFFFF) << np.uint32(K % 32)     # junk past K must not travel
+        dirty[:, wl.nwords(K):] = 0xDEADBEEF
+        for src in (X, dirty):
+            P = orc.panels(src, K)
+            npan = (K + 255) // 256
+            assert P.shape == (npan, rows, 8)
+            flat = P.reshape(-1)
+            seen = np.zeros(flat.size, bool)
+            for r in range(rows):
+                for w in range(wl.nwords(K)):
+                    d = ((w // 8) * rows + r) * 8 + w % 8
+                    assert flat[d] == X[r, w]
+                    seen[d] = True
+            assert (flat[~seen] == 0).all()
