@@ -31,7 +31,9 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
-TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.406e+08}
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.410e+08,
+                         # the same kernel on K-panel operands (profiles/bmm_sweep_k_panels_kernel_stats_and_counters.md)
+                         "mfma_fp4_bmm_xlds_wg256x256_kpanels": 5.420e+08}
 WIDE_KERNEL = "mfma_fp4_bmm_xlds_wg256x256"
 
 
@@ -264,7 +266,7 @@ def main() -> int:
             "note": "operands resident in HBM in the K-panel layout (bnn_panels_from_rows, done once and not timed, as "
                     "for weights and for activations produced by bnn_bmm_thr_panels); the other shapes row-major as above"}
     if not args.skip_extras:
-        extras = run_extras(bnn, wl, np, torch, to_dev, dev, None, rb, t5)
+        extras.update(run_extras(bnn, wl, np, torch, to_dev, dev, None, rb, t5))
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline(wl, np)
@@ -457,21 +459,29 @@ def run_extras(bnn, wl, np, torch, to_dev, dev, only=None, resnet_batches=(256, 
     # ---- layout study (Sec. 5.1 / 4.1 redone for this chip): weights pre-tiled in MFMA fragment order against plain
     if want("layout"):
         # rows on the shapes that read operands straight from L2, and the fragment-load latency against the row stride
+        # (GPU time per launch in a train behind a long-running kernel: the small shapes run shorter than a host launch)
         lay = {"fc_shapes": [], "fragment_load_ticks_vs_row_stride_bytes": {}}
+        train = _Train(bnn, torch, dev)
         for (M, N, K) in ((8, 4096, 4096), (128, 4096, 4096), (1024, 1024, 1024), (1024, 4096, 4096), (4096, 4096, 4096),
                           (8192, 8192, 8192)):
             case = wl.bmm_case(2, M, N, K, index0=900 + M % 7)
             A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
             Bt = bnn.tile_b(B, K)
+            Ap, Bp = bnn.panels_from_rows(A, K), bnn.panels_from_rows(B, K)
             o = torch.empty((M, wl.round_up(wl.nwords(N), 4)), dtype=torch.int32, device=dev)
-            t_rows = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o), 30)
-            t_tile = _time_gpu(torch, lambda: bnn.bmm_thr_tiled(A, Bt, tau, N, K, out=o), 30)
-            t_rows_direct = _time_gpu(torch, lambda: bnn.bmm_thr(A, B, tau, K, out=o, path=bnn.PATH_MFMA), 30)
+            op = torch.empty(((N + 255) // 256, M, 8), dtype=torch.int32, device=dev)
+            n = 100 if M * N <= (1 << 22) else 20
+            t_rows = train.time(lambda: bnn.bmm_thr(A, B, tau, K, out=o), n)
+            t_tile = train.time(lambda: bnn.bmm_thr_tiled(A, Bt, tau, N, K, out=o), n)
+            t_pan = train.time(lambda: bnn.bmm_thr_panels(Ap, Bp, tau, K, out=op), n)
             lay["fc_shapes"].append({"M": M, "N": N, "K": K, "rows_kernel": bnn.bmm_kernel_name(M, N, K),
                                      "rows_ms": round(t_rows, 5), "pretiled_direct_ms": round(t_tile, 5),
+                                     "k_panels_wg256x256_ms": round(t_pan, 5),
                                      "rows_tops": round(2.0 * M * N * K / t_rows / 1e9, 1),
-                                     "pretiled_tops": round(2.0 * M * N * K / t_tile / 1e9, 1)})
-            del A, B, Bt, o
+                                     "pretiled_tops": round(2.0 * M * N * K / t_tile / 1e9, 1),
+                                     "k_panels_tops": round(2.0 * M * N * K / t_pan / 1e9, 1)})
+            del A, B, Bt, Ap, Bp, o, op
+        del train
         for stride in (32, 48, 64, 96, 128, 256, 512, 1024, 2048, 2064, 4096):
             lay["fragment_load_ticks_vs_row_stride_bytes"][str(stride)] = {
                 "dependent": round(bnn.probe_load_stride(stride, iters=8192, dependent=True), 1),
