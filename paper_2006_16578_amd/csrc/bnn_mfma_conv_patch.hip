@@ -260,21 +260,24 @@ __global__ __launch_bounds__(64 * WAVES, 1) void conv_patch_kernel(const uint32_
     if (my_turns > 0) request(tile_of(0));
 
     // The filters: every packed word expanded once per workgroup, [tap][word][column] so that a fragment read is
-    // 32 consecutive units per half-wave.  A thread takes (column, tap) items: one 8- or 16-byte load each, all of
-    // them requested before the first is expanded (every workgroup of the launch reads these same few KB at the
-    // same moment; loads waited for one by one made this prologue longer than the tiles of a small layer).
+    // 32 consecutive units per half-wave.  A thread takes (tap, column) items, consecutive lanes consecutive columns:
+    // their 16-byte LDS writes then fall on consecutive units (with consecutive taps of one column per lane they were
+    // a whole plane apart, all eight lanes LDS serves together on the same banks: 4500 conflict cycles per compute
+    // unit, 2 us, for 128 -> 128 channels).  One 8- or 16-byte load per item, all of them requested before the first
+    // is expanded (every workgroup of the launch reads these same few KB at the same moment; loads waited for one by
+    // one made this prologue longer than the tiles of a small layer).
     {
         constexpr int ITEMS = 9 * COLSP, PER = (ITEMS + 64 * WAVES - 1) / (64 * WAVES);
         uint32_t fw[PER][CW];
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
-            const int item = tid + it * 64 * WAVES, col = item / 9, tap = item - 9 * col;
+            const int item = tid + it * 64 * WAVES, tap = item / COLSP, col = item - COLSP * tap;
             const bool ok = item < ITEMS && col < g.cols;
             mfma::load_words<CW>(B + (ok ? (long long)col * g.ldb_w + tap * CW : 0), fw[it]);
         }
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
-            const int item = tid + it * 64 * WAVES, col = item / 9, tap = item - 9 * col;
+            const int item = tid + it * 64 * WAVES, tap = item / COLSP, col = item - COLSP * tap;
             if (item < ITEMS) {
                 const uint32_t keep = col < g.cols ? 0xFFFFFFFFu : 0u;      // columns past the last: 0 bits
 #pragma unroll
