@@ -1,4 +1,6 @@
 """GPU parity: bnn_bmm / bnn_bmm_thr through the C ABI against the CPU oracle, bit-exact."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -262,6 +264,23 @@ def test_bmm_k_panel_layout(bnn, orc, shape):
         nxt = wl.bmm_case(98, 8, 40, N)
         Wp = bnn.panels_from_rows(to_dev(nxt["B"]), N)
         assert np.array_equal(host(bnn.bmm_panels(to_dev(bits_p), Wp, N)), orc.bmm(ref_bits, nxt["B"], N, tier=1))
+
+
+def test_k_panel_argument_errors(bnn):
+    import torch
+    X = torch.zeros((4, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(bnn.BnnError) as err:
+        bnn.panels_from_rows(X, 300)                       # 300 bits do not fit rows of 8 words
+    assert err.value.status == -1
+    lib = bnn.load()
+    P = torch.zeros((2, 4, 8), dtype=torch.int32, device="cuda")
+    C = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert lib.bnn_bmm_panels(ptr(P), ptr(P), None, 4, 4, 300, 4, None) == -1            # no output
+    assert lib.bnn_bmm_panels(ptr(P), ptr(P), ptr(C), 4, 4, 300, 3, None) == -1          # ldc < N
+    assert lib.bnn_bmm_panels(ctypes.c_void_p(P.data_ptr() + 4), ptr(P), ptr(C), 4, 4, 300, 4, None) == -2   # alignment
+    assert lib.bnn_bmm_thr_panels(ptr(P), ptr(P), None, ptr(C), 4, 4, 300, None) == -1   # thresholds missing
+    assert lib.bnn_bmm_panels(ptr(P), ptr(P), ptr(C), 4, 4, (1 << 20) + 1, 4, None) == -3   # K beyond the supported range
 
 
 def test_probe_load_stride_runs(bnn):
