@@ -478,16 +478,19 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const uint32_t* __restri
 }
 
 // FC on the pooled sums with the fp32 matrix instruction (exact fp32 products, fp32 accumulation): a workgroup
-// computes 32 images x 32 outputs, its four waves taking every fourth step of 8 channels; lane l holds image /
-// output l % 32 and channels 4 * (l / 32) .. + 3 of the step, one MFMA per channel pair.  The four partial tiles meet
+// computes 32 images x 32 outputs, its eight waves taking every eighth step of 8 channels; lane l holds image /
+// output l % 32 and channels 4 * (l / 32) .. + 3 of the step, one MFMA per channel pair.  The eight partial tiles meet
 // in LDS; the division by HW is applied once, to the finished sum.  VEC: C is a multiple of 4 (16-byte loads).
+// (Eight waves: at 512 channels every wave has all of its loads in flight at once -- one memory round trip; a lane's
+// loads go to 32 different rows, so what a wave can have in flight is what bounds this kernel.)
 typedef float fc_v16f __attribute__((ext_vector_type(16)));
 constexpr int FC_STEPS = 8;                     // steps (of 8 channels) a wave requests before it multiplies them
+constexpr int FC_WAVES = 8;
 
 template <bool VEC>
-__global__ __launch_bounds__(256) void head_fc_kernel(const int32_t* __restrict__ pooled, const float* __restrict__ w,
-                                                      float* __restrict__ y, int N, int HW, int C, int J) {
-    __shared__ float red[4][16 * 64];
+__global__ __launch_bounds__(64 * FC_WAVES) void head_fc_kernel(const int32_t* __restrict__ pooled, const float* __restrict__ w,
+                                                                float* __restrict__ y, int N, int HW, int C, int J) {
+    __shared__ float red[FC_WAVES][16 * 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int n0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
@@ -498,11 +501,11 @@ __global__ __launch_bounds__(256) void head_fc_kernel(const int32_t* __restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const int steps = (C + 7) / 8;
-    for (int s0 = wave; s0 < steps; s0 += 4 * FC_STEPS) {
+    for (int s0 = wave; s0 < steps; s0 += FC_WAVES * FC_STEPS) {
         float a[FC_STEPS][4], b[FC_STEPS][4];
 #pragma unroll
         for (int u = 0; u < FC_STEPS; ++u) {
-            const int c = 8 * (s0 + 4 * u) + 4 * half;
+            const int c = 8 * (s0 + FC_WAVES * u) + 4 * half;
             if (VEC) {
                 const bool ok = c < C;                      // C % 4 == 0: the four channels are in range together
                 const int4 pa = (ok && nok) ? *reinterpret_cast<const int4*>(prow + c) : make_int4(0, 0, 0, 0);
@@ -525,13 +528,16 @@ __global__ __launch_bounds__(256) void head_fc_kernel(const int32_t* __restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][r * 64 + lane] = acc[r];
     __syncthreads();
-    // thread (wave, lane) finishes accumulator registers 4 * wave .. + 3 of lane: rows 8 * wave + 4 * half + q
+    // thread (wave, lane) finishes accumulator registers 2 * wave, 2 * wave + 1 of lane (register r: row 8 * (r / 4) +
+    // 4 * half + r % 4)
     const float inv = (float)HW;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = 4 * wave + q;
-        const float sum = (red[0][r * 64 + lane] + red[1][r * 64 + lane]) + (red[2][r * 64 + lane] + red[3][r * 64 + lane]);
-        const int row = n0 + 8 * wave + 4 * half + q, col = j0 + l32;
+    for (int q = 0; q < 16 / FC_WAVES; ++q) {
+        const int r = (16 / FC_WAVES) * wave + q;
+        float sum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < FC_WAVES; ++wv) sum += red[wv][r * 64 + lane];
+        const int row = n0 + 8 * (r >> 2) + 4 * half + (r & 3), col = j0 + l32;
         if (row < N && col < J) y[(long long)row * J + col] = sum / inv;
     }
 }
@@ -632,8 +638,8 @@ int launch_head_f32(const uint32_t* bits, const float* w, float* y, int32_t* poo
         hipLaunchKernelGGL(head_pool_kernel, dim3((unsigned)cdiv(lanes, 256)), dim3(256), 0, s, bits, pooled, N, HW, C);
         const dim3 grid((unsigned)cdiv(N, 32), (unsigned)cdiv(J, 32));
         const bool vec = C % 4 == 0 && ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(pooled)) & 15u) == 0;
-        if (vec) hipLaunchKernelGGL(head_fc_kernel<true>, grid, dim3(256), 0, s, pooled, w, y, N, HW, C, J);
-        else hipLaunchKernelGGL(head_fc_kernel<false>, grid, dim3(256), 0, s, pooled, w, y, N, HW, C, J);
+        if (vec) hipLaunchKernelGGL(head_fc_kernel<true>, grid, dim3(64 * FC_WAVES), 0, s, pooled, w, y, N, HW, C, J);
+        else hipLaunchKernelGGL(head_fc_kernel<false>, grid, dim3(64 * FC_WAVES), 0, s, pooled, w, y, N, HW, C, J);
         return check_launch();
     }
     const size_t lds_bytes = (size_t)2 * C * HEAD_LD * sizeof(float);
