@@ -31,9 +31,9 @@ PAPER_RESNET18_IMG_S = 5.6e3       # the paper's ResNet-18 throughput on an RTX 
 # WRITE_SIZE scaled by a plain copy (profiles/bmm_sweep_dominant_kernel_hbm_traffic.md); bench.py cannot
 # read hardware counters itself, so the measured figure is carried here and reported only for that kernel
 # in the default configuration.
-TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.407e+08,
+TRAFFIC_DEFAULT_SWEEP = {"mfma_fp4_bmm_xlds_wg256x256": 5.409e+08,
                          # the same kernel on K-panel operands (profiles/bmm_sweep_k_panels_kernel_stats_and_counters.md)
-                         "mfma_fp4_bmm_xlds_wg256x256_kpanels": 5.414e+08}
+                         "mfma_fp4_bmm_xlds_wg256x256_kpanels": 5.411e+08}
 WIDE_KERNEL = "mfma_fp4_bmm_xlds_wg256x256"
 
 

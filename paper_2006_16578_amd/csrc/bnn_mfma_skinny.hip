@@ -3,10 +3,10 @@
 // Such a product is bound by streaming the weights: M = 8, K = N = 4096 is 2 MB of B for 0.13 G bit-products.
 // The tiled kernels give it one workgroup per 64 x 64 outputs, each walking all of K serially -- 64 workgroups on
 // 256 compute units, a handful of loads in flight each.  Here a workgroup owns 32 output columns and ALL rows, and
-// its four waves split K between them (the occupancy argument of Sec. 5.2, Design-1, turned around: with few rows
+// its waves (eight for up to 32 rows, else four) split K between them (the occupancy argument of Sec. 5.2, Design-1, turned around: with few rows
 // the parallelism has to come from K and N).  Every wave requests all of its share of B and A up front (four
 // 256-bit chunks in flight per lane), multiplies, and leaves its partial 32 x 32 sums in LDS; after one barrier
-// wave i adds the four partials of row tile i and runs the ordinary epilogue (threshold -> packed bits, or int32).
+// wave i adds the partials of row tile i and runs the ordinary epilogue (threshold -> packed bits, or int32).
 // N / 32 workgroups, each with its whole 16 KB of weights in flight at once.
 #include "bnn_mfma_kernel.h"
 
@@ -16,10 +16,10 @@ namespace {
 using mfma::v16f;
 using mfma::v8i;
 
-constexpr int WAVES = 4;
 constexpr int DEPTH = 4;      // chunks (256 bits of K per row) a wave keeps in flight
 
-template <int MT>
+// WAVES: 8 for a single row tile (the partial sums of 8 waves are 32 KB of LDS), 4 otherwise
+template <int MT, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void mfma_skinny_kernel(const uint32_t* __restrict__ A, const uint32_t* __restrict__ B,
                                                                  Geom g, Epi e) {
     __shared__ float part[WAVES][MT][16][64];
@@ -113,9 +113,9 @@ const char* describe_mfma_skinny(const Geom& g) {
 int launch_mfma_skinny(const uint32_t* A, const uint32_t* B, const Geom& g, const Epi& e, hipStream_t s) {
     const int col_span = (e.bits != nullptr) ? max(g.cols, e.ldbits_w * 32) : g.cols;
     const dim3 grid((unsigned)cdiv(col_span, 32));
-    if (g.rows <= 32) hipLaunchKernelGGL(mfma_skinny_kernel<1>, grid, dim3(64 * WAVES), 0, s, A, B, g, e);
-    else if (g.rows <= 64) hipLaunchKernelGGL(mfma_skinny_kernel<2>, grid, dim3(64 * WAVES), 0, s, A, B, g, e);
-    else hipLaunchKernelGGL(mfma_skinny_kernel<4>, grid, dim3(64 * WAVES), 0, s, A, B, g, e);
+    if (g.rows <= 32) hipLaunchKernelGGL((mfma_skinny_kernel<1, 8>), grid, dim3(64 * 8), 0, s, A, B, g, e);
+    else if (g.rows <= 64) hipLaunchKernelGGL((mfma_skinny_kernel<2, 4>), grid, dim3(64 * 4), 0, s, A, B, g, e);
+    else hipLaunchKernelGGL((mfma_skinny_kernel<4, 4>), grid, dim3(64 * 4), 0, s, A, B, g, e);
     return check_launch();
 }
 
