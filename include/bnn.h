@@ -151,7 +151,7 @@ int bnn_bmm_thr_tiled(const uint32_t* A, const uint32_t* B_tiled, const int32_t*
  * ((w / 8) * rows + r) * 8 + w % 8.  A matrix of `rows` rows and K bits takes ceil(K / 256) * rows * 8 words; the bits
  * past K in the last panel are 0.  A 16-byte load per lane then covers whole 128-byte lines (a slab of 256 bits of
  * 32 rows is 1 KB of contiguous memory), where the row-major layout gives a load instruction 32 bytes in each of 32
- * lines; the large-product kernel runs 5 % faster on it.
+ * lines; the large-product kernel runs 6 % faster on it.
  *   bnn_panels_from_rows: X [rows][ldx_w] -> Xp (ldx_w >= ceil(K/32); bits past K in X are ignored).
  *   bnn_rows_from_panels: Xp -> X [rows][ldx_w] (ldx_w >= ceil(K/32), ldx_w % 4 == 0; words past the panels are zeroed).
  *   bnn_bmm_panels:      C [M][ldc] int32 = A x B^T as bnn_bmm (Eq. 2), A and B given in panels (M resp. N rows).
