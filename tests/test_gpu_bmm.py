@@ -127,6 +127,26 @@ def test_sweep_large_auto_path(bnn, orc, n):
             r0, r0 + step, int((got != ref1[r0:r0 + step]).sum()))
 
 
+@pytest.mark.parametrize("n", [8192, 16384])
+def test_sweep_large_k_panels(bnn, orc, n):
+    # the same two sizes with both operands in K panels, as `bench.py --layout panels` runs them: the packed output (in
+    # panels) and the whole int32 matrix against the tier-1 oracle (which the test above checks against tier 0)
+    case = wl.cfg2_case("sq%d" % n)
+    A, B, tau = to_dev(case["A"]), to_dev(case["B"]), to_dev(case["tau"])
+    Ap, Bp = bnn.panels_from_rows(A, n), bnn.panels_from_rows(B, n)
+    del A, B
+    bits_p = words(bnn.bmm_thr_panels(Ap, Bp, tau, n))
+    C = bnn.bmm_panels(Ap, Bp, n)
+    torch.cuda.synchronize()
+    ref1 = orc.bmm(case["A"], case["B"], n, tier=1)
+    assert np.array_equal(bits_p, orc.panels(orc.threshold_pack(ref1, case["tau"], ldb_w=n // 32), n))
+    step = 2048
+    for r0 in range(0, n, step):
+        got = host(C[r0:r0 + step])
+        assert np.array_equal(got, ref1[r0:r0 + step]), "int32 rows %d..%d: %d wrong" % (
+            r0, r0 + step, int((got != ref1[r0:r0 + step]).sum()))
+
+
 @pytest.mark.parametrize("pname,path", [("auto", 0)] + PATHS)
 def test_threshold_edge_values(bnn, orc, pname, path):
     # thresholds at and beyond the range of the sums, and at the ends of int32: columns whose B row equals or
