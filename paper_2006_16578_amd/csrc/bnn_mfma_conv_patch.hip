@@ -488,10 +488,11 @@ PatchPlan plan_patch(const Geom& g, const Epi& e) {
     pl.lds_bytes = ((size_t)9 * pl.cw * pl.nt * 32 + (size_t)pl.waves * 2 * 64 * pp) * 16 + (size_t)8 * (pl.nt * 2 * 16 + 4) * 4;
     if (pl.lds_bytes > 160 * 1024) return pl;
     const long long ntiles = cdiv(g.rows, 64);
-    // Measured against the direct kernels on 56x56x64->64 and 28x28 / 56x56x128->128 layers over batch sizes: the
-    // 64-column form wins from about 400 tiles, the 128-column form (a wave's tile is 144 or more MFMAs long, and
-    // one tile per wave is then mostly latency) from about 3000.
-    if (ntiles < (S == 2 ? 1024 : pl.nt == 2 ? 512 : 2560)) return pl;
+    // Measured against the direct kernels on 56x56x64->64, 28x28 / 64x64x128->128 and 56x56x64->128 (stride 2) layers
+    // over batch sizes (GPU time per call, microseconds, patch / direct): 64 columns 3.9 / 3.6 at 196 tiles, 3.9 / 4.5 at
+    // 392, 4.0 / 5.9 at 784; 128 columns 6.8 / 7.5 at 784, 7.7 / 7.6 at 1024, 9.3 / 11.2 at 1568; stride 2 5.3 / 4.6 at
+    // 196, 5.5 / 6.2 at 392, 5.7 / 7.6 at 784.
+    if (ntiles < (pl.nt == 2 || S == 2 ? 384 : 768)) return pl;
     pl.pa.wp1 = g.W + 1; pl.pa.hp1 = g.H + 1;
     // the small divisions of the kernel (x / d with one 24-bit multiply) are exact for x * d <= 2^20
     const long long lim = 1LL << 20;

@@ -197,7 +197,7 @@ def test_random_shapes_all_paths(bnn, orc, seed):
 # shapes large enough for each of the bigger workgroup tiles of the direct kernel (512x64, 256x128, 128x128), with
 # ragged last tiles, odd channel counts, strides and paddings; residual in and sum out as well
 LARGER = [(150, 61, 59, 64, 64, 3, 2, 1, "mfma_fp4_conv_wg512x64"), (41, 60, 58, 96, 40, 3, 1, 0, "mfma_fp4_conv_wg512x64"),
-          (29, 61, 60, 128, 128, 3, 1, 1, "mfma_fp4_conv_wg256x128"), (50, 90, 88, 160, 130, 3, 2, 2, "mfma_fp4_conv_wg256x128"),
+          (29, 61, 60, 128, 160, 3, 1, 1, "mfma_fp4_conv_wg256x128"), (50, 90, 88, 160, 130, 3, 2, 2, "mfma_fp4_conv_wg256x128"),
           (13, 59, 57, 256, 100, 3, 1, 1, "mfma_fp4_conv_wg128x128"), (11, 63, 61, 33, 128, 2, 1, 1, "mfma_fp4_conv_wg128x128")]
 
 
